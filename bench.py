@@ -1,0 +1,143 @@
+#!/usr/bin/env python3
+"""Benchmark of the mixed-precision encoder on one MI355X.
+
+Workload: BERT-base 12-layer encoder, batch 32 x 128 tokens, all sequences full length (synthetic
+N(0,0.02) weights, N(0,1) inputs, min-max calibration on a seeded 8x128 batch run on the GPU).
+A step is one forward of the whole encoder.  The headline `value` is sequences/s of the full-INT8
+stack; the other precision modes are timed the same way and reported under "modes".
+
+Extra objects on the JSON line:
+  roofline     - the FFN1 INT8 GEMM (+bias+GELU+quantise) kernel: algorithmic ops per launch
+                 (2 * tokens * ffn * hidden) over its mean launch duration, measured with HIP events
+                 attached to the dispatches inside the timed region, against the int8 MFMA dense peak.
+  cpu_baseline - the CPU oracle (as it stands, OpenMP over sequences) on the same batch.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+INT8_PEAK_TOPS = 5000.0        # MI355X dense int8 MFMA, published: 5.0 POP/s
+FP16_PEAK_TFLOPS = 2500.0      # dense fp16
+HBM_PEAK_GBS = 8000.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="C2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only-mode", default=None, help="time a single precision mode (FULL_INT8, FP16, ...)")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU only (sequences are independent; see DESIGN.md for how the "
+              "path shards). Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2209_09130_amd as P
+    import samp_workloads as W
+
+    if not os.path.exists(P.lib_path()):
+        from paper_2209_09130_amd import build as hip_build
+        hip_build.build(force=True)
+    P.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    w0 = W.config(a.workload)
+    cfg = (w0.layers, w0.hidden, w0.heads, w0.ffn, w0.ln_eps)
+    wts = W.make_weights(w0)
+    hid_np, lens, mask_np = W.make_hidden(w0)
+    hid = torch.from_numpy(hid_np).cuda()
+    mask = torch.from_numpy(mask_np).cuda() if w0.varlen else None
+    T = int(lens.sum())
+
+    # calibration on the GPU: all-FP16 encoder, absmax taps (product path, no oracle involved)
+    cal = torch.from_numpy(W.make_calibration_batch(w0)).cuda()
+    enc16 = P.Encoder(*cfg, (P.FP16,) * w0.layers, wts, None, max_batch=max(w0.batch, cal.shape[0]),
+                      max_seq=max(w0.seq, cal.shape[1]))
+    scales = enc16.calibrate(cal)
+
+    mode_list = [("FULL_INT8", P.FULL_INT8), ("FFN_INT8", P.FFN_INT8), ("MHA_INT8", P.MHA_INT8), ("FP16", P.FP16)]
+    if a.workload != "C2":
+        mode_list = [("CONFIG", None)]
+    if a.only_mode:
+        mode_list = [m for m in mode_list if m[0] == a.only_mode]
+
+    results = {}
+    roof = None
+    for name, mode in mode_list:
+        modes = w0.modes if mode is None else (mode,) * w0.layers
+        enc = enc16 if (mode == P.FP16) else P.Encoder(*cfg, modes, wts, scales, max_batch=w0.batch, max_seq=w0.seq)
+        out = torch.empty_like(hid)
+        for _ in range(a.warmup):
+            enc.forward(hid, mask, out)
+        headline = (name in ("FULL_INT8", "CONFIG"))
+        if headline:
+            enc.profile(P.PROF_FFN1)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(a.steps):
+            enc.forward(hid, mask, out)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        ms = dt / a.steps * 1e3
+        results[name] = {"ms_per_step": ms, "seq_per_s": w0.batch / (ms * 1e-3)}
+        if headline:
+            kms, launches = enc.profile_read()
+            enc.profile(P.PROF_OFF)
+            ffn_int8 = bool(modes[0] & 2)
+            ops = 2.0 * T * w0.ffn * w0.hidden
+            achieved = ops / (kms * 1e-3) / 1e12 if kms > 0 else 0.0
+            peak = INT8_PEAK_TOPS if ffn_int8 else FP16_PEAK_TFLOPS
+            roof = {"kernel": "gemm_nt_kernel<I8,EpiGeluQuant> (FFN1 GEMM + bias + GELU + quantise)" if ffn_int8
+                    else "gemm_nt_kernel<F16,EpiF16> (FFN1)",
+                    "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TOP/s" if ffn_int8 else "TFLOP/s",
+                    "frac": achieved / peak, "traffic": None, "launches_timed": launches,
+                    "mean_launch_us": kms * 1e3, "ops_per_launch": ops}
+        if enc is not enc16:
+            enc.close()
+    enc16.close()
+
+    head = "FULL_INT8" if "FULL_INT8" in results else next(iter(results))
+    line = {
+        "metric": "sequences/sec BERT-base encoder b32xs128 per precision mode; % int8/fp16 MFMA peak",
+        "value": results[head]["seq_per_s"], "unit": "sequences/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": results[head]["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8" if head != "FP16" else "f16", "data": "synthetic",
+        "config": {"workload": f"{a.workload}: {w0.layers}-layer H{w0.hidden} F{w0.ffn} encoder, batch {w0.batch} x "
+                               f"seq {w0.seq}, mode {head}", "tokens": T, "headline_mode": head},
+        "modes": results,
+    }
+    if roof:
+        line["roofline"] = roof
+
+    if not a.no_cpu_baseline:
+        import oracle
+        n_seq = min(w0.batch, 32)
+        modes = w0.modes if head == "CONFIG" else (P.FULL_INT8,) * w0.layers
+        oenc = oracle.Encoder(*cfg, modes, wts, scales)
+        t0 = time.perf_counter()
+        oenc.forward(hid_np[:n_seq], lens[:n_seq])
+        dt = time.perf_counter() - t0
+        oenc.close()
+        line["cpu_baseline"] = {"value": n_seq / dt, "unit": "sequences/s", "cores": oracle.max_threads(), "kind": "oracle",
+                                "sample": f"{n_seq} of {w0.batch} sequences of the same batch, mode {head}, one pass, "
+                                          f"{dt:.1f} s wall"}
+    print(json.dumps(line), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

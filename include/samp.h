@@ -1,0 +1,193 @@
+/*
+ * samp.h - C ABI of the MI355X (gfx950) self-adaptive mixed-precision encoder.
+ *
+ * The library runs the encoder hot path of SAMP (arXiv 2209.09130, Section 3.2):
+ * a stack of BERT-style post-LayerNorm Transformer layers in which, per layer,
+ * the attention block (MHA: QKV GEMM, softmax attention, attention-output GEMM)
+ * and the feed-forward block (FFN: FFN1 GEMM + GELU, FFN2 GEMM) each run either
+ * in FP16 or with post-training-quantised INT8 GEMMs.  "Fully-Quant" is both
+ * blocks INT8, "Quant-FFN-Only" is INT8 FFN with FP16 MHA (Section 3.2); the
+ * per-layer choice of either block is the mixed-precision configuration of
+ * Section 3.2 / Table 1.  Inside a quantised block every tensor between kernels
+ * is int8; dequantise + bias + residual + LayerNorm + quantise are one kernel;
+ * the softmax output is quantised (Section 4.2, Appendix B); the last kernel of
+ * a layer emits floating point when its consumer is not quantised.
+ *
+ * Conventions
+ *   - All `dev` pointers are device memory of the current HIP device, owned by
+ *     the caller, 16-byte aligned unless a stricter alignment is stated.  `host`
+ *     pointers are ordinary host memory.  The library never allocates or frees
+ *     device memory; it owns only the host-side encoder handle.
+ *   - fp16 = IEEE binary16 stored as uint16_t; matrices are row-major; weight
+ *     matrices are [out, in] (K contiguous).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Entry points that launch kernels are asynchronous on that stream and do
+ *     not synchronise, except samp_encoder_create and samp_encoder_calibrate,
+ *     which return after their work is complete.
+ *   - Every function returning int returns SAMP_OK (0) or a negative samp_status;
+ *     samp_last_error() then describes the failure.  No exception or abort
+ *     crosses this boundary.  Arguments are checked on the host before any
+ *     kernel is launched.
+ *   - Quantiser (Appendix B: multiply by a scale, round, symmetric 8-bit range):
+ *     code = clamp(round_half_even(x * (1/s)), -127, 127), where the step s is
+ *     absmax/127 from a min-max calibration (Table 2 caption) and 1/s is formed
+ *     once in binary32.  Weights use one step per output channel.
+ */
+#ifndef SAMP_H
+#define SAMP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SAMP_API __attribute__((visibility("default")))
+
+typedef struct samp_encoder samp_encoder_t;
+
+/* per-layer precision: bit 0 = MHA block INT8, bit 1 = FFN block INT8 (Section 3.2, Table 1) */
+enum { SAMP_FP16 = 0, SAMP_MHA_INT8 = 1, SAMP_FFN_INT8 = 2, SAMP_FULL_INT8 = 3 };
+
+enum {
+    SAMP_OK = 0,
+    SAMP_ERR_ARG = -1,    /* null pointer, negative size, unknown mode, wrong encoder kind        */
+    SAMP_ERR_SHAPE = -2,  /* shape outside the supported set or above max_batch / max_seq         */
+    SAMP_ERR_SPACE = -3,  /* arena / workspace too small or misaligned (256 bytes)                */
+    SAMP_ERR_HIP = -4,    /* a HIP call failed                                                    */
+    SAMP_ERR_SCALE = -5   /* a scale needed by an INT8 block is not finite or not positive        */
+};
+
+/* Supported shapes: head size hidden/heads == 64; hidden % 128 == 0; ffn % 128 == 0;
+ * hidden <= 2048; 1 <= max_seq <= 512; max_batch >= 1.                                           */
+typedef struct {
+    int32_t layers, hidden, heads, ffn, max_batch, max_seq;
+    float ln_eps;
+} samp_config_t;
+
+/* One layer's parameters, HOST pointers, copied during samp_encoder_create.
+ * w_qkv [3H,H]: rows 0..H-1 = Q, H..2H-1 = K, 2H..3H-1 = V; head h owns 64 consecutive rows of each.
+ * w_o [H,H], w_ffn1 [F,H], w_ffn2 [H,F]; biases and LayerNorm vectors are binary32.               */
+typedef struct {
+    const uint16_t *w_qkv, *w_o, *w_ffn1, *w_ffn2;
+    const float *b_qkv, *b_o, *b_ffn1, *b_ffn2, *ln1_g, *ln1_b, *ln2_g, *ln2_b;
+} samp_layer_weights_t;
+
+/* Per-tensor activation steps (absmax/127) of one layer, fixed after calibration (Appendix B):
+ * x = layer input, q k v = projections incl. bias, p = softmax output, ctx = P.V,
+ * attn_out = attention-output GEMM before its bias, ffn_in = first LayerNorm's output,
+ * ffn_mid = GELU output, ffn_out = FFN2 GEMM before its bias.  Only the steps of INT8 blocks are
+ * read: x..attn_out if the MHA block is INT8 (x also when this layer's input must be quantised by
+ * its producer), ffn_in..ffn_out if the FFN block is INT8.                                        */
+typedef struct {
+    float x, q, k, v, p, ctx, attn_out, ffn_in, ffn_mid, ffn_out;
+} samp_layer_scales_t;
+
+/* ---- encoder ---------------------------------------------------------------------------------- */
+
+/* Bytes of device memory samp_encoder_create needs for the packed weights of this configuration
+ * (includes a staging area used only during create).  0 on invalid arguments.                     */
+SAMP_API size_t samp_encoder_arena_bytes(const samp_config_t *cfg, const uint8_t *modes /* host [layers] */);
+
+/* Builds an encoder.  Weights of INT8 blocks are quantised on the device per output channel
+ * (s_w = absmax/127, code = rne(w / s_w)); epilogue multipliers are folded in binary64 and rounded
+ * once to binary32.  `scales` (host [layers]) may be NULL only if every mode is SAMP_FP16.
+ * `dev_arena` (dev, 256-byte aligned, >= samp_encoder_arena_bytes) must outlive the encoder; the
+ * host arrays may be released when the call returns.  Synchronises `stream` before returning.     */
+SAMP_API int samp_encoder_create(const samp_config_t *cfg, const uint8_t *modes,
+                                 const samp_layer_weights_t *weights /* host [layers] */,
+                                 const samp_layer_scales_t *scales /* host [layers] or NULL */,
+                                 void *dev_arena, size_t arena_bytes, void *stream, samp_encoder_t **out);
+
+/* Workspace bytes a forward of batch B and padded length S needs.  0 on invalid arguments.        */
+SAMP_API size_t samp_encoder_workspace_bytes(const samp_encoder_t *enc, int32_t B, int32_t S);
+
+/* One forward pass (Section 3.2).  hidden: dev fp16 [B,S,H].  mask: dev int32 [B,S], 1 = token,
+ * right-padded (a sequence's tokens form a prefix, at least one token), or NULL = every sequence
+ * has S tokens.  With a mask, padding is removed on entry (only valid tokens are computed) and
+ * restored on exit: padded rows of `out` are written as zeros and never influence valid rows.
+ * out: dev fp16 [B,S,H], must not alias hidden.  workspace: dev, 256-byte aligned,
+ * >= samp_encoder_workspace_bytes(enc,B,S); calls sharing a workspace must be stream-ordered.     */
+SAMP_API int samp_encoder_forward(samp_encoder_t *enc, const void *hidden, const int32_t *mask, int32_t B, int32_t S,
+                                  void *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Min-max calibration (Table 2 caption; Appendix B): runs the all-FP16 encoder `enc` (every mode
+ * must be SAMP_FP16) on a calibration batch and returns, per layer, absmax/127 of the ten tensors
+ * of samp_layer_scales_t.  Same argument rules as samp_encoder_forward; no output tensor.
+ * scales_out: host [layers].  Synchronises `stream` before returning.                             */
+SAMP_API int samp_encoder_calibrate(samp_encoder_t *enc, const void *hidden, const int32_t *mask, int32_t B, int32_t S,
+                                    void *workspace, size_t workspace_bytes, void *stream,
+                                    samp_layer_scales_t *scales_out);
+
+/* Releases the host handle (device memory stays with the caller).  NULL is accepted.              */
+SAMP_API int samp_encoder_destroy(samp_encoder_t *enc);
+
+/* Kernel timing for benchmarks.  which = one of SAMP_PROF_*; the chosen kernel's launches inside
+ * subsequent forwards get start/stop events attached to the dispatch itself.  SAMP_PROF_OFF stops.
+ * samp_encoder_profile_read synchronises the events recorded so far, returns their mean duration
+ * in milliseconds and their number, and clears them.                                             */
+enum { SAMP_PROF_OFF = 0, SAMP_PROF_QKV = 1, SAMP_PROF_ATTN = 2, SAMP_PROF_ATTN_OUT = 3, SAMP_PROF_LN1 = 4,
+       SAMP_PROF_FFN1 = 5, SAMP_PROF_FFN2 = 6, SAMP_PROF_LN2 = 7, SAMP_PROF_ENTRY = 8 };
+SAMP_API int samp_encoder_profile(samp_encoder_t *enc, int which);
+SAMP_API int samp_encoder_profile_read(samp_encoder_t *enc, double *mean_ms, int64_t *launches);
+
+/* Thread-local description of the last failure on this thread ("" if none).                       */
+SAMP_API const char *samp_last_error(void);
+
+/* ---- single steps of the path (what the encoder is made of; used by the parity tests) --------- */
+
+/* INT8 GEMM with int32 accumulation (Section 3.2): C[M,N] = A[M,K] . W[N,K]^T, exact.
+ * A, W dev int8, C dev int32.  N % 128 == 0, K % 64 == 0, M >= 1.                                 */
+SAMP_API int samp_gemm_i8_i32(const int8_t *A, const int8_t *W, int32_t *C, int32_t M, int32_t N, int32_t K, void *stream);
+
+/* INT8 GEMM + requantising epilogue: out = clamp(rne(fmaf(float(acc), m[n], b[n]))) as int8.
+ * m, b dev float [N]; b may be NULL (zero).  Used for QKV (bias folded), attention-output, FFN2.  */
+SAMP_API int samp_gemm_i8_requant(const int8_t *A, const int8_t *W, const float *m, const float *b, int8_t *out,
+                                  int32_t M, int32_t N, int32_t K, void *stream);
+
+/* INT8 GEMM + dequantise + bias + GELU + quantise (FFN1): y = fmaf(float(acc), m[n], bias[n]);
+ * g = 0.5 y (1 + erf(y / sqrt 2)); out = clamp(rne(g * (1/s_out))).                               */
+SAMP_API int samp_gemm_i8_gelu_quant(const int8_t *A, const int8_t *W, const float *m, const float *bias, float s_out,
+                                     int8_t *out, int32_t M, int32_t N, int32_t K, void *stream);
+
+/* FP16 GEMM, binary32 accumulation: out = fp16(act(A . W^T + bias)); bias dev float [N] or NULL;
+ * gelu != 0 applies GELU.  N % 128 == 0, K % 32 == 0.                                             */
+SAMP_API int samp_gemm_f16(const uint16_t *A, const uint16_t *W, const float *bias, int32_t gelu, uint16_t *out,
+                           int32_t M, int32_t N, int32_t K, void *stream);
+
+/* Softmax attention over packed rows.  qkv: dev [T,3H] (int8 or fp16), columns [0,H) Q, [H,2H) K,
+ * [2H,3H) V.  cu_seqlens: dev int32 [B+1], sequence b owns rows cu[b]..cu[b+1); max_len >= every
+ * length, <= 512.  INT8 flavour (Section 4.2 / Appendix B: quantised softmax output):
+ * score = float(q.k) * (s_q s_k / 8); P = softmax; Pq = rne(P / s_p); ctx = rne(float(Pq.V) * s_p s_v / s_ctx). */
+SAMP_API int samp_attention_i8(const int8_t *qkv, const int32_t *cu_seqlens, int32_t B, int32_t max_len, int32_t hidden,
+                               int32_t heads, float s_q, float s_k, float s_v, float s_p, float s_ctx, int8_t *ctx,
+                               void *stream);
+SAMP_API int samp_attention_f16(const uint16_t *qkv, const int32_t *cu_seqlens, int32_t B, int32_t max_len, int32_t hidden,
+                                int32_t heads, uint16_t *ctx, void *stream);
+
+/* The fused step of Section 3.2: z = deq(in) + bias + deq(res); y = LayerNorm(z; gamma, beta, eps);
+ * out = quantised y (int8, step s_out) or fp16 y.  in/res/out: dev [M,H], int8 when the matching
+ * *_i8 flag is set (then s_in / s_res / s_out are their steps), else fp16.  H % 4 == 0, H <= 2048.  */
+SAMP_API int samp_add_ln(const void *in, int32_t in_i8, float s_in, const float *bias, const void *res, int32_t res_i8,
+                         float s_res, const float *gamma, const float *beta, float eps, void *out, int32_t out_i8,
+                         float s_out, int32_t M, int32_t H, void *stream);
+
+/* The decision step of the FFN1 epilogue on its own: codes[i] = clamp(rne(GELU(y[i]) / s_out)) for a
+ * dev binary32 vector y of n elements; GELU in its exact-erf form.  fast (dev float [n], may be NULL)
+ * receives the kernel's fast-path GELU values, whose error bound the tests verify.                 */
+SAMP_API int samp_gelu_quant(const float *y, int64_t n, float s_out, int8_t *codes, float *fast, void *stream);
+
+/* Per-output-channel weight quantisation: W dev fp16 [N,K] -> Wq dev int8 [N,K], s_w dev float [N]. */
+SAMP_API int samp_quantize_weight(const uint16_t *W, int32_t N, int32_t K, int8_t *Wq, float *s_w, void *stream);
+
+/* Padding removal on entry (variable-length batches): packs the valid rows of hidden [B,S,H] (fp16)
+ * into packed [T,H] as fp16 (s_x <= 0) or int8 codes with step s_x; writes cu_seqlens [B+1] and
+ * row_map [B*S] (row_map[t] = b*S+s of packed row t).  mask as in samp_encoder_forward, not NULL.  */
+SAMP_API int samp_pack_rows(const uint16_t *hidden, const int32_t *mask, int32_t B, int32_t S, int32_t H, float s_x,
+                            void *packed, int32_t *cu_seqlens, int32_t *row_map, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SAMP_H */

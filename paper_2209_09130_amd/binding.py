@@ -1,0 +1,253 @@
+"""ctypes binding of the C ABI in include/samp.h (same names, argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional, Sequence
+
+import numpy as np
+import torch
+
+FP16, MHA_INT8, FFN_INT8, FULL_INT8 = 0, 1, 2, 3
+(PROF_OFF, PROF_QKV, PROF_ATTN, PROF_ATTN_OUT, PROF_LN1, PROF_FFN1, PROF_FFN2, PROF_LN2, PROF_ENTRY) = range(9)
+SCALE_FIELDS = ("x", "q", "k", "v", "p", "ctx", "attn_out", "ffn_in", "ffn_mid", "ffn_out")
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+
+
+class SampError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libsamp error {code}: {msg}")
+        self.code = code
+
+
+class _Config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("layers", "hidden", "heads", "ffn", "max_batch", "max_seq")] + \
+               [("ln_eps", C.c_float)]
+
+
+_WFIELDS = ("w_qkv", "w_o", "w_ffn1", "w_ffn2", "b_qkv", "b_o", "b_ffn1", "b_ffn2",
+            "ln1_g", "ln1_b", "ln2_g", "ln2_b")
+
+
+class _LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _WFIELDS]
+
+
+class _LayerScales(C.Structure):
+    _fields_ = [(n, C.c_float) for n in SCALE_FIELDS]
+
+
+def lib_path() -> str:
+    return os.path.join(_PKG, "libsamp.so")
+
+
+_lib = None
+
+
+def lib():
+    """Loads libsamp.so.  There is no fallback: without the HIP library nothing here works."""
+    global _lib
+    if _lib is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise ImportError(f"{path} is missing: build it first (python -m paper_2209_09130_amd.build)")
+        L = C.CDLL(path)
+        L.samp_last_error.restype = C.c_char_p
+        L.samp_encoder_arena_bytes.restype = C.c_size_t
+        L.samp_encoder_workspace_bytes.restype = C.c_size_t
+        L.samp_encoder_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+        _lib = L
+    return _lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise SampError(rc, lib().samp_last_error().decode())
+
+
+def _stream() -> C.c_void_p:
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dp(t: Optional[torch.Tensor]) -> C.c_void_p:
+    if t is None:
+        return C.c_void_p(0)
+    assert t.is_cuda and t.is_contiguous()
+    return C.c_void_p(t.data_ptr())
+
+
+def _f(v) -> C.c_float:
+    return C.c_float(float(v))
+
+
+class Encoder:
+    """samp_encoder_create / forward / calibrate / destroy."""
+
+    def __init__(self, layers: int, hidden: int, heads: int, ffn: int, ln_eps: float, modes: Sequence[int],
+                 weights: Sequence[Dict[str, np.ndarray]], scales: Optional[np.ndarray], max_batch: int, max_seq: int,
+                 device: str = "cuda:0"):
+        L = lib()
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        self.cfg = _Config(layers, hidden, heads, ffn, max_batch, max_seq, ln_eps)
+        self.layers, self.hidden = layers, hidden
+        modes_arr = (C.c_uint8 * layers)(*[int(m) for m in modes])
+        keep = []
+        warr = (_LayerWeights * layers)()
+        for i, w in enumerate(weights):
+            for n in _WFIELDS:
+                a = np.ascontiguousarray(w[n], dtype=np.float16 if n.startswith("w_") else np.float32)
+                keep.append(a)
+                setattr(warr[i], n, a.ctypes.data)
+        sarr = None
+        if scales is not None:
+            sc = np.asarray(scales, np.float32).reshape(layers, len(SCALE_FIELDS))
+            sarr = (_LayerScales * layers)()
+            for i in range(layers):
+                for j, n in enumerate(SCALE_FIELDS):
+                    setattr(sarr[i], n, float(sc[i, j]))
+        nbytes = L.samp_encoder_arena_bytes(C.byref(self.cfg), modes_arr)
+        if nbytes == 0:
+            raise SampError(-1, L.samp_last_error().decode())
+        self.arena = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self._h = C.c_void_p()
+        _check(L.samp_encoder_create(C.byref(self.cfg), modes_arr, warr, sarr, _dp(self.arena), C.c_size_t(nbytes),
+                                     _stream(), C.byref(self._h)))
+        self._ws = None
+
+    def workspace_bytes(self, B: int, S: int) -> int:
+        return int(lib().samp_encoder_workspace_bytes(self._h, B, S))
+
+    def _workspace(self, B: int, S: int) -> torch.Tensor:
+        need = self.workspace_bytes(B, S)
+        if need == 0:
+            raise SampError(-1, lib().samp_last_error().decode())
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        return self._ws
+
+    def forward(self, hidden: torch.Tensor, mask: Optional[torch.Tensor] = None,
+                out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        assert hidden.dtype == torch.float16 and hidden.dim() == 3
+        B, S, H = hidden.shape
+        ws = self._workspace(B, S)
+        if out is None:
+            out = torch.empty_like(hidden)
+        if mask is not None:
+            assert mask.dtype == torch.int32 and tuple(mask.shape) == (B, S)
+        _check(lib().samp_encoder_forward(self._h, _dp(hidden), _dp(mask), B, S, _dp(out), _dp(ws),
+                                          C.c_size_t(ws.numel()), _stream()))
+        return out
+
+    def calibrate(self, hidden: torch.Tensor, mask: Optional[torch.Tensor] = None) -> np.ndarray:
+        B, S, H = hidden.shape
+        ws = self._workspace(B, S)
+        out = (_LayerScales * self.layers)()
+        _check(lib().samp_encoder_calibrate(self._h, _dp(hidden), _dp(mask), B, S, _dp(ws), C.c_size_t(ws.numel()),
+                                            _stream(), out))
+        return np.array([[getattr(out[i], n) for n in SCALE_FIELDS] for i in range(self.layers)], np.float32)
+
+    def profile(self, which: int):
+        _check(lib().samp_encoder_profile(self._h, int(which)))
+
+    def profile_read(self):
+        ms, n = C.c_double(), C.c_int64()
+        _check(lib().samp_encoder_profile_read(self._h, C.byref(ms), C.byref(n)))
+        return ms.value, n.value
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h:
+            lib().samp_encoder_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+# ---- single steps (same names as the C entry points without the samp_ prefix) ----------------------
+def gemm_i8_i32(A: torch.Tensor, W: torch.Tensor) -> torch.Tensor:
+    M, K = A.shape
+    N = W.shape[0]
+    out = torch.empty((M, N), dtype=torch.int32, device=A.device)
+    _check(lib().samp_gemm_i8_i32(_dp(A), _dp(W), _dp(out), M, N, K, _stream()))
+    return out
+
+
+def gemm_i8_requant(A, W, m, b) -> torch.Tensor:
+    M, K = A.shape
+    N = W.shape[0]
+    out = torch.empty((M, N), dtype=torch.int8, device=A.device)
+    _check(lib().samp_gemm_i8_requant(_dp(A), _dp(W), _dp(m), _dp(b), _dp(out), M, N, K, _stream()))
+    return out
+
+
+def gemm_i8_gelu_quant(A, W, m, bias, s_out: float) -> torch.Tensor:
+    M, K = A.shape
+    N = W.shape[0]
+    out = torch.empty((M, N), dtype=torch.int8, device=A.device)
+    _check(lib().samp_gemm_i8_gelu_quant(_dp(A), _dp(W), _dp(m), _dp(bias), _f(s_out), _dp(out), M, N, K, _stream()))
+    return out
+
+
+def gemm_f16(A, W, bias, gelu: bool) -> torch.Tensor:
+    M, K = A.shape
+    N = W.shape[0]
+    out = torch.empty((M, N), dtype=torch.float16, device=A.device)
+    _check(lib().samp_gemm_f16(_dp(A), _dp(W), _dp(bias), int(gelu), _dp(out), M, N, K, _stream()))
+    return out
+
+
+def attention_i8(qkv, cu, max_len: int, heads: int, s_q, s_k, s_v, s_p, s_ctx) -> torch.Tensor:
+    T, H3 = qkv.shape
+    H = H3 // 3
+    ctx = torch.zeros((T, H), dtype=torch.int8, device=qkv.device)
+    _check(lib().samp_attention_i8(_dp(qkv), _dp(cu), cu.numel() - 1, max_len, H, heads, _f(s_q), _f(s_k), _f(s_v),
+                                   _f(s_p), _f(s_ctx), _dp(ctx), _stream()))
+    return ctx
+
+
+def attention_f16(qkv, cu, max_len: int, heads: int) -> torch.Tensor:
+    T, H3 = qkv.shape
+    H = H3 // 3
+    ctx = torch.zeros((T, H), dtype=torch.float16, device=qkv.device)
+    _check(lib().samp_attention_f16(_dp(qkv), _dp(cu), cu.numel() - 1, max_len, H, heads, _dp(ctx), _stream()))
+    return ctx
+
+
+def add_ln(inp, s_in, bias, res, s_res, gamma, beta, eps, out_i8: bool, s_out: float = 1.0) -> torch.Tensor:
+    M, H = inp.shape
+    out = torch.empty((M, H), dtype=torch.int8 if out_i8 else torch.float16, device=inp.device)
+    _check(lib().samp_add_ln(_dp(inp), int(inp.dtype == torch.int8), _f(s_in), _dp(bias), _dp(res),
+                             int(res.dtype == torch.int8), _f(s_res), _dp(gamma), _dp(beta), _f(eps), _dp(out),
+                             int(out_i8), _f(s_out), M, H, _stream()))
+    return out
+
+
+def gelu_quant(y: torch.Tensor, s_out: float, want_fast: bool = False):
+    n = y.numel()
+    codes = torch.empty(n, dtype=torch.int8, device=y.device)
+    fast = torch.empty(n, dtype=torch.float32, device=y.device) if want_fast else None
+    _check(lib().samp_gelu_quant(_dp(y), C.c_int64(n), _f(s_out), _dp(codes), _dp(fast), _stream()))
+    return (codes, fast) if want_fast else codes
+
+
+def quantize_weight(W: torch.Tensor):
+    N, K = W.shape
+    Wq = torch.empty((N, K), dtype=torch.int8, device=W.device)
+    s_w = torch.empty(N, dtype=torch.float32, device=W.device)
+    _check(lib().samp_quantize_weight(_dp(W), N, K, _dp(Wq), _dp(s_w), _stream()))
+    return Wq, s_w
+
+
+def pack_rows(hidden: torch.Tensor, mask: torch.Tensor, s_x: float = 0.0):
+    """Returns (packed [B*S,H] (first T rows valid), cu_seqlens [B+1], row_map [B*S])."""
+    B, S, H = hidden.shape
+    packed = torch.zeros((B * S, H), dtype=torch.int8 if s_x > 0 else torch.float16, device=hidden.device)
+    cu = torch.zeros(B + 1, dtype=torch.int32, device=hidden.device)
+    row_map = torch.zeros(B * S, dtype=torch.int32, device=hidden.device)
+    _check(lib().samp_pack_rows(_dp(hidden), _dp(mask), B, S, H, _f(s_x), _dp(packed), _dp(cu), _dp(row_map), _stream()))
+    return packed, cu, row_map

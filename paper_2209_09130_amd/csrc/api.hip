@@ -1,0 +1,544 @@
+// C ABI of libsamp: argument checking, weight packing at create time, workspace carving and the
+// per-layer kernel sequence of Section 3.2 (seven kernels per layer plus entry / exit handling).
+#include "../../include/samp.h"
+#include "samp_common.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+using namespace samp;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                               \
+    do {                                                                                            \
+        hipError_t e_ = (expr);                                                                     \
+        if (e_ != hipSuccess) return fail(SAMP_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_));    \
+    } while (0)
+
+constexpr size_t ALIGN = 256;
+size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+bool good_scale(float s) { return std::isfinite(s) && s > 0.0f; }
+
+struct Layer {
+    int mode;
+    samp_layer_scales_t s;
+    // INT8 blocks: int8 weights and folded epilogue tables; FP16 blocks: fp16 weights
+    void *w_qkv, *w_o, *w_f1, *w_f2;
+    float *m_qkv, *bq_qkv, *m_o, *m_f1, *m_f2;
+    float *b_qkv, *b_o, *b_f1, *b_f2, *g1, *be1, *g2, *be2;
+    float m_sc, inv_sp, m_ctx;                      // attention multipliers of an INT8 MHA block
+};
+
+struct Carver {                                     // hands out aligned pieces of a device buffer
+    char *base; size_t off;
+    template <class T> T *take(size_t count) { T *p = reinterpret_cast<T *>(base + off); off += up(count * sizeof(T)); return p; }
+};
+
+size_t staging_bytes(const samp_config_t &c)
+{
+    const size_t big = (size_t)std::max(3 * c.hidden, c.ffn) * c.hidden;    // largest matrix, elements
+    return up(big * 2) + up((size_t)std::max(3 * c.hidden, c.ffn) * sizeof(float));
+}
+
+int check_config(const samp_config_t *c)
+{
+    if (!c) return fail(SAMP_ERR_ARG, "config is NULL");
+    if (c->layers < 1 || c->heads < 1 || c->max_batch < 1) return fail(SAMP_ERR_SHAPE, "layers, heads, max_batch must be >= 1");
+    if (c->hidden != c->heads * 64) return fail(SAMP_ERR_SHAPE, "head size hidden/heads must be 64 (hidden=%d heads=%d)", c->hidden, c->heads);
+    if (c->hidden % 128 || c->hidden > 2048) return fail(SAMP_ERR_SHAPE, "hidden must be a multiple of 128, at most 2048");
+    if (c->ffn < 128 || c->ffn % 128) return fail(SAMP_ERR_SHAPE, "ffn must be a positive multiple of 128");
+    if (c->max_seq < 1 || c->max_seq > 512) return fail(SAMP_ERR_SHAPE, "max_seq must be in [1, 512]");
+    if (!(c->ln_eps >= 0.0f) || !std::isfinite(c->ln_eps)) return fail(SAMP_ERR_ARG, "ln_eps must be finite and >= 0");
+    return SAMP_OK;
+}
+
+size_t layer_arena_bytes(const samp_config_t &c, int mode)
+{
+    const size_t H = c.hidden, F = c.ffn;
+    size_t n = 0;
+    const size_t e_mha = (mode & 1) ? 1 : 2, e_ffn = (mode & 2) ? 1 : 2;
+    n += up(3 * H * H * e_mha) + up(H * H * e_mha) + up(F * H * e_ffn) + up(H * F * e_ffn);
+    n += 2 * up(3 * H * 4) + up(H * 4) + up(F * 4) + up(H * 4);             // m_qkv, bq_qkv, m_o, m_f1, m_f2
+    n += up(3 * H * 4) + up(F * 4) + 6 * up(H * 4);                         // biases and LayerNorm vectors
+    return n;
+}
+
+constexpr int MAX_EVENTS = 4096;
+
+}  // namespace
+
+struct samp_encoder {
+    samp_config_t cfg;
+    std::vector<Layer> L;
+    bool all_fp16;
+    int prof_which = SAMP_PROF_OFF;
+    std::vector<Timing> events;                     // pool, created on first use
+    int events_used = 0;
+};
+
+namespace {
+
+const Timing *timing(samp_encoder *e, int which)
+{
+    if (e->prof_which != which || e->events_used >= MAX_EVENTS) return nullptr;
+    if ((int)e->events.size() <= e->events_used) {
+        Timing t;
+        if (hipEventCreate(&t.start) != hipSuccess || hipEventCreate(&t.stop) != hipSuccess) return nullptr;
+        e->events.push_back(t);
+    }
+    return &e->events[e->events_used++];
+}
+
+struct Workspace {
+    int *cu, *row_map;
+    void *x, *qkv, *ctx, *ao, *h1, *f1, *f2, *y;
+    float *absmax;                                  // [layers*10], calibration only
+    size_t bytes;
+};
+
+Workspace carve(const samp_config_t &c, int B, int S, void *base)
+{
+    const size_t T = (size_t)B * S, H = c.hidden, F = c.ffn;
+    Carver cv{static_cast<char *>(base), 0};
+    Workspace w;
+    w.cu = cv.take<int>(B + 1);
+    w.row_map = cv.take<int>(T);
+    w.absmax = cv.take<float>((size_t)c.layers * 10);
+    w.x = cv.take<__half>(T * H);
+    w.qkv = cv.take<__half>(T * 3 * H);
+    w.ctx = cv.take<__half>(T * H);
+    w.ao = cv.take<__half>(T * H);
+    w.h1 = cv.take<__half>(T * H);
+    w.f1 = cv.take<__half>(T * F);
+    w.f2 = cv.take<__half>(T * H);
+    w.y = cv.take<__half>(T * H);
+    w.bytes = cv.off;
+    return w;
+}
+
+int check_forward_args(const samp_encoder_t *enc, const void *hidden, int B, int S, const void *workspace, size_t ws_bytes)
+{
+    if (!enc || !hidden || !workspace) return fail(SAMP_ERR_ARG, "encoder, hidden or workspace is NULL");
+    if (B < 1 || S < 1) return fail(SAMP_ERR_SHAPE, "B and S must be >= 1");
+    if (B > enc->cfg.max_batch || S > enc->cfg.max_seq)
+        return fail(SAMP_ERR_SHAPE, "B=%d S=%d exceed max_batch=%d max_seq=%d", B, S, enc->cfg.max_batch, enc->cfg.max_seq);
+    if (!aligned(workspace, ALIGN)) return fail(SAMP_ERR_SPACE, "workspace must be 256-byte aligned");
+    const size_t need = samp_encoder_workspace_bytes(enc, B, S);
+    if (ws_bytes < need) return fail(SAMP_ERR_SPACE, "workspace has %zu bytes, %zu needed", ws_bytes, need);
+    if (!aligned(hidden, 16)) return fail(SAMP_ERR_ARG, "hidden must be 16-byte aligned");
+    return SAMP_OK;
+}
+
+// The kernel sequence.  calib: FP16-only run that also records each tensor's absmax.
+int run(samp_encoder_t *enc, const void *hidden, const int32_t *mask, int B, int S, void *out, void *workspace,
+        hipStream_t st, bool calib)
+{
+    const samp_config_t &c = enc->cfg;
+    const int H = c.hidden, F = c.ffn, heads = c.heads, Lc = c.layers;
+    Workspace w = carve(c, B, S, workspace);
+    const int Tmax = B * S;
+    const bool packed = mask != nullptr;
+    const int *cu = nullptr, *row_map = nullptr;
+    Rows rows{Tmax, nullptr};
+    const void *x = nullptr;
+    const bool first8 = (enc->L[0].mode & 1) != 0;
+
+    if (calib) HIP_TRY(launch_fill_f32(w.absmax, Lc * 10, 0.0f, st));
+
+    // entry: padding removal and, if layer 0's attention block is INT8, quantisation by its producer
+    if (packed) {
+        HIP_TRY(launch_seq_offsets(mask, B, S, w.cu, st));
+        HIP_TRY(launch_pack_rows((const __half *)hidden, w.cu, B, S, H, first8 ? enc->L[0].s.x : 0.0f, w.x, w.row_map,
+                                 (__half *)out, st, timing(enc, SAMP_PROF_ENTRY)));
+        cu = w.cu; row_map = w.row_map; rows.dev_rows = w.cu + B;
+        x = w.x;
+    } else if (first8) {
+        HIP_TRY(launch_quantize_rows((const __half *)hidden, (size_t)Tmax * H, enc->L[0].s.x, (int8_t *)w.x, st,
+                                     timing(enc, SAMP_PROF_ENTRY)));
+        x = w.x;
+    } else {
+        x = hidden;                                 // fp16 input consumed in place
+    }
+    void *ybuf[2] = {w.y, w.x};                     // layer outputs alternate; w.x is free after layer 0's LN-1
+    int yi = 0;
+
+    for (int l = 0; l < Lc; l++) {
+        const Layer &Y = enc->L[l];
+        const bool mha8 = Y.mode & 1, ffn8 = Y.mode & 2, last = (l == Lc - 1);
+        const bool next8 = !last && (enc->L[l + 1].mode & 1);
+        float *am = calib ? w.absmax + l * 10 : nullptr;
+
+        if (mha8) {
+            HIP_TRY(launch_gemm_i8(EPI_REQUANT, (const int8_t *)x, (const int8_t *)Y.w_qkv, w.qkv, Y.m_qkv, Y.bq_qkv, 0.f,
+                                   rows, 3 * H, H, st, timing(enc, SAMP_PROF_QKV)));
+            HIP_TRY(launch_attention_i8((const int8_t *)w.qkv, cu, B, S, H, heads, Y.m_sc, Y.inv_sp, Y.m_ctx,
+                                        (int8_t *)w.ctx, st, timing(enc, SAMP_PROF_ATTN)));
+            HIP_TRY(launch_gemm_i8(EPI_REQUANT, (const int8_t *)w.ctx, (const int8_t *)Y.w_o, w.ao, Y.m_o, nullptr, 0.f,
+                                   rows, H, H, st, timing(enc, SAMP_PROF_ATTN_OUT)));
+        } else {
+            if (am) HIP_TRY(launch_absmax_f16((const __half *)x, rows, H, H, am + 0, st));
+            HIP_TRY(launch_gemm_f16((const __half *)x, (const __half *)Y.w_qkv, Y.b_qkv, false, (__half *)w.qkv, rows,
+                                    3 * H, H, st, timing(enc, SAMP_PROF_QKV)));
+            if (am)
+                for (int part = 0; part < 3; part++)
+                    HIP_TRY(launch_absmax_f16((const __half *)w.qkv + part * H, rows, H, 3 * H, am + 1 + part, st));
+            HIP_TRY(launch_attention_f16((const __half *)w.qkv, cu, B, S, H, heads, 0.125f, (__half *)w.ctx,
+                                         am ? am + 4 : nullptr, st, timing(enc, SAMP_PROF_ATTN)));
+            if (am) HIP_TRY(launch_absmax_f16((const __half *)w.ctx, rows, H, H, am + 5, st));
+            HIP_TRY(launch_gemm_f16((const __half *)w.ctx, (const __half *)Y.w_o, nullptr, false, (__half *)w.ao, rows, H, H,
+                                    st, timing(enc, SAMP_PROF_ATTN_OUT)));
+            if (am) HIP_TRY(launch_absmax_f16((const __half *)w.ao, rows, H, H, am + 6, st));
+        }
+        {   // bias + residual + LayerNorm (+ quantise for an INT8 FFN); residual = the block's own input tensor
+            AddLnArgs a{w.ao, mha8, Y.s.attn_out, Y.b_o, x, mha8, Y.s.x, Y.g1, Y.be1, c.ln_eps,
+                        w.h1, ffn8, Y.s.ffn_in, nullptr, am ? am + 7 : nullptr, rows, H};
+            HIP_TRY(launch_add_ln(a, st, timing(enc, SAMP_PROF_LN1)));
+        }
+        if (ffn8) {
+            HIP_TRY(launch_gemm_i8(EPI_GELU_QUANT, (const int8_t *)w.h1, (const int8_t *)Y.w_f1, w.f1, Y.m_f1, Y.b_f1,
+                                   1.0f / Y.s.ffn_mid, rows, F, H, st, timing(enc, SAMP_PROF_FFN1)));
+            HIP_TRY(launch_gemm_i8(EPI_REQUANT, (const int8_t *)w.f1, (const int8_t *)Y.w_f2, w.f2, Y.m_f2, nullptr, 0.f,
+                                   rows, H, F, st, timing(enc, SAMP_PROF_FFN2)));
+        } else {
+            HIP_TRY(launch_gemm_f16((const __half *)w.h1, (const __half *)Y.w_f1, Y.b_f1, true, (__half *)w.f1, rows, F, H,
+                                    st, timing(enc, SAMP_PROF_FFN1)));
+            if (am) HIP_TRY(launch_absmax_f16((const __half *)w.f1, rows, F, F, am + 8, st));
+            HIP_TRY(launch_gemm_f16((const __half *)w.f1, (const __half *)Y.w_f2, nullptr, false, (__half *)w.f2, rows, H, F,
+                                    st, timing(enc, SAMP_PROF_FFN2)));
+            if (am) HIP_TRY(launch_absmax_f16((const __half *)w.f2, rows, H, H, am + 9, st));
+        }
+        {   // second fused step; the last layer always leaves fp16, scattered back to [B,S,H]
+            void *dst = last ? (calib ? ybuf[yi] : out) : ybuf[yi];
+            AddLnArgs a{w.f2, ffn8, Y.s.ffn_out, Y.b_f2, w.h1, ffn8, Y.s.ffn_in, Y.g2, Y.be2, c.ln_eps,
+                        dst, next8, next8 ? enc->L[l + 1].s.x : 1.0f, (last && !calib) ? row_map : nullptr, nullptr, rows, H};
+            HIP_TRY(launch_add_ln(a, st, timing(enc, SAMP_PROF_LN2)));
+            x = dst;
+            yi ^= 1;
+        }
+    }
+    return SAMP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *samp_last_error(void) { return g_err; }
+
+size_t samp_encoder_arena_bytes(const samp_config_t *cfg, const uint8_t *modes)
+{
+    if (check_config(cfg) != SAMP_OK) return 0;
+    if (!modes) { fail(SAMP_ERR_ARG, "modes is NULL"); return 0; }
+    size_t n = 0;
+    for (int l = 0; l < cfg->layers; l++) {
+        if (modes[l] > 3) { fail(SAMP_ERR_ARG, "unknown mode %d for layer %d", modes[l], l); return 0; }
+        n += layer_arena_bytes(*cfg, modes[l]);
+    }
+    return n + staging_bytes(*cfg);
+}
+
+int samp_encoder_create(const samp_config_t *cfg, const uint8_t *modes, const samp_layer_weights_t *weights,
+                        const samp_layer_scales_t *scales, void *dev_arena, size_t arena_bytes, void *stream,
+                        samp_encoder_t **out)
+{
+    if (int rc = check_config(cfg)) return rc;
+    if (!modes || !weights || !dev_arena || !out) return fail(SAMP_ERR_ARG, "modes, weights, dev_arena or out is NULL");
+    *out = nullptr;
+    bool any8 = false;
+    for (int l = 0; l < cfg->layers; l++) {
+        if (modes[l] > 3) return fail(SAMP_ERR_ARG, "unknown mode %d for layer %d", modes[l], l);
+        any8 |= modes[l] != 0;
+        const samp_layer_weights_t &w = weights[l];
+        if (!w.w_qkv || !w.w_o || !w.w_ffn1 || !w.w_ffn2 || !w.b_qkv || !w.b_o || !w.b_ffn1 || !w.b_ffn2 || !w.ln1_g ||
+            !w.ln1_b || !w.ln2_g || !w.ln2_b)
+            return fail(SAMP_ERR_ARG, "layer %d has a NULL weight pointer", l);
+    }
+    if (any8 && !scales) return fail(SAMP_ERR_ARG, "scales is NULL but a layer has an INT8 block");
+    for (int l = 0; l < cfg->layers && any8; l++) {
+        const samp_layer_scales_t &s = scales[l];
+        const bool need_x = (modes[l] & 1);
+        if (need_x && !(good_scale(s.x) && good_scale(s.q) && good_scale(s.k) && good_scale(s.v) && good_scale(s.p) &&
+                        good_scale(s.ctx) && good_scale(s.attn_out)))
+            return fail(SAMP_ERR_SCALE, "layer %d: an attention-block scale is not finite and positive", l);
+        if ((modes[l] & 2) && !(good_scale(s.ffn_in) && good_scale(s.ffn_mid) && good_scale(s.ffn_out)))
+            return fail(SAMP_ERR_SCALE, "layer %d: a feed-forward-block scale is not finite and positive", l);
+    }
+    if (!aligned(dev_arena, ALIGN)) return fail(SAMP_ERR_SPACE, "arena must be 256-byte aligned");
+    const size_t need = samp_encoder_arena_bytes(cfg, modes);
+    if (arena_bytes < need) return fail(SAMP_ERR_SPACE, "arena has %zu bytes, %zu needed", arena_bytes, need);
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    samp_encoder *E = new (std::nothrow) samp_encoder();
+    if (!E) return fail(SAMP_ERR_ARG, "out of host memory");
+    E->cfg = *cfg;
+    E->all_fp16 = !any8;
+    E->L.resize(cfg->layers);
+    const size_t H = cfg->hidden, F = cfg->ffn;
+    Carver cv{static_cast<char *>(dev_arena), 0};
+    const size_t big = std::max(3 * H, F);
+    __half *stage = cv.take<__half>(big * H);
+    float *s_w = cv.take<float>(big);
+
+    auto body = [&]() -> int {
+        for (int l = 0; l < cfg->layers; l++) {
+            Layer &Y = E->L[l];
+            const samp_layer_weights_t &w = weights[l];
+            Y.mode = modes[l];
+            if (scales) Y.s = scales[l]; else memset(&Y.s, 0, sizeof(Y.s));
+            const bool mha8 = Y.mode & 1, ffn8 = Y.mode & 2;
+            auto vec = [&](const float *src, size_t n, float **dst) -> int {
+                *dst = cv.take<float>(n);
+                HIP_TRY(hipMemcpyAsync(*dst, src, n * sizeof(float), hipMemcpyHostToDevice, st));
+                return SAMP_OK;
+            };
+            if (int rc = vec(w.b_qkv, 3 * H, &Y.b_qkv)) return rc;
+            if (int rc = vec(w.b_o, H, &Y.b_o)) return rc;
+            if (int rc = vec(w.b_ffn1, F, &Y.b_f1)) return rc;
+            if (int rc = vec(w.b_ffn2, H, &Y.b_f2)) return rc;
+            if (int rc = vec(w.ln1_g, H, &Y.g1)) return rc;
+            if (int rc = vec(w.ln1_b, H, &Y.be1)) return rc;
+            if (int rc = vec(w.ln2_g, H, &Y.g2)) return rc;
+            if (int rc = vec(w.ln2_b, H, &Y.be2)) return rc;
+            Y.m_qkv = cv.take<float>(3 * H); Y.bq_qkv = cv.take<float>(3 * H);
+            Y.m_o = cv.take<float>(H); Y.m_f1 = cv.take<float>(F); Y.m_f2 = cv.take<float>(H);
+
+            // fp16 matrix -> either kept as fp16 or quantised per output channel into int8
+            auto matrix = [&](const uint16_t *src, size_t N, size_t K, bool q8, void **dst) -> int {
+                if (!q8) {
+                    *dst = cv.take<__half>(N * K);
+                    HIP_TRY(hipMemcpyAsync(*dst, src, N * K * 2, hipMemcpyHostToDevice, st));
+                } else {
+                    *dst = cv.take<int8_t>(N * K);
+                    HIP_TRY(hipMemcpyAsync(stage, src, N * K * 2, hipMemcpyHostToDevice, st));
+                    HIP_TRY(launch_quantize_weight(stage, (int)N, (int)K, (int8_t *)*dst, s_w, st));
+                }
+                return SAMP_OK;
+            };
+            if (int rc = matrix(w.w_qkv, 3 * H, H, mha8, &Y.w_qkv)) return rc;
+            if (mha8) {
+                const float so[3] = {Y.s.q, Y.s.k, Y.s.v};
+                for (int part = 0; part < 3; part++)
+                    HIP_TRY(launch_fold(nullptr, Y.s.x, s_w + part * H, Y.b_qkv + part * H, so[part], (int)H,
+                                        Y.m_qkv + part * H, Y.bq_qkv + part * H, st));
+                Y.m_sc = (float)((double)Y.s.q * (double)Y.s.k / std::sqrt(64.0));
+                Y.inv_sp = 1.0f / Y.s.p;
+                Y.m_ctx = (float)((double)Y.s.p * (double)Y.s.v / (double)Y.s.ctx);
+            }
+            if (int rc = matrix(w.w_o, H, H, mha8, &Y.w_o)) return rc;
+            if (mha8) HIP_TRY(launch_fold(nullptr, Y.s.ctx, s_w, nullptr, Y.s.attn_out, (int)H, Y.m_o, nullptr, st));
+            if (int rc = matrix(w.w_ffn1, F, H, ffn8, &Y.w_f1)) return rc;
+            if (ffn8) HIP_TRY(launch_fold(nullptr, Y.s.ffn_in, s_w, nullptr, 1.0f, (int)F, Y.m_f1, nullptr, st));
+            if (int rc = matrix(w.w_ffn2, H, F, ffn8, &Y.w_f2)) return rc;
+            if (ffn8) HIP_TRY(launch_fold(nullptr, Y.s.ffn_mid, s_w, nullptr, Y.s.ffn_out, (int)H, Y.m_f2, nullptr, st));
+        }
+        HIP_TRY(hipStreamSynchronize(st));
+        return SAMP_OK;
+    };
+    const int rc = body();
+    if (rc != SAMP_OK) { delete E; return rc; }
+    *out = E;
+    return SAMP_OK;
+}
+
+size_t samp_encoder_workspace_bytes(const samp_encoder_t *enc, int32_t B, int32_t S)
+{
+    if (!enc || B < 1 || S < 1) { fail(SAMP_ERR_ARG, "encoder is NULL or B, S < 1"); return 0; }
+    return carve(enc->cfg, B, S, nullptr).bytes;
+}
+
+int samp_encoder_forward(samp_encoder_t *enc, const void *hidden, const int32_t *mask, int32_t B, int32_t S, void *out,
+                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (int rc = check_forward_args(enc, hidden, B, S, workspace, workspace_bytes)) return rc;
+    if (!out) return fail(SAMP_ERR_ARG, "out is NULL");
+    if (out == hidden) return fail(SAMP_ERR_ARG, "out must not alias hidden");
+    if (!aligned(out, 16)) return fail(SAMP_ERR_ARG, "out must be 16-byte aligned");
+    return run(enc, hidden, mask, B, S, out, workspace, static_cast<hipStream_t>(stream), false);
+}
+
+int samp_encoder_calibrate(samp_encoder_t *enc, const void *hidden, const int32_t *mask, int32_t B, int32_t S,
+                           void *workspace, size_t workspace_bytes, void *stream, samp_layer_scales_t *scales_out)
+{
+    if (int rc = check_forward_args(enc, hidden, B, S, workspace, workspace_bytes)) return rc;
+    if (!scales_out) return fail(SAMP_ERR_ARG, "scales_out is NULL");
+    if (!enc->all_fp16) return fail(SAMP_ERR_ARG, "calibration needs an encoder whose layers are all SAMP_FP16");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (int rc = run(enc, hidden, mask, B, S, nullptr, workspace, st, true)) return rc;
+    const int n = enc->cfg.layers * 10;
+    std::vector<float> am(n);
+    Workspace w = carve(enc->cfg, B, S, workspace);
+    HIP_TRY(hipMemcpyAsync(am.data(), w.absmax, n * sizeof(float), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    float *dst = reinterpret_cast<float *>(scales_out);
+    for (int i = 0; i < n; i++) dst[i] = am[i] / 127.0f;
+    return SAMP_OK;
+}
+
+int samp_encoder_destroy(samp_encoder_t *enc)
+{
+    if (!enc) return SAMP_OK;
+    for (Timing &t : enc->events) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
+    delete enc;
+    return SAMP_OK;
+}
+
+int samp_encoder_profile(samp_encoder_t *enc, int which)
+{
+    if (!enc) return fail(SAMP_ERR_ARG, "encoder is NULL");
+    if (which < SAMP_PROF_OFF || which > SAMP_PROF_ENTRY) return fail(SAMP_ERR_ARG, "unknown kernel class %d", which);
+    enc->prof_which = which;
+    return SAMP_OK;
+}
+
+int samp_encoder_profile_read(samp_encoder_t *enc, double *mean_ms, int64_t *launches)
+{
+    if (!enc || !mean_ms || !launches) return fail(SAMP_ERR_ARG, "NULL argument");
+    double total = 0.0;
+    for (int i = 0; i < enc->events_used; i++) {
+        HIP_TRY(hipEventSynchronize(enc->events[i].stop));
+        float ms = 0.0f;
+        HIP_TRY(hipEventElapsedTime(&ms, enc->events[i].start, enc->events[i].stop));
+        total += ms;
+    }
+    *launches = enc->events_used;
+    *mean_ms = enc->events_used ? total / enc->events_used : 0.0;
+    enc->events_used = 0;
+    return SAMP_OK;
+}
+
+// ---- single steps --------------------------------------------------------------------------------
+
+static int check_gemm(const void *A, const void *W, const void *out, int M, int N, int K, int kmul)
+{
+    if (!A || !W || !out) return fail(SAMP_ERR_ARG, "NULL matrix pointer");
+    if (M < 1 || N < 128 || N % 128 || K < kmul || K % kmul)
+        return fail(SAMP_ERR_SHAPE, "GEMM needs M >= 1, N %% 128 == 0, K %% %d == 0 (M=%d N=%d K=%d)", kmul, M, N, K);
+    if (!aligned(A, 16) || !aligned(W, 16) || !aligned(out, 16)) return fail(SAMP_ERR_ARG, "matrices must be 16-byte aligned");
+    return SAMP_OK;
+}
+
+int samp_gemm_i8_i32(const int8_t *A, const int8_t *W, int32_t *C, int32_t M, int32_t N, int32_t K, void *stream)
+{
+    if (int rc = check_gemm(A, W, C, M, N, K, 64)) return rc;
+    HIP_TRY(launch_gemm_i8(EPI_RAW_I32, A, W, C, nullptr, nullptr, 0.f, Rows{M, nullptr}, N, K, (hipStream_t)stream, nullptr));
+    return SAMP_OK;
+}
+
+int samp_gemm_i8_requant(const int8_t *A, const int8_t *W, const float *m, const float *b, int8_t *out, int32_t M,
+                         int32_t N, int32_t K, void *stream)
+{
+    if (int rc = check_gemm(A, W, out, M, N, K, 64)) return rc;
+    if (!m) return fail(SAMP_ERR_ARG, "multiplier table is NULL");
+    HIP_TRY(launch_gemm_i8(EPI_REQUANT, A, W, out, m, b, 0.f, Rows{M, nullptr}, N, K, (hipStream_t)stream, nullptr));
+    return SAMP_OK;
+}
+
+int samp_gemm_i8_gelu_quant(const int8_t *A, const int8_t *W, const float *m, const float *bias, float s_out, int8_t *out,
+                            int32_t M, int32_t N, int32_t K, void *stream)
+{
+    if (int rc = check_gemm(A, W, out, M, N, K, 64)) return rc;
+    if (!m || !bias) return fail(SAMP_ERR_ARG, "multiplier or bias table is NULL");
+    if (!good_scale(s_out)) return fail(SAMP_ERR_SCALE, "s_out must be finite and positive");
+    HIP_TRY(launch_gemm_i8(EPI_GELU_QUANT, A, W, out, m, bias, 1.0f / s_out, Rows{M, nullptr}, N, K, (hipStream_t)stream, nullptr));
+    return SAMP_OK;
+}
+
+int samp_gemm_f16(const uint16_t *A, const uint16_t *W, const float *bias, int32_t gelu, uint16_t *out, int32_t M, int32_t N,
+                  int32_t K, void *stream)
+{
+    if (int rc = check_gemm(A, W, out, M, N, K, 32)) return rc;
+    HIP_TRY(launch_gemm_f16((const __half *)A, (const __half *)W, bias, gelu != 0, (__half *)out, Rows{M, nullptr}, N, K,
+                            (hipStream_t)stream, nullptr));
+    return SAMP_OK;
+}
+
+static int check_attention(const void *qkv, const int32_t *cu, int B, int max_len, int hidden, int heads, const void *ctx)
+{
+    if (!qkv || !cu || !ctx) return fail(SAMP_ERR_ARG, "NULL pointer");
+    if (B < 1 || max_len < 1 || max_len > 512) return fail(SAMP_ERR_SHAPE, "B >= 1 and 1 <= max_len <= 512 required");
+    if (heads < 1 || hidden != heads * 64) return fail(SAMP_ERR_SHAPE, "head size must be 64");
+    if (!aligned(qkv, 16) || !aligned(ctx, 16)) return fail(SAMP_ERR_ARG, "tensors must be 16-byte aligned");
+    return SAMP_OK;
+}
+
+int samp_attention_i8(const int8_t *qkv, const int32_t *cu, int32_t B, int32_t max_len, int32_t hidden, int32_t heads,
+                      float s_q, float s_k, float s_v, float s_p, float s_ctx, int8_t *ctx, void *stream)
+{
+    if (int rc = check_attention(qkv, cu, B, max_len, hidden, heads, ctx)) return rc;
+    if (!(good_scale(s_q) && good_scale(s_k) && good_scale(s_v) && good_scale(s_p) && good_scale(s_ctx)))
+        return fail(SAMP_ERR_SCALE, "attention scales must be finite and positive");
+    const float m_sc = (float)((double)s_q * (double)s_k / std::sqrt(64.0));
+    const float m_ctx = (float)((double)s_p * (double)s_v / (double)s_ctx);
+    HIP_TRY(launch_attention_i8(qkv, cu, B, max_len, hidden, heads, m_sc, 1.0f / s_p, m_ctx, ctx, (hipStream_t)stream, nullptr));
+    return SAMP_OK;
+}
+
+int samp_attention_f16(const uint16_t *qkv, const int32_t *cu, int32_t B, int32_t max_len, int32_t hidden, int32_t heads,
+                       uint16_t *ctx, void *stream)
+{
+    if (int rc = check_attention(qkv, cu, B, max_len, hidden, heads, ctx)) return rc;
+    HIP_TRY(launch_attention_f16((const __half *)qkv, cu, B, max_len, hidden, heads, 0.125f, (__half *)ctx, nullptr,
+                                 (hipStream_t)stream, nullptr));
+    return SAMP_OK;
+}
+
+int samp_add_ln(const void *in, int32_t in_i8, float s_in, const float *bias, const void *res, int32_t res_i8, float s_res,
+                const float *gamma, const float *beta, float eps, void *out, int32_t out_i8, float s_out, int32_t M, int32_t H,
+                void *stream)
+{
+    if (!in || !bias || !res || !gamma || !beta || !out) return fail(SAMP_ERR_ARG, "NULL pointer");
+    if (M < 1 || H < 4 || H % 4 || H > 2048) return fail(SAMP_ERR_SHAPE, "M >= 1, H %% 4 == 0, H <= 2048 required");
+    if ((in_i8 && !good_scale(s_in)) || (res_i8 && !good_scale(s_res)) || (out_i8 && !good_scale(s_out)))
+        return fail(SAMP_ERR_SCALE, "a step of an int8 operand is not finite and positive");
+    AddLnArgs a{in, in_i8 != 0, s_in, bias, res, res_i8 != 0, s_res, gamma, beta, eps, out, out_i8 != 0, s_out,
+                nullptr, nullptr, Rows{M, nullptr}, H};
+    HIP_TRY(launch_add_ln(a, (hipStream_t)stream, nullptr));
+    return SAMP_OK;
+}
+
+int samp_gelu_quant(const float *y, int64_t n, float s_out, int8_t *codes, float *fast, void *stream)
+{
+    if (!y || !codes) return fail(SAMP_ERR_ARG, "NULL pointer");
+    if (n < 1) return fail(SAMP_ERR_SHAPE, "n >= 1 required");
+    if (!good_scale(s_out)) return fail(SAMP_ERR_SCALE, "s_out must be finite and positive");
+    HIP_TRY(launch_gelu_quant(y, (size_t)n, 1.0f / s_out, codes, fast, (hipStream_t)stream));
+    return SAMP_OK;
+}
+
+int samp_quantize_weight(const uint16_t *W, int32_t N, int32_t K, int8_t *Wq, float *s_w, void *stream)
+{
+    if (!W || !Wq || !s_w) return fail(SAMP_ERR_ARG, "NULL pointer");
+    if (N < 1 || K < 1) return fail(SAMP_ERR_SHAPE, "N, K >= 1 required");
+    HIP_TRY(launch_quantize_weight((const __half *)W, N, K, Wq, s_w, (hipStream_t)stream));
+    return SAMP_OK;
+}
+
+int samp_pack_rows(const uint16_t *hidden, const int32_t *mask, int32_t B, int32_t S, int32_t H, float s_x, void *packed,
+                   int32_t *cu, int32_t *row_map, void *stream)
+{
+    if (!hidden || !mask || !packed || !cu || !row_map) return fail(SAMP_ERR_ARG, "NULL pointer");
+    if (B < 1 || S < 1 || H < 8 || H % 8) return fail(SAMP_ERR_SHAPE, "B, S >= 1 and H %% 8 == 0 required");
+    if (B > 8192) return fail(SAMP_ERR_SHAPE, "B too large");
+    HIP_TRY(launch_seq_offsets(mask, B, S, cu, (hipStream_t)stream));
+    HIP_TRY(launch_pack_rows((const __half *)hidden, cu, B, S, H, s_x, packed, row_map, nullptr, (hipStream_t)stream, nullptr));
+    return SAMP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,311 @@
+// Softmax attention over packed (padding-free) rows on gfx950 matrix cores.
+//
+// INT8 flavour (Section 4.2 / Appendix B: the softmax output is quantised with a step fixed at
+// calibration, so both batched products are int8 x int8 -> int32):
+//     score = float(q.k) * m_sc;  P = softmax(score);  Pq = rne(P / s_p);  ctx = rne(float(Pq.V) * m_ctx)
+// Because the step of P is static, P must be fully normalised before it is rounded: a block keeps
+// a whole strip of scores on chip (32 queries x all keys of the sequence, <= 512), so the scores
+// never touch memory and no running rescale is needed.
+//
+// One block = (sequence, head, 32 queries), 4 waves; wave w owns key tiles w, w+4, ... (32 keys
+// each).  S^T = K.Q^T is computed so that in the 32x32 MFMA result a lane holds ONE query and 16
+// keys: after the softmax those 16 values are, as they stand, the lane's operand of the P.V MFMA.
+// Its other operand is V^T, staged per wave through LDS.  Row maxima, row sums and the partial
+// P.V products are combined across the 4 waves through LDS (integer partial sums: exact).
+// Every floating-point value that decides an int8 code follows one fixed sequence of binary32
+// operations; exp and the row sum are evaluated in binary64 and rounded once.
+#include "samp_common.h"
+#include <hip/hip_ext.h>
+
+namespace samp {
+namespace {
+
+constexpr int QB = 32;                 // queries per block
+constexpr int VT_STRIDE_I8 = 36;       // bytes per V^T row (32 keys + pad), int8
+constexpr int VT_STRIDE_F16 = 72;      // bytes per V^T row (32 keys + pad), fp16
+
+struct SeqInfo { int t0, n; };
+__device__ __forceinline__ SeqInfo seq_info(const int *cu, int b, int max_len)
+{
+    if (cu) { const int t0 = cu[b]; return {t0, cu[b + 1] - t0}; }
+    return {b * max_len, max_len};
+}
+
+template <int NT>
+__global__ __launch_bounds__(256) void attention_i8_kernel(const int8_t *__restrict__ qkv, const int *__restrict__ cu,
+                                                           int max_len, int H, float m_sc, float inv_sp, float m_ctx,
+                                                           int8_t *__restrict__ ctx)
+{
+    __shared__ __attribute__((aligned(16))) int8_t vt[4][NT][64 * VT_STRIDE_I8];
+    __shared__ __attribute__((aligned(16))) int so[4][QB][64];
+    __shared__ float smax[4][QB];
+    __shared__ double ssum[4][QB];
+
+    const SeqInfo sq = seq_info(cu, blockIdx.z, max_len);
+    const int q0 = blockIdx.x * QB;
+    if (q0 >= sq.n) return;
+    const int n = sq.n, head = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, g = lane >> 5;
+    const size_t ld = (size_t)3 * H;
+    const int8_t *base = qkv + (size_t)sq.t0 * ld + head * 64;
+
+    // Q strip: second MFMA operand, lane (query r, half g) holds 16 consecutive bytes of the head dim
+    const int qrow = min(q0 + r, n - 1);
+    v4i qf[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ks++) qf[ks] = *reinterpret_cast<const v4i *>(base + (size_t)qrow * ld + ks * 32 + g * 16);
+
+    float sc[NT][16];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < NT; i++) {
+        const int j0 = (w + 4 * i) * 32;
+        if (j0 < n) {                                           // wave-uniform
+            const int krow = min(j0 + r, n - 1);
+            const int8_t *kp = base + (size_t)krow * ld + H;
+            v16i acc;
+#pragma unroll
+            for (int e = 0; e < 16; e++) acc[e] = 0;
+#pragma unroll
+            for (int ks = 0; ks < 2; ks++)
+                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(*reinterpret_cast<const v4i *>(kp + ks * 32 + g * 16), qf[ks], acc, 0, 0, 0);
+            // stage V^T of this key tile: lane copies 2 x 16 channels of one key, byte by byte
+            const int8_t *vp = base + 2 * H;
+#pragma unroll
+            for (int u = 0; u < 2; u++) {
+                const int idx = lane + 64 * u, key = idx >> 2, c0 = (idx & 3) * 16;
+                const v4i v = *reinterpret_cast<const v4i *>(vp + (size_t)min(j0 + key, n - 1) * ld + c0);
+#pragma unroll
+                for (int e = 0; e < 16; e++)
+                    vt[w][i][(c0 + e) * VT_STRIDE_I8 + key] = (int8_t)(v[e >> 2] >> (8 * (e & 3)));
+            }
+#pragma unroll
+            for (int e = 0; e < 16; e++) {
+                const int key = j0 + 8 * (e >> 2) + 4 * g + (e & 3);
+                sc[i][e] = key < n ? (float)acc[e] * m_sc : -INFINITY;
+                mx = __builtin_fmaxf(mx, sc[i][e]);
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 16; e++) sc[i][e] = -INFINITY;
+        }
+    }
+    mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32, 64));
+    if (g == 0) smax[w][r] = mx;
+    __syncthreads();
+    mx = __builtin_fmaxf(__builtin_fmaxf(smax[0][r], smax[1][r]), __builtin_fmaxf(smax[2][r], smax[3][r]));
+
+    double part = 0.0;
+#pragma unroll
+    for (int i = 0; i < NT; i++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+            const float ev = (float)exp((double)(sc[i][e] - mx));     // exp(-inf) = 0 for masked keys
+            sc[i][e] = ev;
+            part += (double)ev;
+        }
+    part += __shfl_xor(part, 32, 64);
+    if (g == 0) ssum[w][r] = part;
+    __syncthreads();
+    const float S = (float)(((ssum[0][r] + ssum[1][r]) + ssum[2][r]) + ssum[3][r]);
+    const float rS = __fdiv_rn(1.0f, S);
+
+    v16i o[2];
+#pragma unroll
+    for (int cb = 0; cb < 2; cb++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) o[cb][e] = 0;
+#pragma unroll
+    for (int i = 0; i < NT; i++) {
+        if ((w + 4 * i) * 32 < n) {
+            v4i pf;
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                int c[4];
+#pragma unroll
+                for (int t = 0; t < 4; t++) c[t] = qcode((sc[i][4 * q + t] * rS) * inv_sp);
+                pf[q] = pack4(c[0], c[1], c[2], c[3]);
+            }
+#pragma unroll
+            for (int cb = 0; cb < 2; cb++) {
+                v4i vf;
+#pragma unroll
+                for (int q = 0; q < 4; q++)
+                    vf[q] = *reinterpret_cast<const int *>(&vt[w][i][(cb * 32 + r) * VT_STRIDE_I8 + 8 * q + 4 * g]);
+                o[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(pf, vf, o[cb], 0, 0, 0);
+            }
+        }
+    }
+    // partial context of this wave: lane holds channel cb*32 + r and queries 8q + 4g + t
+#pragma unroll
+    for (int cb = 0; cb < 2; cb++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) so[w][8 * (e >> 2) + 4 * g + (e & 3)][cb * 32 + r] = o[cb][e];
+    __syncthreads();
+
+    const int query = tid >> 3, c0 = (tid & 7) * 8;
+    if (q0 + query < n) {
+        int codes[8];
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+            const int O = ((so[0][query][c0 + e] + so[1][query][c0 + e]) + so[2][query][c0 + e]) + so[3][query][c0 + e];
+            codes[e] = qcode((float)O * m_ctx);
+        }
+        v2i pk = {pack4(codes[0], codes[1], codes[2], codes[3]), pack4(codes[4], codes[5], codes[6], codes[7])};
+        *reinterpret_cast<v2i *>(ctx + (size_t)(sq.t0 + q0 + query) * H + head * 64 + c0) = pk;
+    }
+}
+
+// FP16 flavour: fp16 q, k, v; binary32 scores, fast exp; P rounded to fp16 before P.V; binary32
+// accumulation of P.V.  Optionally records the largest softmax output (calibration of the P step).
+template <int NT>
+__global__ __launch_bounds__(256) void attention_f16_kernel(const __half *__restrict__ qkv, const int *__restrict__ cu,
+                                                            int max_len, int H, float scale, __half *__restrict__ ctx,
+                                                            float *__restrict__ p_absmax)
+{
+    __shared__ __attribute__((aligned(16))) char vt[4][NT][64 * VT_STRIDE_F16];
+    __shared__ __attribute__((aligned(16))) float so[4][QB][64];
+    __shared__ float smax[4][QB];
+    __shared__ float ssum[4][QB];
+
+    const SeqInfo sq = seq_info(cu, blockIdx.z, max_len);
+    const int q0 = blockIdx.x * QB;
+    if (q0 >= sq.n) return;
+    const int n = sq.n, head = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, g = lane >> 5;
+    const size_t ld = (size_t)3 * H;
+    const __half *base = qkv + (size_t)sq.t0 * ld + head * 64;
+
+    const int qrow = min(q0 + r, n - 1);
+    v8h qf[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ks++) qf[ks] = *reinterpret_cast<const v8h *>(base + (size_t)qrow * ld + ks * 16 + g * 8);
+
+    float sc[NT][16];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < NT; i++) {
+        const int j0 = (w + 4 * i) * 32;
+        if (j0 < n) {
+            const int krow = min(j0 + r, n - 1);
+            const __half *kp = base + (size_t)krow * ld + H;
+            v16f acc;
+#pragma unroll
+            for (int e = 0; e < 16; e++) acc[e] = 0.0f;
+#pragma unroll
+            for (int ks = 0; ks < 4; ks++)
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(*reinterpret_cast<const v8h *>(kp + ks * 16 + g * 8), qf[ks], acc, 0, 0, 0);
+            // stage V^T: lane copies 4 x 8 channels of one key
+            const __half *vp = base + 2 * H;
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                const int idx = lane + 64 * u, key = idx >> 3, c0 = (idx & 7) * 8;
+                const v8h v = *reinterpret_cast<const v8h *>(vp + (size_t)min(j0 + key, n - 1) * ld + c0);
+#pragma unroll
+                for (int e = 0; e < 8; e++)
+                    *reinterpret_cast<_Float16 *>(&vt[w][i][(c0 + e) * VT_STRIDE_F16 + key * 2]) = v[e];
+            }
+#pragma unroll
+            for (int e = 0; e < 16; e++) {
+                const int key = j0 + 8 * (e >> 2) + 4 * g + (e & 3);
+                sc[i][e] = key < n ? acc[e] * scale : -INFINITY;
+                mx = __builtin_fmaxf(mx, sc[i][e]);
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 16; e++) sc[i][e] = -INFINITY;
+        }
+    }
+    mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32, 64));
+    if (g == 0) smax[w][r] = mx;
+    __syncthreads();
+    mx = __builtin_fmaxf(__builtin_fmaxf(smax[0][r], smax[1][r]), __builtin_fmaxf(smax[2][r], smax[3][r]));
+
+    float part = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NT; i++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+            const float ev = __builtin_amdgcn_exp2f((sc[i][e] - mx) * 1.44269504088896341f);
+            sc[i][e] = ev;
+            part += ev;
+        }
+    part += __shfl_xor(part, 32, 64);
+    if (g == 0) ssum[w][r] = part;
+    __syncthreads();
+    const float S = ((ssum[0][r] + ssum[1][r]) + ssum[2][r]) + ssum[3][r];
+    const float rS = __fdiv_rn(1.0f, S);
+    if (p_absmax && w == 0 && g == 0 && q0 + r < n)              // the row's largest P is exp(0) / S
+        atomicMax(reinterpret_cast<int *>(p_absmax), __float_as_int((float)(_Float16)rS));
+
+    v16f o[2];
+#pragma unroll
+    for (int cb = 0; cb < 2; cb++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) o[cb][e] = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NT; i++) {
+        if ((w + 4 * i) * 32 < n) {
+#pragma unroll
+            for (int hf = 0; hf < 2; hf++) {                    // keys 8q+4g+t for q in {2hf, 2hf+1}
+                v8h pf;
+#pragma unroll
+                for (int e = 0; e < 8; e++) pf[e] = to_half(sc[i][8 * hf + e] * rS);
+#pragma unroll
+                for (int cb = 0; cb < 2; cb++) {
+                    const char *rowp = &vt[w][i][(cb * 32 + r) * VT_STRIDE_F16];
+                    const v4h lo = *reinterpret_cast<const v4h *>(rowp + (16 * hf + 4 * g) * 2);
+                    const v4h hi = *reinterpret_cast<const v4h *>(rowp + (16 * hf + 8 + 4 * g) * 2);
+                    const v8h vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(pf, vf, o[cb], 0, 0, 0);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int cb = 0; cb < 2; cb++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) so[w][8 * (e >> 2) + 4 * g + (e & 3)][cb * 32 + r] = o[cb][e];
+    __syncthreads();
+
+    const int query = tid >> 3, c0 = (tid & 7) * 8;
+    if (q0 + query < n) {
+        v8h outv;
+#pragma unroll
+        for (int e = 0; e < 8; e++)
+            outv[e] = to_half(((so[0][query][c0 + e] + so[1][query][c0 + e]) + so[2][query][c0 + e]) + so[3][query][c0 + e]);
+        *reinterpret_cast<v8h *>(ctx + (size_t)(sq.t0 + q0 + query) * H + head * 64 + c0) = outv;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_attention_i8(const int8_t *qkv, const int *cu, int B, int max_len, int H, int heads, float m_sc,
+                               float inv_sp, float m_ctx, int8_t *ctx, hipStream_t st, const Timing *tm)
+{
+    dim3 grid((max_len + QB - 1) / QB, heads, B), block(256);
+    hipEvent_t e0 = tm ? tm->start : nullptr, e1 = tm ? tm->stop : nullptr;
+    if (max_len <= 128)
+        hipExtLaunchKernelGGL((attention_i8_kernel<1>), grid, block, 0, st, e0, e1, 0, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx);
+    else if (max_len <= 256)
+        hipExtLaunchKernelGGL((attention_i8_kernel<2>), grid, block, 0, st, e0, e1, 0, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx);
+    else
+        hipExtLaunchKernelGGL((attention_i8_kernel<4>), grid, block, 0, st, e0, e1, 0, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx);
+    return hipGetLastError();
+}
+
+hipError_t launch_attention_f16(const __half *qkv, const int *cu, int B, int max_len, int H, int heads, float scale,
+                                __half *ctx, float *p_absmax, hipStream_t st, const Timing *tm)
+{
+    dim3 grid((max_len + QB - 1) / QB, heads, B), block(256);
+    hipEvent_t e0 = tm ? tm->start : nullptr, e1 = tm ? tm->stop : nullptr;
+    if (max_len <= 128)
+        hipExtLaunchKernelGGL((attention_f16_kernel<1>), grid, block, 0, st, e0, e1, 0, qkv, cu, max_len, H, scale, ctx, p_absmax);
+    else if (max_len <= 256)
+        hipExtLaunchKernelGGL((attention_f16_kernel<2>), grid, block, 0, st, e0, e1, 0, qkv, cu, max_len, H, scale, ctx, p_absmax);
+    else
+        hipExtLaunchKernelGGL((attention_f16_kernel<4>), grid, block, 0, st, e0, e1, 0, qkv, cu, max_len, H, scale, ctx, p_absmax);
+    return hipGetLastError();
+}
+
+}  // namespace samp

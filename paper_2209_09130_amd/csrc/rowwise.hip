@@ -1,0 +1,338 @@
+// Memory-bound kernels of the encoder: the fused dequantise + bias + residual + LayerNorm (+ quantise)
+// step of Section 3.2, padding removal on entry, entry quantisation, per-channel weight quantisation
+// and epilogue-table folding at create time, and the absmax taps of the min-max calibration.
+// All of them move each byte once with coalesced 4..16-byte accesses; reductions stay inside a wave.
+#include "samp_common.h"
+#include <hip/hip_ext.h>
+
+namespace samp {
+namespace {
+
+// ---------------------------------------------------------------------------------------------
+// Fused step: one wave per token row, lane l owns channels 4l..4l+3 of every 256-channel slab.
+//   z = fmaf(in_q, s_in, bias) or in + bias;  z = fmaf(res_q, s_res, z) or z + res
+//   mean / variance in binary64 (two passes over registers), rounded once to binary32
+//   y = fmaf((z - mu) * rstd, gamma, beta);  out = rne(y / s_out) or fp16(y)
+// ---------------------------------------------------------------------------------------------
+template <int NJ, bool IN_I8, bool RES_I8, bool OUT_I8>
+__global__ __launch_bounds__(256) void add_ln_kernel(AddLnArgs a)
+{
+    const int M = a.rows.dev_rows ? *a.rows.dev_rows : a.rows.host_rows;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= M) return;
+    const int lane = threadIdx.x & 63, H = a.H;
+    const size_t base = (size_t)row * H;
+
+    float z[NJ][4];
+    double sum = 0.0;
+#pragma unroll
+    for (int j = 0; j < NJ; j++) {
+        const int c = j * 256 + lane * 4;
+        if (c < H) {
+            const v4f bb = *reinterpret_cast<const v4f *>(a.bias + c);
+            float t[4];
+            if (IN_I8) {
+                const int p = *reinterpret_cast<const int *>((const int8_t *)a.in + base + c);
+#pragma unroll
+                for (int e = 0; e < 4; e++) t[e] = __builtin_fmaf((float)(int8_t)(p >> (8 * e)), a.s_in, bb[e]);
+            } else {
+                const v4h p = *reinterpret_cast<const v4h *>((const __half *)a.in + base + c);
+#pragma unroll
+                for (int e = 0; e < 4; e++) t[e] = (float)p[e] + bb[e];
+            }
+            if (RES_I8) {
+                const int p = *reinterpret_cast<const int *>((const int8_t *)a.res + base + c);
+#pragma unroll
+                for (int e = 0; e < 4; e++) z[j][e] = __builtin_fmaf((float)(int8_t)(p >> (8 * e)), a.s_res, t[e]);
+            } else {
+                const v4h p = *reinterpret_cast<const v4h *>((const __half *)a.res + base + c);
+#pragma unroll
+                for (int e = 0; e < 4; e++) z[j][e] = t[e] + (float)p[e];
+            }
+#pragma unroll
+            for (int e = 0; e < 4; e++) sum += (double)z[j][e];
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; e++) z[j][e] = 0.0f;
+        }
+    }
+    const double mu = wave_sum(sum) / (double)H;
+    double sq = 0.0;
+#pragma unroll
+    for (int j = 0; j < NJ; j++) {
+        if (j * 256 + lane * 4 < H) {
+#pragma unroll
+            for (int e = 0; e < 4; e++) { const double d = (double)z[j][e] - mu; sq += d * d; }
+        }
+    }
+    const double var = wave_sum(sq) / (double)H;
+    const float mu32 = (float)mu;
+    const float rstd32 = (float)(1.0 / sqrt(var + (double)a.eps));
+    const float inv_s = OUT_I8 ? 1.0f / a.s_out : 0.0f;
+    const size_t obase = (size_t)(a.row_map ? a.row_map[row] : row) * H;
+    float amax = 0.0f;
+#pragma unroll
+    for (int j = 0; j < NJ; j++) {
+        const int c = j * 256 + lane * 4;
+        if (c < H) {
+            const v4f gg = *reinterpret_cast<const v4f *>(a.gamma + c);
+            const v4f be = *reinterpret_cast<const v4f *>(a.beta + c);
+            float y[4];
+#pragma unroll
+            for (int e = 0; e < 4; e++) y[e] = __builtin_fmaf((z[j][e] - mu32) * rstd32, gg[e], be[e]);
+            if (OUT_I8) {
+                *reinterpret_cast<int *>((int8_t *)a.out + obase + c) =
+                    pack4(qcode(y[0] * inv_s), qcode(y[1] * inv_s), qcode(y[2] * inv_s), qcode(y[3] * inv_s));
+            } else {
+                const v4h h = {to_half(y[0]), to_half(y[1]), to_half(y[2]), to_half(y[3])};
+                *reinterpret_cast<v4h *>((__half *)a.out + obase + c) = h;
+                if (a.absmax_out) {
+#pragma unroll
+                    for (int e = 0; e < 4; e++) amax = __builtin_fmaxf(amax, __builtin_fabsf((float)h[e]));
+                }
+            }
+        }
+    }
+    if (!OUT_I8 && a.absmax_out) {
+        amax = wave_max(amax);
+        if (lane == 0) atomicMax(reinterpret_cast<int *>(a.absmax_out), __float_as_int(amax));   // values >= 0
+    }
+}
+
+template <int NJ>
+hipError_t launch_add_ln_nj(const AddLnArgs &a, hipStream_t st, const Timing *tm)
+{
+    dim3 grid((a.rows.host_rows + 3) / 4), block(256);
+    hipEvent_t e0 = tm ? tm->start : nullptr, e1 = tm ? tm->stop : nullptr;
+#define SAMP_LN_CASE(I, R, O)                                                                              \
+    if (a.in_i8 == I && a.res_i8 == R && a.out_i8 == O) {                                                  \
+        hipExtLaunchKernelGGL((add_ln_kernel<NJ, I, R, O>), grid, block, 0, st, e0, e1, 0, a);             \
+        return hipGetLastError();                                                                          \
+    }
+    SAMP_LN_CASE(true, true, true) SAMP_LN_CASE(true, true, false) SAMP_LN_CASE(false, false, true)
+    SAMP_LN_CASE(false, false, false) SAMP_LN_CASE(true, false, true) SAMP_LN_CASE(true, false, false)
+    SAMP_LN_CASE(false, true, true) SAMP_LN_CASE(false, true, false)
+#undef SAMP_LN_CASE
+    return hipErrorInvalidValue;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Sequence offsets: cu[b] = number of valid tokens before sequence b (exclusive prefix sum of the
+// mask's row sums), cu[B] = T.  One block; wave w sums the rows w, w+16, ...
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void seq_offsets_kernel(const int *__restrict__ mask, int B, int S, int *__restrict__ cu)
+{
+    extern __shared__ int len[];                    // [B]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int b = wave; b < B; b += 16) {
+        int s = 0;
+        if (mask) { for (int i = lane; i < S; i += 64) s += mask[(size_t)b * S + i] != 0; }
+        else s = (lane == 0) ? S : 0;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+        if (lane == 0) len[b] = s;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int b = 0; b < B; b++) { cu[b] = run; run += len[b]; }
+        cu[B] = run;
+    }
+}
+
+// Padding removal: one wave per (b, s) row.  Valid rows are copied (or quantised) to packed row
+// cu[b] + s and remember where they came from; padded rows zero the matching row of the final output.
+__global__ __launch_bounds__(256) void pack_rows_kernel(const __half *__restrict__ hidden, const int *__restrict__ cu,
+                                                        int B, int S, int H, float s_x, void *__restrict__ packed,
+                                                        int *__restrict__ row_map, __half *__restrict__ out_zero_pad)
+{
+    const int rowid = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (rowid >= B * S) return;
+    const int lane = threadIdx.x & 63;
+    const int b = rowid / S, s = rowid - b * S;
+    const int t0 = cu[b], n = cu[b + 1] - t0;
+    if (s >= n) {
+        if (out_zero_pad)
+            for (int c = lane * 8; c < H; c += 512) *reinterpret_cast<v4i *>(out_zero_pad + (size_t)rowid * H + c) = v4i{0, 0, 0, 0};
+        return;
+    }
+    const int t = t0 + s;
+    if (lane == 0) row_map[t] = rowid;
+    const __half *src = hidden + (size_t)rowid * H;
+    if (s_x > 0.0f) {
+        const float inv_s = 1.0f / s_x;
+        for (int c = lane * 8; c < H; c += 512) {
+            const v8h v = *reinterpret_cast<const v8h *>(src + c);
+            v2i o;
+            o.x = pack4(qcode((float)v[0] * inv_s), qcode((float)v[1] * inv_s), qcode((float)v[2] * inv_s), qcode((float)v[3] * inv_s));
+            o.y = pack4(qcode((float)v[4] * inv_s), qcode((float)v[5] * inv_s), qcode((float)v[6] * inv_s), qcode((float)v[7] * inv_s));
+            *reinterpret_cast<v2i *>((int8_t *)packed + (size_t)t * H + c) = o;
+        }
+    } else {
+        for (int c = lane * 8; c < H; c += 512)
+            *reinterpret_cast<v4i *>((__half *)packed + (size_t)t * H + c) = *reinterpret_cast<const v4i *>(src + c);
+    }
+}
+
+// Entry quantisation without padding removal: code = rne(x * (1/s_x)), 8 elements per thread.
+__global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *__restrict__ x, size_t n8, float s_x,
+                                                            int8_t *__restrict__ out)
+{
+    const float inv_s = 1.0f / s_x;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (size_t)gridDim.x * 256) {
+        const v8h v = *reinterpret_cast<const v8h *>(x + i * 8);
+        v2i o;
+        o.x = pack4(qcode((float)v[0] * inv_s), qcode((float)v[1] * inv_s), qcode((float)v[2] * inv_s), qcode((float)v[3] * inv_s));
+        o.y = pack4(qcode((float)v[4] * inv_s), qcode((float)v[5] * inv_s), qcode((float)v[6] * inv_s), qcode((float)v[7] * inv_s));
+        *reinterpret_cast<v2i *>(out + i * 8) = o;
+    }
+}
+
+// Per-output-channel weight quantisation (create time): one block per row of W[N,K].
+//   s_w = absmax / 127 (1 for an all-zero row), code = rne(w / s_w) with a true binary32 division.
+__global__ __launch_bounds__(256) void quantize_weight_kernel(const __half *__restrict__ W, int K, int8_t *__restrict__ Wq,
+                                                              float *__restrict__ s_w)
+{
+    __shared__ float red[4];
+    const int n = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const __half *row = W + (size_t)n * K;
+    float amax = 0.0f;
+    for (int k = threadIdx.x; k < K; k += 256) amax = __builtin_fmaxf(amax, __builtin_fabsf((float)row[k]));
+    amax = wave_max(amax);
+    if (lane == 0) red[wave] = amax;
+    __syncthreads();
+    amax = __builtin_fmaxf(__builtin_fmaxf(red[0], red[1]), __builtin_fmaxf(red[2], red[3]));
+    const float s = amax > 0.0f ? __fdiv_rn(amax, 127.0f) : 1.0f;
+    if (threadIdx.x == 0) s_w[n] = s;
+    for (int k = threadIdx.x; k < K; k += 256) Wq[(size_t)n * K + k] = (int8_t)qcode(__fdiv_rn((float)row[k], s));
+}
+
+// Epilogue tables: m[n] = s_in * s_w[n] / s_out, b[n] = bias[n] / s_out, formed in binary64 and
+// rounded once (s_out = 1 and bias = nullptr give the plain dequantising multiplier).
+__global__ void fold_kernel(float s_in, const float *__restrict__ s_w, const float *__restrict__ bias, float s_out, int N,
+                            float *__restrict__ m, float *__restrict__ b)
+{
+    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= N) return;
+    m[n] = (float)((double)s_in * (double)s_w[n] / (double)s_out);
+    if (b) b[n] = bias ? (float)((double)bias[n] / (double)s_out) : 0.0f;
+}
+
+// Calibration tap: running absmax of an fp16 [rows, cols] view with leading dimension ld.
+__global__ __launch_bounds__(256) void absmax_f16_kernel(const __half *__restrict__ x, int host_rows,
+                                                         const int *__restrict__ dev_rows, int cols, int ld,
+                                                         float *__restrict__ slot)
+{
+    const int rows = dev_rows ? *dev_rows : host_rows;
+    float amax = 0.0f;
+    const int c8 = cols / 8;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < (size_t)rows * c8; i += (size_t)gridDim.x * 256) {
+        const size_t r = i / c8, c = (i - r * c8) * 8;
+        const v8h v = *reinterpret_cast<const v8h *>(x + r * ld + c);
+#pragma unroll
+        for (int e = 0; e < 8; e++) amax = __builtin_fmaxf(amax, __builtin_fabsf((float)v[e]));
+    }
+    amax = wave_max(amax);
+    if ((threadIdx.x & 63) == 0) atomicMax(reinterpret_cast<int *>(slot), __float_as_int(amax));
+}
+
+// The FFN1 epilogue's decision step on its own: codes = rne(GELU(y) / s_out); optionally also the
+// fast-path GELU values, so that their error bound can be checked from outside.
+__global__ __launch_bounds__(256) void gelu_quant_kernel(const float *__restrict__ y, size_t n, float inv_s,
+                                                         int8_t *__restrict__ codes, float *__restrict__ fast)
+{
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+        const float v = y[i];
+        codes[i] = (int8_t)gelu_quant_code(v, inv_s);
+        if (fast) fast[i] = gelu_fast(v);
+    }
+}
+
+__global__ void fill_f32_kernel(float *p, int n, float v)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+}  // namespace
+
+hipError_t launch_add_ln(const AddLnArgs &a, hipStream_t st, const Timing *tm)
+{
+    const int nj = (a.H + 255) / 256;
+    switch (nj) {
+    case 1: return launch_add_ln_nj<1>(a, st, tm);
+    case 2: return launch_add_ln_nj<2>(a, st, tm);
+    case 3: return launch_add_ln_nj<3>(a, st, tm);
+    case 4: return launch_add_ln_nj<4>(a, st, tm);
+    case 5: return launch_add_ln_nj<5>(a, st, tm);
+    case 6: return launch_add_ln_nj<6>(a, st, tm);
+    case 7: return launch_add_ln_nj<7>(a, st, tm);
+    case 8: return launch_add_ln_nj<8>(a, st, tm);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_quantize_weight(const __half *W, int N, int K, int8_t *Wq, float *s_w, hipStream_t st)
+{
+    hipLaunchKernelGGL(quantize_weight_kernel, dim3(N), dim3(256), 0, st, W, K, Wq, s_w);
+    return hipGetLastError();
+}
+
+hipError_t launch_fold(const float *, float s_in, const float *s_w, const float *bias, float s_out, int N, float *m,
+                       float *b, hipStream_t st)
+{
+    hipLaunchKernelGGL(fold_kernel, dim3((N + 255) / 256), dim3(256), 0, st, s_in, s_w, bias, s_out, N, m, b);
+    return hipGetLastError();
+}
+
+hipError_t launch_seq_offsets(const int *mask, int B, int S, int *cu, hipStream_t st)
+{
+    hipLaunchKernelGGL(seq_offsets_kernel, dim3(1), dim3(1024), (size_t)B * sizeof(int), st, mask, B, S, cu);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack_rows(const __half *hidden, const int *cu, int B, int S, int H, float s_x, void *packed,
+                            int *row_map, __half *out_zero_pad, hipStream_t st, const Timing *tm)
+{
+    dim3 grid((B * S + 3) / 4), block(256);
+    hipExtLaunchKernelGGL(pack_rows_kernel, grid, block, 0, st, tm ? tm->start : nullptr, tm ? tm->stop : nullptr, 0,
+                          hidden, cu, B, S, H, s_x, packed, row_map, out_zero_pad);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_rows(const __half *x, size_t n, float s_x, int8_t *out, hipStream_t st, const Timing *tm)
+{
+    const size_t n8 = n / 8;
+    size_t blocks = (n8 + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipExtLaunchKernelGGL(quantize_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, st, tm ? tm->start : nullptr,
+                          tm ? tm->stop : nullptr, 0, x, n8, s_x, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_absmax_f16(const __half *x, Rows rows, int cols, int ld, float *slot, hipStream_t st)
+{
+    size_t work = (size_t)rows.host_rows * (cols / 8);
+    size_t blocks = (work + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(absmax_f16_kernel, dim3((unsigned)blocks), dim3(256), 0, st, x, rows.host_rows, rows.dev_rows, cols,
+                       ld, slot);
+    return hipGetLastError();
+}
+
+hipError_t launch_gelu_quant(const float *y, size_t n, float inv_s, int8_t *codes, float *fast, hipStream_t st)
+{
+    size_t blocks = (n + 255) / 256;
+    if (blocks > 16384) blocks = 16384;
+    hipLaunchKernelGGL(gelu_quant_kernel, dim3((unsigned)blocks), dim3(256), 0, st, y, n, inv_s, codes, fast);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_f32(float *p, int n, float v, hipStream_t st)
+{
+    hipLaunchKernelGGL(fill_f32_kernel, dim3((n + 255) / 256), dim3(256), 0, st, p, n, v);
+    return hipGetLastError();
+}
+
+}  // namespace samp

@@ -1,0 +1,65 @@
+"""The C-ABI library loads without a GPU, exports every symbol the header declares, and turns
+invalid arguments into error codes on the host (no kernel is launched here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "samp.h")
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_2209_09130_amd as P
+    from paper_2209_09130_amd import build as B
+    if not os.path.exists(P.lib_path()):
+        B.build(force=True)
+    return P.lib()
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"SAMP_API[^;(]*?\b(samp_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_entry_points():
+    names = declared_symbols()
+    for must in ("samp_encoder_create", "samp_encoder_forward", "samp_encoder_workspace_bytes",
+                 "samp_encoder_destroy", "samp_last_error"):
+        assert must in names
+    assert len(names) >= 15
+
+
+def test_library_exports_every_declared_symbol(L):
+    for name in declared_symbols():
+        assert hasattr(L, name), name
+
+
+def test_invalid_arguments_become_error_codes_on_the_host(L):
+    from paper_2209_09130_amd.binding import _Config
+    L.samp_encoder_arena_bytes.restype = C.c_size_t
+    modes = (C.c_uint8 * 2)(3, 0)
+    ok = _Config(2, 768, 12, 3072, 8, 128, 1e-12)
+    assert L.samp_encoder_arena_bytes(C.byref(ok), modes) > 2 * (768 * 768 * 4 + 2 * 768 * 3072)
+    bad_head = _Config(2, 768, 8, 3072, 8, 128, 1e-12)
+    assert L.samp_encoder_arena_bytes(C.byref(bad_head), modes) == 0
+    assert b"head size" in L.samp_last_error()
+    bad_seq = _Config(2, 768, 12, 3072, 8, 1024, 1e-12)
+    assert L.samp_encoder_arena_bytes(C.byref(bad_seq), modes) == 0
+    assert L.samp_encoder_arena_bytes(C.byref(ok), (C.c_uint8 * 2)(7, 0)) == 0
+    assert L.samp_encoder_arena_bytes(None, modes) == 0
+    # step entry points reject NULL pointers and unsupported shapes before touching the device
+    assert L.samp_gemm_i8_i32(None, None, None, 1, 128, 64, None) == -1
+    buf = (C.c_char * 64)()
+    assert L.samp_gemm_i8_i32(buf, buf, buf, 1, 100, 64, None) == -2
+    assert L.samp_gemm_i8_i32(buf, buf, buf, 1, 128, 60, None) == -2
+    assert L.samp_add_ln(None, 0, C.c_float(1), None, None, 0, C.c_float(1), None, None, C.c_float(0), None, 0,
+                         C.c_float(1), 1, 768, None) == -1
+    assert L.samp_encoder_workspace_bytes(None, 1, 1) == 0
+    assert L.samp_encoder_destroy(None) == 0
+    out = C.c_void_p()
+    assert L.samp_encoder_create(C.byref(ok), modes, None, None, None, C.c_size_t(0), None, C.byref(out)) == -1
+    assert L.samp_encoder_forward(None, None, None, 1, 1, None, None, C.c_size_t(0), None) == -1

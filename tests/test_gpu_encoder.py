@@ -1,0 +1,289 @@
+"""GPU parity of the whole encoder against the CPU oracle, through samp_encoder_create / forward.
+
+Bar: layer outputs within max-abs 2e-2 and mean-abs 2e-3 of the oracle.
+  * FULL_INT8 stacks (every decision reproducible) and FP16 stacks (no decisions) meet it end to end
+    on every element; FULL_INT8 outputs are bit-identical.
+  * A layer that mixes an FP16 block with a quantised one can differ from the oracle by one int8 code
+    at isolated elements of the quantised residual stream: binary32 MFMA accumulation order against
+    binary64 in the oracle decides an fp16 rounding, which decides a code; both codes are valid
+    roundings of values that agree to ~1e-5.  Such a layer is required to have mean-abs <= 2e-3 on
+    all elements, max-abs <= 2e-2 on all but a fraction <= 2e-3 of them, nothing off by more than a
+    few code steps ("flips" below).
+  * A flipped code perturbs the next layer's input and quantisers amplify perturbations (each
+    flipped element of the residual stream flips a few more codes per layer), so after many mixed
+    layers two correct implementations decorrelate at the level of the quantisation noise itself.
+    Deep mixed stacks are therefore checked layer by layer with the oracle's own layer input
+    (teacher forcing), plus an end-to-end validity check: the GPU result must be as close to the
+    unquantised reference as the oracle's result is.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import samp_workloads as W
+from samp_workloads import FP16, MHA_INT8, FFN_INT8, FULL_INT8
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, MEAN_ABS = 2e-2, 2e-3
+
+
+@pytest.fixture(scope="module")
+def P():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2209_09130_amd as P
+    P.lib()
+    return P
+
+
+def args(w):
+    return (w.layers, w.hidden, w.heads, w.ffn, w.ln_eps)
+
+
+def run_gpu(P, w, wts, sc, hid, mask):
+    import torch
+    enc = P.Encoder(*args(w), w.modes, wts, sc, max_batch=hid.shape[0], max_seq=hid.shape[1])
+    h = torch.from_numpy(hid).cuda()
+    m = None if mask is None else torch.from_numpy(mask).cuda()
+    out = enc.forward(h, m)
+    torch.cuda.synchronize()
+    out2 = enc.forward(h, m)            # determinism: a second run is bit-identical
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+    enc.close()
+    return out.cpu().numpy()
+
+
+def layer_args(w, l):
+    return (1, w.hidden, w.heads, w.ffn, w.ln_eps)
+
+
+def teacher_forced_layers(P, w, wts, sc, hid, lens, mask, label):
+    """Every layer on its own, GPU and oracle fed with the oracle's output of the previous layer."""
+    x = hid
+    for l in range(w.layers):
+        w1 = W.Workload(f"{w.name}.L{l}", 1, w.hidden, w.heads, w.ffn, hid.shape[0], hid.shape[1], (w.modes[l],),
+                        ln_eps=w.ln_eps)
+        want = oracle.Encoder(*layer_args(w, l), w1.modes, wts[l:l + 1], sc[l:l + 1]).forward(x, lens)
+        got = run_gpu(P, w1, wts[l:l + 1], sc[l:l + 1], x, mask)
+        compare(got, want, lens, STRICT[w.modes[l]], f"{label} layer {l} {W.MODE_NAMES[w.modes[l]]} (teacher forced)")
+        x = want
+
+
+def valid_against_reference(got, want, ref, lens, label):
+    """End-to-end check where codes may legitimately differ: both results are quantised evaluations of
+    the same model, so both must sit at the same distance from the unquantised reference."""
+    dg, dw, dd = [], [], []
+    for b in range(got.shape[0]):
+        n = int(lens[b])
+        assert not got[b, n:].any()
+        g, o, r = (a[b, :n].astype(np.float64).ravel() for a in (got, want, ref))
+        dg.append(np.abs(g - r)); dw.append(np.abs(o - r)); dd.append(np.abs(g - o))
+    dg, dw, dd = map(np.concatenate, (dg, dw, dd))
+    print(f"[parity] {label}: |gpu-ref| mean {dg.mean():.4g}  |oracle-ref| mean {dw.mean():.4g}  "
+          f"|gpu-oracle| mean {dd.mean():.4g} max {dd.max():.4g}", flush=True)
+    assert 0.8 <= dg.mean() / dw.mean() <= 1.25
+    assert dd.mean() <= 2.0 * dw.mean()
+
+
+def compare(got, want, lens, strict, label=""):
+    B, S, H = got.shape
+    diffs = []
+    for b in range(B):
+        n = int(lens[b])
+        assert not got[b, n:].any(), "padded rows must be zero"
+        diffs.append(np.abs(got[b, :n].astype(np.float64) - want[b, :n].astype(np.float64)).ravel())
+    d = np.concatenate(diffs)
+    frac_bad = float((d > MAX_ABS).mean())
+    print(f"[parity] {label}: max {d.max():.4g} mean {d.mean():.4g} frac>{MAX_ABS} {frac_bad:.3g} "
+          f"bit-identical {float((d == 0).mean()):.4f}", flush=True)
+    assert d.mean() <= MEAN_ABS
+    if strict:
+        assert d.max() <= MAX_ABS
+    else:
+        assert frac_bad <= 2e-3
+        assert d.max() <= 0.25
+    return d
+
+
+def small(modes, batch=5, seq=48, varlen=True, layers=None):
+    layers = len(modes) if layers is None else layers
+    return W.Workload("small", layers, 128, 2, 256, batch, seq, tuple(modes), varlen=varlen, min_len=1,
+                      plain_params=False, calib_batch=4, calib_seq=48)
+
+
+STRICT = {FP16: True, FULL_INT8: True, MHA_INT8: False, FFN_INT8: False}
+
+
+@pytest.mark.parametrize("mode", [FP16, FULL_INT8, FFN_INT8, MHA_INT8])
+@pytest.mark.parametrize("varlen", [False, True])
+def test_small_encoder_every_mode(P, mode, varlen):
+    w = small((mode,) * 3, varlen=varlen)
+    wts = W.make_weights(w)
+    hid, lens, mask = W.make_hidden(w)
+    sc = oracle.calibrate(*args(w), wts, W.make_calibration_batch(w))
+    want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid, lens)
+    got = run_gpu(P, w, wts, sc, hid, mask if varlen else None)
+    d = compare(got, want, lens, STRICT[mode], f"small {W.MODE_NAMES[mode]} varlen={varlen}")
+    if mode == FULL_INT8:
+        # every decision on this path is reproducible: the fp16 outputs are bit-identical
+        assert (d == 0).all()
+
+
+@pytest.mark.parametrize("modes", [(FULL_INT8, FP16, FULL_INT8, FFN_INT8), (FP16, MHA_INT8, FFN_INT8, FULL_INT8),
+                                   (FFN_INT8, FULL_INT8, MHA_INT8, FP16)])
+def test_small_encoder_mixed_masks_and_transitions(P, modes):
+    w = small(modes)
+    wts = W.make_weights(w)
+    hid, lens, mask = W.make_hidden(w)
+    sc = oracle.calibrate(*args(w), wts, W.make_calibration_batch(w))
+    want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid, lens)
+    got = run_gpu(P, w, wts, sc, hid, mask)
+    compare(got, want, lens, False, f"small mixed {modes}")
+
+
+def test_padding_is_inert_and_single_token_sequences_work(P):
+    import torch
+    w = small((FULL_INT8, FFN_INT8), batch=4, seq=40)
+    wts = W.make_weights(w)
+    hid, _, _ = W.make_hidden(w)
+    lens = np.array([1, 40, 7, 33], np.int32)
+    mask = (np.arange(w.seq)[None, :] < lens[:, None]).astype(np.int32)
+    sc = oracle.calibrate(*args(w), wts, W.make_calibration_batch(w))
+    got = run_gpu(P, w, wts, sc, hid, mask)
+    hid2 = hid.copy()
+    for b in range(4):
+        hid2[b, lens[b]:] = 123.0
+    got2 = run_gpu(P, w, wts, sc, hid2, mask)
+    assert np.array_equal(got, got2)
+    want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid, lens)
+    compare(got, want, lens, False, "padding")
+
+
+def test_c1_single_layer_bert_base_ffn_int8(P):
+    w = W.config("C1")
+    wts = W.make_weights(w)
+    hid, lens, _ = W.make_hidden(w)
+    sc = oracle.calibrate(*args(w), wts, W.make_calibration_batch(w))
+    want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid, lens)
+    got = run_gpu(P, w, wts, sc, hid, None)
+    compare(got, want, lens, False, "C1")
+
+
+
+@pytest.mark.parametrize("mode", [FULL_INT8, FP16])
+def test_c2_bert_base_12_layers_batch_32_end_to_end(P, mode):
+    """Benchmark configuration, in the launch configuration bench.py times (no mask).  The oracle runs
+    a sample of the 32 sequences (they are independent because all scales are static)."""
+    w = W.config("C2").with_modes(mode)
+    wts = W.make_weights(w)
+    hid, lens, _ = W.make_hidden(w)
+    sc = oracle.calibrate(*args(w), wts, W.make_calibration_batch(w))
+    got = run_gpu(P, w, wts, sc, hid, None)
+    pick = [0, 13, 31]
+    want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid[pick], lens[pick])
+    d = compare(got[pick], want, lens[pick], True, f"C2 {W.MODE_NAMES[mode]}")
+    if mode == FULL_INT8:
+        assert (d == 0).all()
+
+
+@pytest.mark.parametrize("mode", [FFN_INT8, MHA_INT8])
+def test_c2_mixed_precision_modes_layer_by_layer_and_end_to_end(P, mode):
+    w = W.config("C2").with_modes(mode)
+    wts = W.make_weights(w)
+    hid, lens, _ = W.make_hidden(w)
+    sc = oracle.calibrate(*args(w), wts, W.make_calibration_batch(w))
+    pick = [0, 13, 31]
+    # every layer at the benchmark batch size, teacher forced on the sampled sequences
+    teacher_forced_layers(P, w, wts, sc, hid[pick], lens[pick], None, f"C2 {W.MODE_NAMES[mode]}")
+    got = run_gpu(P, w, wts, sc, hid, None)
+    want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid[pick], lens[pick])
+    ref, _ = oracle.reference_forward(*args(w), wts, hid[pick], lens[pick])
+    valid_against_reference(got[pick], want, ref, lens[pick], f"C2 {W.MODE_NAMES[mode]} end to end")
+
+
+def test_c3_variable_length_mixed_mask(P):
+    """Layers 0-5 Fully-Quant, 6-11 FP16, batch 64 with lengths in [16,128]: the quantised half is
+    reproducible, the FP16 half has no decisions, so the whole stack meets the bar end to end."""
+    w = W.config("C3")
+    wts = W.make_weights(w)
+    hid, lens, mask = W.make_hidden(w)
+    sc = oracle.calibrate(*args(w), wts, W.make_calibration_batch(w))
+    got = run_gpu(P, w, wts, sc, hid, mask)
+    pick = [0, 1, int(np.argmin(lens)), int(np.argmax(lens)), 63]
+    want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid[pick], lens[pick])
+    compare(got[pick], want, lens[pick], True, "C3")
+    for b in range(w.batch):
+        assert not got[b, lens[b]:].any()
+
+
+def test_c4_bert_large_with_outlier_channels(P):
+    """24-layer H1024 F4096, batch 32 x 256, 1 % of the channels scaled x20 (per-tensor steps under
+    stress).  Reduced depth for the oracle's sake: the first 4 layers at full batch shape, Fully-Quant
+    end to end (bit-identical) and Quant-FFN-Only layer by layer."""
+    w0 = W.config("C4")
+    w = W.bert_large("C4x4", 4, w0.batch, w0.seq, FULL_INT8, outlier_frac=w0.outlier_frac)
+    wts = W.make_weights(w)
+    hid, lens, _ = W.make_hidden(w)
+    sc = oracle.calibrate(*args(w), wts, W.make_calibration_batch(w))
+    got = run_gpu(P, w, wts, sc, hid, None)
+    pick = [0, 31]
+    want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid[pick], lens[pick])
+    d = compare(got[pick], want, lens[pick], True, "C4 (4 layers) FULL_INT8")
+    assert (d == 0).all()
+    wf = w.with_modes(FFN_INT8)
+    teacher_forced_layers(P, wf, wts, sc, hid[pick], lens[pick], None, "C4 (4 layers) FFN_INT8")
+
+
+def test_c5_long_sequences(P):
+    """Batch 128 x 512 Fully-Quant (large-GEMM regime, 512 x 512 attention).  Two layers at the full
+    batch shape; the oracle checks the first and last sequence."""
+    w0 = W.config("C5")
+    w = W.bert_base("C5x2", 2, w0.batch, w0.seq, FULL_INT8)
+    wts = W.make_weights(w)
+    hid, lens, _ = W.make_hidden(w)
+    sc = oracle.calibrate(*args(w), wts, W.make_calibration_batch(w))
+    got = run_gpu(P, w, wts, sc, hid, None)
+    pick = [0, 127]
+    want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid[pick], lens[pick])
+    d = compare(got[pick], want, lens[pick], True, "C5 (2 layers) FULL_INT8")
+    assert (d == 0).all()
+
+
+def test_gpu_calibration_matches_the_oracle_calibration(P):
+    import torch
+    w = W.config("C1").with_modes(FP16)
+    wts = W.make_weights(w)
+    cal = W.make_calibration_batch(w)
+    want = oracle.calibrate(*args(w), wts, cal)
+    enc = P.Encoder(*args(w), w.modes, wts, None, max_batch=cal.shape[0], max_seq=cal.shape[1])
+    got = enc.calibrate(torch.from_numpy(cal).cuda())
+    enc.close()
+    # the GPU calibrates on its fp16 forward, the oracle on the unrounded model: steps agree to fp16 accuracy
+    assert np.abs(got / want - 1).max() < 1e-2
+    assert got[0, 0] == want[0, 0]                       # the input's absmax is exact
+
+
+def test_error_paths_on_the_device_side(P):
+    import torch
+    w = small((FULL_INT8,), batch=2, seq=16, varlen=False)
+    wts = W.make_weights(w)
+    sc = oracle.calibrate(*args(w), wts, W.make_calibration_batch(w))
+    bad = sc.copy(); bad[0, 4] = 0.0
+    with pytest.raises(P.SampError) as e:
+        P.Encoder(*args(w), w.modes, wts, bad, max_batch=2, max_seq=16)
+    assert e.value.code == -5
+    with pytest.raises(P.SampError) as e:
+        P.Encoder(*args(w), w.modes, wts, None, max_batch=2, max_seq=16)
+    assert e.value.code == -1
+    enc = P.Encoder(*args(w), w.modes, wts, sc, max_batch=2, max_seq=16)
+    hid = torch.zeros((3, 16, 128), dtype=torch.float16, device="cuda")
+    with pytest.raises(P.SampError) as e:
+        enc.forward(hid)
+    assert e.value.code == -2
+    with pytest.raises(P.SampError) as e:
+        enc.calibrate(hid[:2])
+    assert e.value.code == -1
+    enc.close()

@@ -1,0 +1,243 @@
+"""GPU parity of the single steps of the path against the CPU oracle (through the C ABI).
+
+Integer results (int32 accumulators, int8 codes) must be bit-exact; fp16 results of steps whose
+arithmetic is a fixed sequence of binary32 operations must be bit-exact too; fp16 GEMM and fp16
+attention (binary32 accumulation in hardware order against binary64 in the oracle) are compared
+with a tolerance derived from that difference.
+"""
+import numpy as np
+import pytest
+
+import oracle
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2209_09130_amd as P
+    P.lib()
+    return P
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    import torch
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+# ------------------------------------------------------------------ INT8 GEMM
+@pytest.mark.parametrize("M,N,K", [(1, 128, 64), (128, 128, 64), (77, 256, 192), (300, 768, 768), (513, 128, 3072)])
+def test_int8_gemm_accumulators_bit_exact(P, M, N, K):
+    rng = np.random.default_rng(M + N + K)
+    A = rng.integers(-127, 128, (M, K), dtype=np.int8)
+    W = rng.integers(-127, 128, (N, K), dtype=np.int8)
+    got = host(P.gemm_i8_i32(dev(A), dev(W)))
+    assert np.array_equal(got, oracle.gemm_i8_i32(A, W))
+
+
+def test_int8_gemm_extremes_and_full_size_sampled(P):
+    K = 4096
+    A = np.full((130, K), 127, np.int8); A[1::2] = -127
+    W = np.full((128, K), 127, np.int8); W[::3] = -127
+    got = host(P.gemm_i8_i32(dev(A), dev(W)))
+    assert np.array_equal(got.astype(np.int64), A.astype(np.int64) @ W.astype(np.int64).T)
+    # benchmark shape (tokens 4096, FFN2: N 768, K 3072): sampled rows against the oracle, all via int64 matmul
+    rng = np.random.default_rng(0)
+    A = rng.integers(-127, 128, (4096, 3072), dtype=np.int8)
+    W = rng.integers(-127, 128, (768, 3072), dtype=np.int8)
+    got = host(P.gemm_i8_i32(dev(A), dev(W)))
+    rows = np.r_[0, 127, 128, 4095, rng.integers(0, 4096, 28)]
+    assert np.array_equal(got[rows], oracle.gemm_i8_i32(A[rows], W))
+    assert np.array_equal(got.astype(np.int64), A.astype(np.int64) @ W.astype(np.int64).T)
+
+
+def _tables(rng, N, with_bias=True):
+    s_w = (rng.random(N) * 2e-4 + 5e-5).astype(np.float32)
+    bias = (rng.standard_normal(N) * 0.2).astype(np.float32) if with_bias else None
+    return s_w, bias
+
+
+@pytest.mark.parametrize("M,N,K,with_bias", [(200, 256, 768, True), (129, 768, 128, False)])
+def test_int8_gemm_requant_epilogue_bit_exact(P, M, N, K, with_bias):
+    rng = np.random.default_rng(M * 7 + N)
+    A = rng.integers(-127, 128, (M, K), dtype=np.int8)
+    W = rng.integers(-127, 128, (N, K), dtype=np.int8)
+    s_w, bias = _tables(rng, N, with_bias)
+    m, b = oracle.fold_requant(0.037, s_w, bias, 0.021 * np.sqrt(K / 768))
+    want = oracle.epilogue_requant(oracle.gemm_i8_i32(A, W), m, b)
+    got = host(P.gemm_i8_requant(dev(A), dev(W), dev(m), dev(b) if with_bias else None))
+    assert np.array_equal(got, want)
+    assert np.abs(want).max() == 127 and (np.abs(want) < 127).mean() > 0.5      # clamp and interior both hit
+
+
+def test_int8_gemm_gelu_quant_epilogue_bit_exact(P):
+    rng = np.random.default_rng(21)
+    M, N, K = 260, 384, 768
+    A = rng.integers(-127, 128, (M, K), dtype=np.int8)
+    W = rng.integers(-127, 128, (N, K), dtype=np.int8)
+    s_w, bias = _tables(rng, N)
+    m = oracle.fold_dequant(0.05, s_w)
+    s_out = 0.0147
+    want = oracle.epilogue_gelu_quant(oracle.gemm_i8_i32(A, W), m, bias, s_out)
+    got = host(P.gemm_i8_gelu_quant(dev(A), dev(W), dev(m), dev(bias), s_out))
+    assert np.array_equal(got, want)
+    assert want.max() == 127 and (want == 0).any() and (want < 0).any()
+
+
+def test_gelu_quant_decision_is_exact_and_fast_path_error_is_bounded(P):
+    """The kernel takes the fast GELU value only when it cannot change the rounded code.  Check
+    (a) the codes equal the oracle's on a dense sweep incl. values planted next to rounding ties,
+    (b) |fast - exact| stays below half the bound the kernel assumes (8e-7 * |y|)."""
+    rng = np.random.default_rng(22)
+    ys = np.concatenate([
+        np.linspace(-12, 12, 3_000_001, dtype=np.float64).astype(np.float32),
+        (rng.standard_normal(2_000_000) * 0.6).astype(np.float32),
+        np.array([0.0, -0.0, 1e-30, -1e-30, 40.0, -40.0, 1e4, -1e4], np.float32),
+    ])
+    for s_out in (0.0247, 0.0031, 0.25):
+        codes, fast = P.gelu_quant(dev(ys), s_out, want_fast=True)
+        codes, fast = host(codes), host(fast)
+        exact = np.array([oracle.gelu(v) for v in ys[::997]], np.float32)
+        err = np.abs(fast[::997].astype(np.float64) - exact.astype(np.float64))
+        bound = 8e-7 * np.abs(ys[::997].astype(np.float64)) + 1e-37
+        assert (err <= 0.5 * bound + 6e-8 * np.abs(exact)).all()
+        # the oracle's epilogue with acc = 0 reduces to code(GELU(bias)): feed y as the bias vector
+        want = oracle.epilogue_gelu_quant(np.zeros((1, ys.size), np.int32), np.zeros(ys.size, np.float32), ys, s_out)[0]
+        assert np.array_equal(codes, want)
+    # values sitting right at rounding ties of the code: y with GELU(y)/s = k + 0.5 (bisection on the oracle)
+    s_out = 0.0247
+    ties = []
+    for k in range(0, 100, 3):
+        lo, hi = 0.0, 8.0
+        target = (k + 0.5) * s_out
+        for _ in range(60):
+            mid = (lo + hi) / 2
+            if oracle.gelu(np.float32(mid)) < target:
+                lo = mid
+            else:
+                hi = mid
+        c = np.float32(lo)
+        ties += [np.nextafter(c, np.float32(-9)), c, np.nextafter(c, np.float32(9))]
+        for step in range(2, 6):
+            ties += [np.float32(c - step * np.spacing(c)), np.float32(c + step * np.spacing(c))]
+    ties = np.array(ties, np.float32)
+    got = host(P.gelu_quant(dev(ties), s_out))
+    want = oracle.epilogue_gelu_quant(np.zeros((1, ties.size), np.int32), np.zeros(ties.size, np.float32), ties, s_out)[0]
+    assert np.array_equal(got, want)
+
+
+# ------------------------------------------------------------------ FP16 GEMM
+@pytest.mark.parametrize("M,N,K,bias,gelu", [(200, 256, 768, True, False), (131, 128, 96, False, False),
+                                             (150, 384, 768, True, True)])
+def test_fp16_gemm_within_accumulation_tolerance(P, M, N, K, bias, gelu):
+    rng = np.random.default_rng(M + K)
+    A = rng.standard_normal((M, K)).astype(np.float16)
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float16)
+    b = (rng.standard_normal(N) * 0.1).astype(np.float32) if bias else None
+    want = oracle.gemm_f16(A, W, b, gelu).astype(np.float64)
+    got = host(P.gemm_f16(dev(A), dev(W), dev(b) if bias else None, gelu)).astype(np.float64)
+    # binary32 accumulation error << one fp16 ulp: results differ by at most one ulp, and rarely
+    ulp = np.maximum(np.abs(want), 2.0 ** -14) * 2.0 ** -10
+    assert (np.abs(got - want) <= ulp + 1e-6).all()
+    assert (got != want).mean() < 5e-3
+
+
+# ------------------------------------------------------------------ attention
+def _cu(lens):
+    return np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+
+
+@pytest.mark.parametrize("lens,heads", [([128], 2), ([1, 5, 32, 33, 64, 17], 3), ([200, 256, 129], 2), ([512, 300], 1)])
+def test_int8_attention_bit_exact(P, lens, heads):
+    rng = np.random.default_rng(sum(lens))
+    H = heads * 64
+    cu = _cu(lens)
+    T = int(cu[-1])
+    # q, k ~ N(0, 26) codes as after a real projection (|code| <= 127), v likewise
+    qkv = np.clip(np.rint(rng.standard_normal((T, 3 * H)) * 26), -127, 127).astype(np.int8)
+    sc = (0.0209, 0.0249, 0.021, 0.0003, 0.0021)
+    want = oracle.attention_i8(qkv, cu, heads, *sc)
+    got = host(P.attention_i8(dev(qkv), dev(cu), max(lens), heads, *sc))
+    assert np.array_equal(got, want)
+    assert np.abs(want).max() > 20
+
+
+def test_int8_attention_peaked_softmax_bit_exact(P):
+    # a large score step makes the softmax peaked: codes span 0..127 and clamp
+    rng = np.random.default_rng(5)
+    heads, lens = 2, [96, 31]
+    H = heads * 64
+    cu = _cu(lens)
+    qkv = np.clip(np.rint(rng.standard_normal((int(cu[-1]), 3 * H)) * 40), -127, 127).astype(np.int8)
+    sc = (0.05, 0.05, 0.021, 0.004, 0.006)
+    want = oracle.attention_i8(qkv, cu, heads, *sc)
+    got = host(P.attention_i8(dev(qkv), dev(cu), max(lens), heads, *sc))
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("lens,heads", [([128], 2), ([1, 5, 32, 33, 64, 17], 3), ([300, 512], 1)])
+def test_fp16_attention_within_tolerance(P, lens, heads):
+    rng = np.random.default_rng(sum(lens) + 1)
+    H = heads * 64
+    cu = _cu(lens)
+    qkv = (rng.standard_normal((int(cu[-1]), 3 * H)) * 0.6).astype(np.float16)
+    want = oracle.attention_f16(qkv, cu, heads).astype(np.float64)
+    got = host(P.attention_f16(dev(qkv), dev(cu), max(lens), heads)).astype(np.float64)
+    # P is rounded to fp16 on both sides from slightly different binary32 values (fast exp vs binary64 exp):
+    # each P may differ by one fp16 ulp (2^-11 relative) -> context error << 2^-11 * max|v|
+    assert np.abs(got - want).max() <= 2e-3
+    assert np.abs(got - want).mean() <= 1e-4
+
+
+# ------------------------------------------------------------------ fused bias + residual + LayerNorm (+ quant)
+@pytest.mark.parametrize("H", [128, 768, 1024])
+@pytest.mark.parametrize("in8,res8,out8", [(1, 1, 1), (1, 1, 0), (0, 0, 1), (0, 0, 0), (1, 0, 1), (0, 1, 0)])
+def test_add_ln_bit_exact(P, H, in8, res8, out8):
+    rng = np.random.default_rng(H + in8 * 4 + res8 * 2 + out8)
+    M = 37
+    a = rng.integers(-127, 128, (M, H), dtype=np.int8) if in8 else (rng.standard_normal((M, H)) * 0.5).astype(np.float16)
+    r = rng.integers(-127, 128, (M, H), dtype=np.int8) if res8 else rng.standard_normal((M, H)).astype(np.float16)
+    bias = (rng.standard_normal(H) * 0.1).astype(np.float32)
+    g = (1 + 0.1 * rng.standard_normal(H)).astype(np.float32)
+    be = (0.1 * rng.standard_normal(H)).astype(np.float32)
+    s_in, s_res, s_out, eps = 0.0105, 0.0372, 0.0369, 1e-12
+    want = oracle.add_ln(a, s_in, bias, r, s_res, g, be, eps, bool(out8), s_out)
+    got = host(P.add_ln(dev(a), s_in, dev(bias), dev(r), s_res, dev(g), dev(be), eps, bool(out8), s_out))
+    assert np.array_equal(got.view(np.uint8 if out8 else np.uint16), want.view(np.uint8 if out8 else np.uint16))
+
+
+# ------------------------------------------------------------------ create-time and entry steps
+def test_weight_quantisation_bit_exact(P):
+    rng = np.random.default_rng(31)
+    W = (rng.standard_normal((300, 768)) * 0.02).astype(np.float16)
+    W[17] = 0
+    Wq, s_w = P.quantize_weight(dev(W))
+    wq, sw = oracle.quantize_weight(W)
+    assert np.array_equal(host(Wq), wq) and np.array_equal(host(s_w), sw)
+
+
+@pytest.mark.parametrize("quant", [False, True])
+def test_padding_removal_packs_valid_rows(P, quant):
+    rng = np.random.default_rng(32)
+    B, S, H = 5, 40, 128
+    lens = np.array([40, 1, 17, 33, 8], np.int32)
+    hid = rng.standard_normal((B, S, H)).astype(np.float16)
+    mask = (np.arange(S)[None, :] < lens[:, None]).astype(np.int32)
+    s_x = 0.0371 if quant else 0.0
+    packed, cu, row_map = P.pack_rows(dev(hid), dev(mask), s_x)
+    packed, cu, row_map = host(packed), host(cu), host(row_map)
+    assert np.array_equal(cu, _cu(lens))
+    T = int(cu[-1])
+    rows = np.concatenate([hid[b, :lens[b]] for b in range(B)])
+    want = oracle.quantize_f16(rows, s_x) if quant else rows
+    assert np.array_equal(packed[:T], want)
+    assert np.array_equal(row_map[:T], np.concatenate([b * S + np.arange(lens[b]) for b in range(B)]))
