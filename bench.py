@@ -9,7 +9,7 @@ stack; the other precision modes are timed the same way and reported under "mode
 Extra objects on the JSON line:
   roofline     - the FFN1 INT8 GEMM (+bias+GELU+quantise) kernel: algorithmic ops per launch
                  (2 * tokens * ffn * hidden) over its mean launch duration, measured with HIP events
-                 attached to the dispatches inside the timed region, against the int8 MFMA dense peak.
+                 attached to the dispatches over a repeat of the timed steps, against the int8 MFMA dense peak.
   cpu_baseline - the CPU oracle (as it stands, OpenMP over sequences) on the same batch.
 """
 from __future__ import annotations
@@ -84,8 +84,6 @@ def main() -> int:
         for _ in range(a.warmup):
             enc.forward(hid, mask, out)
         headline = (name in ("FULL_INT8", "CONFIG"))
-        if headline:
-            enc.profile(P.PROF_FFN1)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(a.steps):
@@ -95,6 +93,13 @@ def main() -> int:
         ms = dt / a.steps * 1e3
         results[name] = {"ms_per_step": ms, "seq_per_s": w0.batch / (ms * 1e-3)}
         if headline:
+            # The dominant kernel's launch duration: the same K steps once more with HIP events attached
+            # to that kernel's dispatches (an event-carrying dispatch costs a few microseconds of queue
+            # time, so this pass is kept out of the throughput figure above).
+            enc.profile(P.PROF_FFN1)
+            for _ in range(a.steps):
+                enc.forward(hid, mask, out)
+            torch.cuda.synchronize()
             kms, launches = enc.profile_read()
             enc.profile(P.PROF_OFF)
             ffn_int8 = bool(modes[0] & 2)

@@ -10,18 +10,21 @@
 // 32x32 result a lane owns ONE token row and four consecutive output channels per register
 // group -- which is what the per-channel epilogue tables and the packed int8/fp16 stores want.
 //
-// Block tile 128 (tokens) x 128 (channels), 4 waves in 2x2, wave tile 64x64 = 2x2 MFMA tiles.
-// K is consumed 64 bytes per step through double-buffered LDS tiles whose 16-byte chunks are
-// XOR-swizzled so that both the 16-byte stores and the ds_read_b128 operand fetches are spread
-// over all banks.
+// A block of 4 waves (2 x 2) computes a (64 TM) x (64 TN) tile, each wave (32 TM) x (32 TN).
+// K is consumed 64 bytes per stage through an NSTAGE-deep ring of LDS tiles that is filled by
+// direct global->LDS loads (global_load_lds_dwordx4, no register staging), so that NSTAGE-1
+// stages of loads are in flight while one is being multiplied: the memory round trip of a step
+// is several times longer than its MFMA work, and only a deep ring hides it.  A direct load puts
+// lane i's 16 bytes at LDS position i of a 1 KiB run; the XOR swizzle that keeps the operand
+// fetches (ds_read_b128) conflict-free is therefore applied to the global address instead.
+// Work-groups are renumbered so that each XCD (own L2) owns a contiguous range of tiles.
 #include "samp_common.h"
 
 namespace samp {
 namespace {
 
-constexpr int BM = 128, BN = 128, BKB = 64;      // BKB: bytes of K per main-loop step
+constexpr int BKB = 64;                          // bytes of K per stage
 constexpr int NTHREADS = 256;
-constexpr int TILE_BYTES = 128 * BKB;            // one operand tile in LDS
 
 // swizzle of the 16-byte chunk index inside a 64-byte LDS row
 __device__ __forceinline__ int swz(int row) { return ((row >> 1) & 3) ^ ((row >> 3) & 1); }
@@ -39,7 +42,10 @@ struct F16 {
     { return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0, 0, 0); }
 };
 
-// ---- epilogues: turn 4 accumulators (one token row, channels n..n+3) into stored output ---------
+// ---- epilogues -------------------------------------------------------------------------------
+// A 32x32 result tile gives each lane 16 accumulators: register 4q+t holds channel
+// n_tile + 8q + 4g + t (g = lane >> 5) of the lane's token row.  tile() turns them into the four
+// packed output groups of the lane (q = 0..3).
 struct EpiRawI32 {                                // test hook: the exact int32 accumulators
     int32_t *out; int N;
     static constexpr int OUT_BYTES = 4;
@@ -52,28 +58,65 @@ struct EpiRequant {                               // code = rne(fmaf(acc, m[n], 
     const float *m, *b;
     static constexpr int OUT_BYTES = 1;
     static constexpr bool STAGED = true;
-    __device__ __forceinline__ int pack(int n, int a0, int a1, int a2, int a3) const
+    typedef int pack_t;
+    __device__ __forceinline__ void tile(const v16i &acc, int n_tile, int g, int (&pk)[4]) const
     {
-        const v4f mm = *reinterpret_cast<const v4f *>(m + n);
-        v4f bb = {0.f, 0.f, 0.f, 0.f};
-        if (b) bb = *reinterpret_cast<const v4f *>(b + n);
-        return pack4(qcode(__builtin_fmaf((float)a0, mm.x, bb.x)), qcode(__builtin_fmaf((float)a1, mm.y, bb.y)),
-                     qcode(__builtin_fmaf((float)a2, mm.z, bb.z)), qcode(__builtin_fmaf((float)a3, mm.w, bb.w)));
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+            const int n = n_tile + 8 * q + 4 * g;
+            const v4f mm = *reinterpret_cast<const v4f *>(m + n);
+            v4f bb = {0.f, 0.f, 0.f, 0.f};
+            if (b) bb = *reinterpret_cast<const v4f *>(b + n);
+            pk[q] = pack4(qcode(__builtin_fmaf((float)acc[4 * q + 0], mm.x, bb.x)),
+                          qcode(__builtin_fmaf((float)acc[4 * q + 1], mm.y, bb.y)),
+                          qcode(__builtin_fmaf((float)acc[4 * q + 2], mm.z, bb.z)),
+                          qcode(__builtin_fmaf((float)acc[4 * q + 3], mm.w, bb.w)));
+        }
     }
 };
 
-struct EpiGeluQuant {                             // y = fmaf(acc, m[n], bias[n]); code = rne(GELU(y) / s_out)
+// y = fmaf(acc, m[n], bias[n]); code = rne(GELU(y) / s_out), decided exactly: the fast binary32
+// GELU is used wherever it provably rounds like the binary64 definition; the few elements that sit
+// within the fast path's error bound of a rounding tie are collected in a per-lane bit mask and
+// redone in binary64 by one compact loop (one copy of the slow code per tile, rarely entered).
+struct EpiGeluQuant {
     const float *m, *bias; float inv_s;
     static constexpr int OUT_BYTES = 1;
     static constexpr bool STAGED = true;
-    __device__ __forceinline__ int pack(int n, int a0, int a1, int a2, int a3) const
+    typedef int pack_t;
+    __device__ __forceinline__ void tile(const v16i &acc, int n_tile, int g, int (&pk)[4]) const
     {
-        const v4f mm = *reinterpret_cast<const v4f *>(m + n);
-        const v4f bb = *reinterpret_cast<const v4f *>(bias + n);
-        return pack4(gelu_quant_code(__builtin_fmaf((float)a0, mm.x, bb.x), inv_s),
-                     gelu_quant_code(__builtin_fmaf((float)a1, mm.y, bb.y), inv_s),
-                     gelu_quant_code(__builtin_fmaf((float)a2, mm.z, bb.z), inv_s),
-                     gelu_quant_code(__builtin_fmaf((float)a3, mm.w, bb.w), inv_s));
+        unsigned slow = 0;
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+            const int n = n_tile + 8 * q + 4 * g;
+            const v4f mm = *reinterpret_cast<const v4f *>(m + n);
+            const v4f bb = *reinterpret_cast<const v4f *>(bias + n);
+            int c[4];
+#pragma unroll
+            for (int t = 0; t < 4; t++) {
+                const float y = __builtin_fmaf((float)acc[4 * q + t], mm[t], bb[t]);
+                bool near_tie;
+                c[t] = gelu_quant_code_fast(y, inv_s, near_tie);
+                slow |= (unsigned)near_tie << (4 * q + t);
+            }
+            pk[q] = pack4(c[0], c[1], c[2], c[3]);
+        }
+        while (__builtin_amdgcn_ballot_w64(slow != 0) != 0) {          // wave-uniform loop, rarely entered
+            const bool active = slow != 0;
+            const int e = active ? __builtin_ctz(slow) : 0;
+            int a = acc[0];
+#pragma unroll
+            for (int k = 1; k < 16; k++) a = (e == k) ? acc[k] : a;
+            const int n = n_tile + 8 * (e >> 2) + 4 * g + (e & 3);
+            const float y = __builtin_fmaf((float)a, m[n], bias[n]);
+            const int code = qcode(gelu_exact(y) * inv_s);
+            const int sh = 8 * (e & 3);
+#pragma unroll
+            for (int q = 0; q < 4; q++)
+                if (active && (e >> 2) == q) pk[q] = (pk[q] & ~(0xff << sh)) | ((code & 0xff) << sh);
+            slow &= slow - 1;
+        }
     }
 };
 
@@ -81,110 +124,131 @@ struct EpiF16 {                                   // fp16(act(acc + bias[n]))
     const float *bias; bool gelu;
     static constexpr int OUT_BYTES = 2;
     static constexpr bool STAGED = true;
-    __device__ __forceinline__ v2i pack(int n, float a0, float a1, float a2, float a3) const
+    typedef v2i pack_t;
+    __device__ __forceinline__ void tile(const v16f &acc, int n_tile, int g, v2i (&pk)[4]) const
     {
-        if (bias) {
-            const v4f bb = *reinterpret_cast<const v4f *>(bias + n);
-            a0 += bb.x; a1 += bb.y; a2 += bb.z; a3 += bb.w;
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+            const int n = n_tile + 8 * q + 4 * g;
+            float a0 = acc[4 * q], a1 = acc[4 * q + 1], a2 = acc[4 * q + 2], a3 = acc[4 * q + 3];
+            if (bias) {
+                const v4f bb = *reinterpret_cast<const v4f *>(bias + n);
+                a0 += bb.x; a1 += bb.y; a2 += bb.z; a3 += bb.w;
+            }
+            if (gelu) { a0 = gelu_fast(a0); a1 = gelu_fast(a1); a2 = gelu_fast(a2); a3 = gelu_fast(a3); }
+            const v4h h = {to_half(a0), to_half(a1), to_half(a2), to_half(a3)};
+            pk[q] = __builtin_bit_cast(v2i, h);
         }
-        if (gelu) { a0 = gelu_fast(a0); a1 = gelu_fast(a1); a2 = gelu_fast(a2); a3 = gelu_fast(a3); }
-        const v4h h = {to_half(a0), to_half(a1), to_half(a2), to_half(a3)};
-        return __builtin_bit_cast(v2i, h);
     }
 };
 
-template <class T, class Epi>
+// wait until at most N vector-memory operations of this wave are outstanding and all of its LDS
+// reads have returned, then barrier.
+// The "memory" clobber keeps the compiler from moving LDS accesses across it.
+template <int N>
+__device__ __forceinline__ void wait_vm_and_barrier()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+template <class T, class Epi, int TM, int TN, int NSTAGE>
 __global__ __launch_bounds__(NTHREADS) void gemm_nt_kernel(const char *__restrict__ A, const char *__restrict__ W,
                                                             char *__restrict__ out, Epi epi, int host_rows,
-                                                            const int *__restrict__ dev_rows, int N, int Kbytes)
+                                                            const int *__restrict__ dev_rows, int N, int Kbytes,
+                                                            int tiles_n, int tiles_total)
 {
-    // LDS: [buffer][operand][128 rows][64 bytes]; reused as the output staging tile afterwards
-    __shared__ __attribute__((aligned(16))) char lds[2 * 2 * TILE_BYTES + 4096];
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int A_BYTES = BM * BKB, W_BYTES = BN * BKB, STAGE_BYTES = A_BYTES + W_BYTES;
+    constexpr int NA = BM / 64, NW = BN / 64;                // direct-load instructions per wave per stage
+    constexpr int NLD = NA + NW;
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
 
+    // XCD-aware renumbering: hardware hands consecutive work-groups to the 8 XCDs in turn; give
+    // each XCD a contiguous range of tiles (same token rows, all channel tiles) for L2 reuse.
+    int tile = blockIdx.x;
+    {
+        const int per = tiles_total >> 3, body = per << 3;
+        if (tile < body) tile = (tile & 7) * per + (tile >> 3);
+    }
     const int M = dev_rows ? *dev_rows : host_rows;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
     if (m0 >= M) return;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;       // wave tile origin inside the block tile
+    const int wm = (wave >> 1) * 32 * TM, wn = (wave & 1) * 32 * TN;   // wave tile origin inside the block tile
     const int r = lane & 31, g = lane >> 5;
 
-    // global -> LDS copy assignment: 512 chunks of 16 bytes per operand tile, 2 per thread
-    const int crow = tid >> 2, cchunk = tid & 3;
-    const char *a_src[2], *w_src[2];
-    int lds_off[2];
+    // direct loads: instruction j of this wave fills rows 16*(wave + 4j) .. +15 of an operand tile;
+    // lane i supplies row (i >> 2), LDS chunk (i & 3), i.e. global chunk (i & 3) ^ swz(row).
+    const char *a_src[NA], *w_src[NW];
 #pragma unroll
-    for (int u = 0; u < 2; u++) {
-        const int row = crow + u * 64;
+    for (int j = 0; j < NA; j++) {
+        const int row = 16 * (wave + 4 * j) + (lane >> 2);
         int am = m0 + row; if (am > M - 1) am = M - 1;            // rows past the end re-read the last row
-        a_src[u] = A + (size_t)am * Kbytes + cchunk * 16;
-        w_src[u] = W + (size_t)(n0 + row) * Kbytes + cchunk * 16;
-        lds_off[u] = row * BKB + ((cchunk ^ swz(row)) << 4);
+        a_src[j] = A + (size_t)am * Kbytes + (((lane & 3) ^ swz(row)) << 4);
     }
+#pragma unroll
+    for (int j = 0; j < NW; j++) {
+        const int row = 16 * (wave + 4 * j) + (lane >> 2);
+        w_src[j] = W + (size_t)(n0 + row) * Kbytes + (((lane & 3) ^ swz(row)) << 4);
+    }
+    auto issue = [&](int kt) {
+        char *st = lds + (kt % NSTAGE) * STAGE_BYTES;
+#pragma unroll
+        for (int j = 0; j < NA; j++)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(a_src[j] + (size_t)kt * BKB),
+                                             (__attribute__((address_space(3))) void *)(st + (wave + 4 * j) * 1024), 16, 0, 0);
+#pragma unroll
+        for (int j = 0; j < NW; j++)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(w_src[j] + (size_t)kt * BKB),
+                                             (__attribute__((address_space(3))) void *)(st + A_BYTES + (wave + 4 * j) * 1024), 16, 0, 0);
+    };
 
-    typename T::acc_t acc[2][2];                                  // [channel tile][token tile]
+    typename T::acc_t acc[TN][TM];                                // [channel tile][token tile]
 #pragma unroll
-    for (int i = 0; i < 2; i++)
+    for (int i = 0; i < TN; i++)
 #pragma unroll
-        for (int j = 0; j < 2; j++)
+        for (int j = 0; j < TM; j++)
 #pragma unroll
             for (int e = 0; e < 16; e++) acc[i][j][e] = 0;
 
     const int KT = Kbytes / BKB;
-    v4i ra[2], rw[2];
 #pragma unroll
-    for (int u = 0; u < 2; u++) {
-        ra[u] = *reinterpret_cast<const v4i *>(a_src[u]);
-        rw[u] = *reinterpret_cast<const v4i *>(w_src[u]);
-    }
-#pragma unroll
-    for (int u = 0; u < 2; u++) {
-        *reinterpret_cast<v4i *>(lds + lds_off[u]) = ra[u];
-        *reinterpret_cast<v4i *>(lds + TILE_BYTES + lds_off[u]) = rw[u];
-    }
-    __syncthreads();
+    for (int s = 0; s < NSTAGE - 1; s++)
+        if (s < KT) issue(s);
 
     for (int kt = 0; kt < KT; kt++) {
-        const char *cur = lds + (kt & 1) * 2 * TILE_BYTES;
-        if (kt + 1 < KT) {
-#pragma unroll
-            for (int u = 0; u < 2; u++) {
-                ra[u] = *reinterpret_cast<const v4i *>(a_src[u] + (size_t)(kt + 1) * BKB);
-                rw[u] = *reinterpret_cast<const v4i *>(w_src[u] + (size_t)(kt + 1) * BKB);
-            }
-        }
+        // stage kt must have landed: all but the loads of the (up to NSTAGE-2) later stages
+        if (kt + NSTAGE - 2 < KT) wait_vm_and_barrier<(NSTAGE - 2) * NLD>();
+        else wait_vm_and_barrier<0>();
+        if (kt + NSTAGE - 1 < KT) issue(kt + NSTAGE - 1);        // refills the buffer consumed at kt-1
+        const char *cur = lds + (kt % NSTAGE) * STAGE_BYTES;
 #pragma unroll
         for (int ks = 0; ks < 2; ks++) {
-            v4i fa[2], fw[2];
+            v4i fa[TM], fw[TN];
 #pragma unroll
-            for (int i = 0; i < 2; i++) {
-                const int rowa = wm + i * 32 + r, roww = wn + i * 32 + r;
-                fa[i] = *reinterpret_cast<const v4i *>(cur + rowa * BKB + (((2 * ks + g) ^ swz(rowa)) << 4));
-                fw[i] = *reinterpret_cast<const v4i *>(cur + TILE_BYTES + roww * BKB + (((2 * ks + g) ^ swz(roww)) << 4));
+            for (int j = 0; j < TM; j++) {
+                const int row = wm + j * 32 + r;
+                fa[j] = *reinterpret_cast<const v4i *>(cur + row * BKB + (((2 * ks + g) ^ swz(row)) << 4));
             }
 #pragma unroll
-            for (int i = 0; i < 2; i++)
-#pragma unroll
-                for (int j = 0; j < 2; j++) acc[i][j] = T::mma(fw[i], fa[j], acc[i][j]);
-        }
-        if (kt + 1 < KT) {
-            char *nxt = lds + ((kt + 1) & 1) * 2 * TILE_BYTES;
-#pragma unroll
-            for (int u = 0; u < 2; u++) {
-                *reinterpret_cast<v4i *>(nxt + lds_off[u]) = ra[u];
-                *reinterpret_cast<v4i *>(nxt + TILE_BYTES + lds_off[u]) = rw[u];
+            for (int i = 0; i < TN; i++) {
+                const int row = wn + i * 32 + r;
+                fw[i] = *reinterpret_cast<const v4i *>(cur + A_BYTES + row * BKB + (((2 * ks + g) ^ swz(row)) << 4));
             }
+#pragma unroll
+            for (int i = 0; i < TN; i++)
+#pragma unroll
+                for (int j = 0; j < TM; j++) acc[i][j] = T::mma(fw[i], fa[j], acc[i][j]);
         }
-        __syncthreads();
     }
 
-    // Result layout of a 32x32 tile (first operand = channels, second = tokens): lane holds token
-    // (lane & 31) and, in register 4q+t, channel 8q + 4(lane >> 5) + t.
     if constexpr (!Epi::STAGED) {
 #pragma unroll
-        for (int i = 0; i < 2; i++)
+        for (int i = 0; i < TN; i++)
 #pragma unroll
-            for (int j = 0; j < 2; j++) {
+            for (int j = 0; j < TM; j++) {
                 const int row = m0 + wm + j * 32 + r;
                 if (row < M) {
 #pragma unroll
@@ -195,21 +259,21 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_kernel(const char *__restric
                 }
             }
     } else {
-        // stage the 128x128 output tile in LDS, then write full rows with 16-byte stores
+        // stage the output tile in LDS (the ring is idle now), then write full rows, 16 bytes per lane
         constexpr int OB = Epi::OUT_BYTES;
         constexpr int STRIDE = BN * OB + 16;
-        static_assert(BM * STRIDE <= 2 * 2 * TILE_BYTES + 4096, "staging tile does not fit");
+        static_assert(BM * STRIDE <= NSTAGE * STAGE_BYTES, "staging tile does not fit in the ring");
+        wait_vm_and_barrier<0>();
 #pragma unroll
-        for (int i = 0; i < 2; i++)
+        for (int i = 0; i < TN; i++)
 #pragma unroll
-            for (int j = 0; j < 2; j++) {
+            for (int j = 0; j < TM; j++) {
+                typename Epi::pack_t pk[4];
+                epi.tile(acc[i][j], n0 + wn + i * 32, g, pk);
                 const int lrow = wm + j * 32 + r;
 #pragma unroll
-                for (int q = 0; q < 4; q++) {
-                    const int ln = wn + i * 32 + 8 * q + 4 * g;
-                    auto v = epi.pack(n0 + ln, acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-                    *reinterpret_cast<decltype(v) *>(lds + lrow * STRIDE + ln * OB) = v;
-                }
+                for (int q = 0; q < 4; q++)
+                    *reinterpret_cast<typename Epi::pack_t *>(lds + lrow * STRIDE + (wn + i * 32 + 8 * q + 4 * g) * OB) = pk[q];
             }
         __syncthreads();
         constexpr int CHUNKS = BN * OB / 16;                      // 16-byte chunks per output row
@@ -226,18 +290,31 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_kernel(const char *__restric
     }
 }
 
+template <class T, class Epi, int TM, int TN, int NSTAGE>
+hipError_t launch_cfg(const void *A, const void *W, void *out, const Epi &epi, Rows rows, int N, int K, hipStream_t st,
+                      const Timing *tm)
+{
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr size_t LDS = (size_t)NSTAGE * (BM + BN) * BKB;
+    auto kern = gemm_nt_kernel<T, Epi, TM, TN, NSTAGE>;
+    static bool attr_set = false;                                 // > 64 KiB of dynamic LDS must be enabled once
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int tiles_n = N / BN, tiles_m = (rows.host_rows + BM - 1) / BM, total = tiles_n * tiles_m;
+    hipExtLaunchKernelGGL(kern, dim3(total), dim3(NTHREADS), LDS, st, tm ? tm->start : nullptr, tm ? tm->stop : nullptr, 0,
+                          (const char *)A, (const char *)W, (char *)out, epi, rows.host_rows, rows.dev_rows, N, K * T::ELEM,
+                          tiles_n, total);
+    return hipGetLastError();
+}
+
 template <class T, class Epi>
 hipError_t launch(const void *A, const void *W, void *out, const Epi &epi, Rows rows, int N, int K, hipStream_t st,
                   const Timing *tm)
 {
-    dim3 grid(N / BN, (rows.host_rows + BM - 1) / BM), block(NTHREADS);
-    if (tm)
-        hipExtLaunchKernelGGL((gemm_nt_kernel<T, Epi>), grid, block, 0, st, tm->start, tm->stop, 0, (const char *)A,
-                              (const char *)W, (char *)out, epi, rows.host_rows, rows.dev_rows, N, K * T::ELEM);
-    else
-        hipLaunchKernelGGL((gemm_nt_kernel<T, Epi>), grid, block, 0, st, (const char *)A, (const char *)W, (char *)out,
-                           epi, rows.host_rows, rows.dev_rows, N, K * T::ELEM);
-    return hipGetLastError();
+    return launch_cfg<T, Epi, 2, 2, 4>(A, W, out, epi, rows, N, K, st, tm);
 }
 
 }  // namespace

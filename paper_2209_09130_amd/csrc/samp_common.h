@@ -72,17 +72,25 @@ __device__ __forceinline__ float gelu_exact(float y)
 // Bound on |gelu_fast(y) - GELU(y)|, validated exhaustively by the GPU tests.
 #define SAMP_GELU_FAST_ABS_ERR_PER_UNIT 8.0e-7f
 
-// code = rne(GELU(y) * inv_s), decided exactly: the fast value is used when it is provably on the
-// same side of every rounding boundary as the binary64 value, otherwise the binary64 path decides.
-__device__ __forceinline__ int gelu_quant_code(float y, float inv_s)
+// code = rne(GELU(y) * inv_s) from the fast GELU, plus a flag telling whether the value lies within
+// the fast path's error bound of a rounding tie (then the binary64 definition has to decide).
+__device__ __forceinline__ int gelu_quant_code_fast(float y, float inv_s, bool &near_tie)
 {
-    float c = gelu_fast(y) * inv_s;
+    const float c = gelu_fast(y) * inv_s;
     const float r = __builtin_rintf(c);
     const float dist = __builtin_fabsf(__builtin_fabsf(c - r) - 0.5f);   // distance to the nearest tie
     const float margin = __builtin_fabsf(y) * inv_s * SAMP_GELU_FAST_ABS_ERR_PER_UNIT
                        + __builtin_fabsf(c) * 6.0e-7f + 1.0e-30f;
-    if (dist <= margin) c = gelu_exact(y) * inv_s;
-    return qcode(c);
+    near_tie = dist <= margin;
+    return (int)__builtin_fminf(__builtin_fmaxf(r, -127.0f), 127.0f);
+}
+
+// The same decision for one value on its own.
+__device__ __forceinline__ int gelu_quant_code(float y, float inv_s)
+{
+    bool near_tie;
+    const int c = gelu_quant_code_fast(y, inv_s, near_tie);
+    return near_tie ? qcode(gelu_exact(y) * inv_s) : c;
 }
 
 // ---- wave reductions (64 lanes) ----------------------------------------------------------------
