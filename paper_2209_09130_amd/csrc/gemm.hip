@@ -23,11 +23,14 @@
 namespace samp {
 namespace {
 
-constexpr int BKB = 64;                          // bytes of K per stage
-constexpr int NTHREADS = 256;
-
-// swizzle of the 16-byte chunk index inside a 64-byte LDS row
-__device__ __forceinline__ int swz(int row) { return ((row >> 1) & 3) ^ ((row >> 3) & 1); }
+// XOR swizzle of the 16-byte chunk index inside an LDS row of BKB bytes (BKB = 64: 4 chunks,
+// BKB = 128: 8 chunks), chosen so that the lanes of one ds_read_b128 phase hit distinct banks.
+template <int BKB>
+__device__ __forceinline__ int swz(int row)
+{
+    if constexpr (BKB == 64) return ((row >> 1) & 3) ^ ((row >> 3) & 1);
+    else return (row & 7) ^ ((row >> 3) & 1);
+}
 
 struct I8 {
     typedef v16i acc_t;
@@ -45,28 +48,40 @@ struct F16 {
 // ---- epilogues -------------------------------------------------------------------------------
 // A 32x32 result tile gives each lane 16 accumulators: register 4q+t holds channel
 // n_tile + 8q + 4g + t (g = lane >> 5) of the lane's token row.  tile() turns them into the four
-// packed output groups of the lane (q = 0..3).
+// packed output groups of the lane (q = 0..3).  The per-channel tables of the block's BN channels
+// are copied into LDS when the block starts (load_tables), so that their memory latency is hidden
+// behind the main loop; tile() reads them from there (tab, indexed by the channel inside the block).
 struct EpiRawI32 {                                // test hook: the exact int32 accumulators
     int32_t *out; int N;
     static constexpr int OUT_BYTES = 4;
     static constexpr bool STAGED = false;
+    static constexpr int NTAB = 0;
+    __device__ __forceinline__ void load_tables(float *, int, int, int, int) const {}
     __device__ __forceinline__ void direct(int row, int n, int a0, int a1, int a2, int a3) const
     { *reinterpret_cast<v4i *>(out + (size_t)row * N + n) = v4i{a0, a1, a2, a3}; }
 };
+
+__device__ __forceinline__ void copy_table(float *dst, const float *src, int n0, int bn, int tid, int nthreads)
+{
+    for (int c = tid * 4; c < bn; c += nthreads * 4)
+        *reinterpret_cast<v4f *>(dst + c) = src ? *reinterpret_cast<const v4f *>(src + n0 + c) : v4f{0.f, 0.f, 0.f, 0.f};
+}
 
 struct EpiRequant {                               // code = rne(fmaf(acc, m[n], b[n]))
     const float *m, *b;
     static constexpr int OUT_BYTES = 1;
     static constexpr bool STAGED = true;
+    static constexpr int NTAB = 2;
     typedef int pack_t;
-    __device__ __forceinline__ void tile(const v16i &acc, int n_tile, int g, int (&pk)[4]) const
+    __device__ __forceinline__ void load_tables(float *tab, int n0, int bn, int tid, int nthreads) const
+    { copy_table(tab, m, n0, bn, tid, nthreads); copy_table(tab + bn, b, n0, bn, tid, nthreads); }
+    __device__ __forceinline__ void tile(const v16i &acc, const float *tab, int bn, int n_loc, int n_glob, int g, int (&pk)[4]) const
     {
 #pragma unroll
         for (int q = 0; q < 4; q++) {
-            const int n = n_tile + 8 * q + 4 * g;
-            const v4f mm = *reinterpret_cast<const v4f *>(m + n);
-            v4f bb = {0.f, 0.f, 0.f, 0.f};
-            if (b) bb = *reinterpret_cast<const v4f *>(b + n);
+            const int n = n_loc + 8 * q + 4 * g;
+            const v4f mm = *reinterpret_cast<const v4f *>(tab + n);
+            const v4f bb = *reinterpret_cast<const v4f *>(tab + bn + n);
             pk[q] = pack4(qcode(__builtin_fmaf((float)acc[4 * q + 0], mm.x, bb.x)),
                           qcode(__builtin_fmaf((float)acc[4 * q + 1], mm.y, bb.y)),
                           qcode(__builtin_fmaf((float)acc[4 * q + 2], mm.z, bb.z)),
@@ -83,15 +98,18 @@ struct EpiGeluQuant {
     const float *m, *bias; float inv_s;
     static constexpr int OUT_BYTES = 1;
     static constexpr bool STAGED = true;
+    static constexpr int NTAB = 2;
     typedef int pack_t;
-    __device__ __forceinline__ void tile(const v16i &acc, int n_tile, int g, int (&pk)[4]) const
+    __device__ __forceinline__ void load_tables(float *tab, int n0, int bn, int tid, int nthreads) const
+    { copy_table(tab, m, n0, bn, tid, nthreads); copy_table(tab + bn, bias, n0, bn, tid, nthreads); }
+    __device__ __forceinline__ void tile(const v16i &acc, const float *tab, int bn, int n_loc, int n_glob, int g, int (&pk)[4]) const
     {
         unsigned slow = 0;
 #pragma unroll
         for (int q = 0; q < 4; q++) {
-            const int n = n_tile + 8 * q + 4 * g;
-            const v4f mm = *reinterpret_cast<const v4f *>(m + n);
-            const v4f bb = *reinterpret_cast<const v4f *>(bias + n);
+            const int n = n_loc + 8 * q + 4 * g;
+            const v4f mm = *reinterpret_cast<const v4f *>(tab + n);
+            const v4f bb = *reinterpret_cast<const v4f *>(tab + bn + n);
             int c[4];
 #pragma unroll
             for (int t = 0; t < 4; t++) {
@@ -108,8 +126,8 @@ struct EpiGeluQuant {
             int a = acc[0];
 #pragma unroll
             for (int k = 1; k < 16; k++) a = (e == k) ? acc[k] : a;
-            const int n = n_tile + 8 * (e >> 2) + 4 * g + (e & 3);
-            const float y = __builtin_fmaf((float)a, m[n], bias[n]);
+            const int n = n_loc + 8 * (e >> 2) + 4 * g + (e & 3);
+            const float y = __builtin_fmaf((float)a, tab[n], tab[bn + n]);
             const int code = qcode(gelu_exact(y) * inv_s);
             const int sh = 8 * (e & 3);
 #pragma unroll
@@ -124,17 +142,16 @@ struct EpiF16 {                                   // fp16(act(acc + bias[n]))
     const float *bias; bool gelu;
     static constexpr int OUT_BYTES = 2;
     static constexpr bool STAGED = true;
+    static constexpr int NTAB = 1;
     typedef v2i pack_t;
-    __device__ __forceinline__ void tile(const v16f &acc, int n_tile, int g, v2i (&pk)[4]) const
+    __device__ __forceinline__ void load_tables(float *tab, int n0, int bn, int tid, int nthreads) const
+    { copy_table(tab, bias, n0, bn, tid, nthreads); }
+    __device__ __forceinline__ void tile(const v16f &acc, const float *tab, int bn, int n_loc, int n_glob, int g, v2i (&pk)[4]) const
     {
 #pragma unroll
         for (int q = 0; q < 4; q++) {
-            const int n = n_tile + 8 * q + 4 * g;
-            float a0 = acc[4 * q], a1 = acc[4 * q + 1], a2 = acc[4 * q + 2], a3 = acc[4 * q + 3];
-            if (bias) {
-                const v4f bb = *reinterpret_cast<const v4f *>(bias + n);
-                a0 += bb.x; a1 += bb.y; a2 += bb.z; a3 += bb.w;
-            }
+            const v4f bb = *reinterpret_cast<const v4f *>(tab + n_loc + 8 * q + 4 * g);
+            float a0 = acc[4 * q] + bb.x, a1 = acc[4 * q + 1] + bb.y, a2 = acc[4 * q + 2] + bb.z, a3 = acc[4 * q + 3] + bb.w;
             if (gelu) { a0 = gelu_fast(a0); a1 = gelu_fast(a1); a2 = gelu_fast(a2); a3 = gelu_fast(a3); }
             const v4h h = {to_half(a0), to_half(a1), to_half(a2), to_half(a3)};
             pk[q] = __builtin_bit_cast(v2i, h);
@@ -142,9 +159,14 @@ struct EpiF16 {                                   // fp16(act(acc + bias[n]))
     }
 };
 
+__device__ __forceinline__ int to_bits(int v) { return v; }
+__device__ __forceinline__ int to_bits(float v) { return __float_as_int(v); }
+__device__ __forceinline__ int plus_bits(int a, int bits) { return a + bits; }
+__device__ __forceinline__ float plus_bits(float a, int bits) { return a + __int_as_float(bits); }
+
 // wait until at most N vector-memory operations of this wave are outstanding and all of its LDS
-// reads have returned, then barrier.
-// The "memory" clobber keeps the compiler from moving LDS accesses across it.
+// reads have returned, then barrier.  The "memory" clobber keeps the compiler from moving LDS
+// accesses across it.
 template <int N>
 __device__ __forceinline__ void wait_vm_and_barrier()
 {
@@ -152,17 +174,27 @@ __device__ __forceinline__ void wait_vm_and_barrier()
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-template <class T, class Epi, int TM, int TN, int NSTAGE>
-__global__ __launch_bounds__(NTHREADS) void gemm_nt_kernel(const char *__restrict__ A, const char *__restrict__ W,
-                                                            char *__restrict__ out, Epi epi, int host_rows,
-                                                            const int *__restrict__ dev_rows, int N, int Kbytes,
-                                                            int tiles_n, int tiles_total)
+// KS = 1: 4 waves, each multiplies both 32-byte halves of a stage.
+// KS = 2: 8 waves; waves 0-3 take the first half of every stage, waves 4-7 the second half, and the
+//         two partial accumulators of a wave tile are added through LDS before the epilogue (int32
+//         adds are exact, so the split cannot change an INT8 result).  Twice the waves per SIMD for
+//         the shapes that have too few tiles to fill the chip otherwise.
+template <class T, class Epi, int TM, int TN, int BKB, int NSTAGE, int KS, int WAVES_PER_EU>
+__global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(WAVES_PER_EU, 8)))
+void gemm_nt_kernel(const char *__restrict__ A, const char *__restrict__ W, char *__restrict__ out, Epi epi, int host_rows,
+                    const int *__restrict__ dev_rows, int N, int Kbytes, int tiles_n, int tiles_total)
 {
+    constexpr int NT = 256 * KS, NWAVES = 4 * KS;
     constexpr int BM = 64 * TM, BN = 64 * TN;
     constexpr int A_BYTES = BM * BKB, W_BYTES = BN * BKB, STAGE_BYTES = A_BYTES + W_BYTES;
-    constexpr int NA = BM / 64, NW = BN / 64;                // direct-load instructions per wave per stage
+    constexpr int CH = BKB / 16, RPI = 64 / CH;                  // chunks per row; rows per direct-load instruction
+    static_assert(BKB == 64 || BKB == 128, "stage depth");
+    static_assert((BM / RPI) % NWAVES == 0 && (BN / RPI) % NWAVES == 0, "tile rows must split evenly over the waves");
+    constexpr int NA = BM / RPI / NWAVES, NW = BN / RPI / NWAVES; // direct-load instructions per wave per stage
     constexpr int NLD = NA + NW;
+    constexpr int RING_BYTES = NSTAGE * STAGE_BYTES;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
+    float *tab = reinterpret_cast<float *>(lds + RING_BYTES);
 
     // XCD-aware renumbering: hardware hands consecutive work-groups to the 8 XCDs in turn; give
     // each XCD a contiguous range of tiles (same token rows, all channel tiles) for L2 reuse.
@@ -176,34 +208,41 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_kernel(const char *__restric
     if (m0 >= M) return;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = (wave >> 1) * 32 * TM, wn = (wave & 1) * 32 * TN;   // wave tile origin inside the block tile
+    const int w4 = wave & 3, kgroup = wave >> 2;
+    const int wm = (w4 >> 1) * 32 * TM, wn = (w4 & 1) * 32 * TN;       // wave tile origin inside the block tile
     const int r = lane & 31, g = lane >> 5;
 
-    // direct loads: instruction j of this wave fills rows 16*(wave + 4j) .. +15 of an operand tile;
-    // lane i supplies row (i >> 2), LDS chunk (i & 3), i.e. global chunk (i & 3) ^ swz(row).
+    // direct loads: instruction j of this wave fills RPI consecutive rows (1 KiB) of an operand tile;
+    // lane i supplies row (i / CH), LDS chunk (i % CH), i.e. global chunk (i % CH) ^ swz(row).
     const char *a_src[NA], *w_src[NW];
 #pragma unroll
     for (int j = 0; j < NA; j++) {
-        const int row = 16 * (wave + 4 * j) + (lane >> 2);
+        const int row = RPI * (wave + NWAVES * j) + lane / CH;
         int am = m0 + row; if (am > M - 1) am = M - 1;            // rows past the end re-read the last row
-        a_src[j] = A + (size_t)am * Kbytes + (((lane & 3) ^ swz(row)) << 4);
+        a_src[j] = A + (size_t)am * Kbytes + (((lane % CH) ^ swz<BKB>(row)) << 4);
     }
 #pragma unroll
     for (int j = 0; j < NW; j++) {
-        const int row = 16 * (wave + 4 * j) + (lane >> 2);
-        w_src[j] = W + (size_t)(n0 + row) * Kbytes + (((lane & 3) ^ swz(row)) << 4);
+        const int row = RPI * (wave + NWAVES * j) + lane / CH;
+        w_src[j] = W + (size_t)(n0 + row) * Kbytes + (((lane % CH) ^ swz<BKB>(row)) << 4);
     }
     auto issue = [&](int kt) {
         char *st = lds + (kt % NSTAGE) * STAGE_BYTES;
 #pragma unroll
         for (int j = 0; j < NA; j++)
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(a_src[j] + (size_t)kt * BKB),
-                                             (__attribute__((address_space(3))) void *)(st + (wave + 4 * j) * 1024), 16, 0, 0);
+                                             (__attribute__((address_space(3))) void *)(st + (wave + NWAVES * j) * 1024), 16, 0, 0);
 #pragma unroll
         for (int j = 0; j < NW; j++)
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(w_src[j] + (size_t)kt * BKB),
-                                             (__attribute__((address_space(3))) void *)(st + A_BYTES + (wave + 4 * j) * 1024), 16, 0, 0);
+                                             (__attribute__((address_space(3))) void *)(st + A_BYTES + (wave + NWAVES * j) * 1024), 16, 0, 0);
     };
+
+    const int KT = Kbytes / BKB;
+#pragma unroll
+    for (int s = 0; s < NSTAGE - 1; s++)
+        if (s < KT) issue(s);
+    epi.load_tables(tab, n0, BN, tid, NT);            // ordinary loads; consumed after the main loop
 
     typename T::acc_t acc[TN][TM];                                // [channel tile][token tile]
 #pragma unroll
@@ -213,11 +252,6 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_kernel(const char *__restric
 #pragma unroll
             for (int e = 0; e < 16; e++) acc[i][j][e] = 0;
 
-    const int KT = Kbytes / BKB;
-#pragma unroll
-    for (int s = 0; s < NSTAGE - 1; s++)
-        if (s < KT) issue(s);
-
     for (int kt = 0; kt < KT; kt++) {
         // stage kt must have landed: all but the loads of the (up to NSTAGE-2) later stages
         if (kt + NSTAGE - 2 < KT) wait_vm_and_barrier<(NSTAGE - 2) * NLD>();
@@ -225,17 +259,18 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_kernel(const char *__restric
         if (kt + NSTAGE - 1 < KT) issue(kt + NSTAGE - 1);        // refills the buffer consumed at kt-1
         const char *cur = lds + (kt % NSTAGE) * STAGE_BYTES;
 #pragma unroll
-        for (int ks = 0; ks < 2; ks++) {
+        for (int kk = 0; kk < CH / 2 / KS; kk++) {
+            const int ks = KS == 2 ? kk * 2 + kgroup : kk;
             v4i fa[TM], fw[TN];
 #pragma unroll
             for (int j = 0; j < TM; j++) {
                 const int row = wm + j * 32 + r;
-                fa[j] = *reinterpret_cast<const v4i *>(cur + row * BKB + (((2 * ks + g) ^ swz(row)) << 4));
+                fa[j] = *reinterpret_cast<const v4i *>(cur + row * BKB + (((2 * ks + g) ^ swz<BKB>(row)) << 4));
             }
 #pragma unroll
             for (int i = 0; i < TN; i++) {
                 const int row = wn + i * 32 + r;
-                fw[i] = *reinterpret_cast<const v4i *>(cur + A_BYTES + row * BKB + (((2 * ks + g) ^ swz(row)) << 4));
+                fw[i] = *reinterpret_cast<const v4i *>(cur + A_BYTES + row * BKB + (((2 * ks + g) ^ swz<BKB>(row)) << 4));
             }
 #pragma unroll
             for (int i = 0; i < TN; i++)
@@ -243,41 +278,91 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_kernel(const char *__restric
                 for (int j = 0; j < TM; j++) acc[i][j] = T::mma(fw[i], fa[j], acc[i][j]);
         }
     }
+    wait_vm_and_barrier<0>();                                     // the ring is idle from here on
+
+    // KS = 2: the two K halves of a wave tile are summed through LDS, one MFMA tile per round;
+    // afterwards group 0 owns the channel tiles i < TN/2 of the wave tile, group 1 the others.
+    constexpr int TN_OWN = TN / KS;
+    if constexpr (KS == 2) {
+        static_assert(TN % 2 == 0, "channel tiles must split over the two wave groups");
+        static_assert(NWAVES * 4096 <= RING_BYTES, "exchange buffer does not fit in the ring");
+        v4i *mine = reinterpret_cast<v4i *>(lds + wave * 4096) + lane;
+        const v4i *theirs = reinterpret_cast<const v4i *>(lds + (wave ^ 4) * 4096) + lane;
+#pragma unroll
+        for (int io = 0; io < TN_OWN; io++)
+#pragma unroll
+            for (int j = 0; j < TM; j++) {
+                const int i_send = kgroup == 0 ? io + TN_OWN : io, i_keep = kgroup == 0 ? io : io + TN_OWN;
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    v4i v;
+#pragma unroll
+                    for (int t = 0; t < 4; t++) v[t] = to_bits(kgroup == 0 ? acc[TN_OWN + io][j][4 * q + t] : acc[io][j][4 * q + t]);
+                    mine[q * 64] = v;
+                }
+                __syncthreads();
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const v4i v = theirs[q * 64];
+#pragma unroll
+                    for (int t = 0; t < 4; t++) {
+                        const int bits = t == 0 ? v.x : t == 1 ? v.y : t == 2 ? v.z : v.w;
+                        if (kgroup == 0) acc[io][j][4 * q + t] = plus_bits(acc[io][j][4 * q + t], bits);
+                        else acc[TN_OWN + io][j][4 * q + t] = plus_bits(acc[TN_OWN + io][j][4 * q + t], bits);
+                    }
+                }
+                __syncthreads();
+                (void)i_send; (void)i_keep;
+            }
+    }
 
     if constexpr (!Epi::STAGED) {
 #pragma unroll
-        for (int i = 0; i < TN; i++)
+        for (int io = 0; io < TN_OWN; io++)
 #pragma unroll
             for (int j = 0; j < TM; j++) {
                 const int row = m0 + wm + j * 32 + r;
                 if (row < M) {
 #pragma unroll
                     for (int q = 0; q < 4; q++) {
-                        const int n = n0 + wn + i * 32 + 8 * q + 4 * g;
-                        epi.direct(row, n, acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+                        if (KS == 2 && kgroup == 1) {
+                            const int n = n0 + wn + (io + TN_OWN) * 32 + 8 * q + 4 * g;
+                            epi.direct(row, n, acc[io + TN_OWN][j][4 * q], acc[io + TN_OWN][j][4 * q + 1], acc[io + TN_OWN][j][4 * q + 2], acc[io + TN_OWN][j][4 * q + 3]);
+                        } else {
+                            const int n = n0 + wn + io * 32 + 8 * q + 4 * g;
+                            epi.direct(row, n, acc[io][j][4 * q], acc[io][j][4 * q + 1], acc[io][j][4 * q + 2], acc[io][j][4 * q + 3]);
+                        }
                     }
                 }
             }
     } else {
-        // stage the output tile in LDS (the ring is idle now), then write full rows, 16 bytes per lane
+        // stage the output tile in LDS, then write full rows, 16 bytes per lane
         constexpr int OB = Epi::OUT_BYTES;
         constexpr int STRIDE = BN * OB + 16;
-        static_assert(BM * STRIDE <= NSTAGE * STAGE_BYTES, "staging tile does not fit in the ring");
-        wait_vm_and_barrier<0>();
+        static_assert(BM * STRIDE <= RING_BYTES, "staging tile does not fit in the ring");
 #pragma unroll
-        for (int i = 0; i < TN; i++)
+        for (int io = 0; io < TN_OWN; io++)
 #pragma unroll
             for (int j = 0; j < TM; j++) {
                 typename Epi::pack_t pk[4];
-                epi.tile(acc[i][j], n0 + wn + i * 32, g, pk);
                 const int lrow = wm + j * 32 + r;
+                if (KS == 2 && kgroup == 1) {
+                    const int nl = wn + (io + TN_OWN) * 32;
+                    epi.tile(acc[io + TN_OWN][j], tab, BN, nl, n0 + nl, g, pk);
 #pragma unroll
-                for (int q = 0; q < 4; q++)
-                    *reinterpret_cast<typename Epi::pack_t *>(lds + lrow * STRIDE + (wn + i * 32 + 8 * q + 4 * g) * OB) = pk[q];
+                    for (int q = 0; q < 4; q++)
+                        *reinterpret_cast<typename Epi::pack_t *>(lds + lrow * STRIDE + (nl + 8 * q + 4 * g) * OB) = pk[q];
+                } else {
+                    const int nl = wn + io * 32;
+                    epi.tile(acc[io][j], tab, BN, nl, n0 + nl, g, pk);
+#pragma unroll
+                    for (int q = 0; q < 4; q++)
+                        *reinterpret_cast<typename Epi::pack_t *>(lds + lrow * STRIDE + (nl + 8 * q + 4 * g) * OB) = pk[q];
+                }
             }
         __syncthreads();
         constexpr int CHUNKS = BN * OB / 16;                      // 16-byte chunks per output row
-        constexpr int ROWS_PER_PASS = NTHREADS / CHUNKS;
+        constexpr int ROWS_PER_PASS = NT / CHUNKS;
         const int orow = tid / CHUNKS, ochunk = tid % CHUNKS;
 #pragma unroll
         for (int p = 0; p < BM / ROWS_PER_PASS; p++) {
@@ -290,13 +375,15 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_kernel(const char *__restric
     }
 }
 
-template <class T, class Epi, int TM, int TN, int NSTAGE>
+template <class T, class Epi, int TM, int TN, int BKB, int NSTAGE, int KS, int WPE>
 hipError_t launch_cfg(const void *A, const void *W, void *out, const Epi &epi, Rows rows, int N, int K, hipStream_t st,
                       const Timing *tm)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN;
-    constexpr size_t LDS = (size_t)NSTAGE * (BM + BN) * BKB;
-    auto kern = gemm_nt_kernel<T, Epi, TM, TN, NSTAGE>;
+    constexpr size_t LDS = (size_t)NSTAGE * (BM + BN) * BKB + (size_t)Epi::NTAB * BN * sizeof(float);
+    if (N % BN) return hipErrorInvalidValue;
+    if ((K * T::ELEM) % BKB) return hipErrorInvalidValue;
+    auto kern = gemm_nt_kernel<T, Epi, TM, TN, BKB, NSTAGE, KS, WPE>;
     static bool attr_set = false;                                 // > 64 KiB of dynamic LDS must be enabled once
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
@@ -304,20 +391,37 @@ hipError_t launch_cfg(const void *A, const void *W, void *out, const Epi &epi, R
         attr_set = true;
     }
     const int tiles_n = N / BN, tiles_m = (rows.host_rows + BM - 1) / BM, total = tiles_n * tiles_m;
-    hipExtLaunchKernelGGL(kern, dim3(total), dim3(NTHREADS), LDS, st, tm ? tm->start : nullptr, tm ? tm->stop : nullptr, 0,
+    hipExtLaunchKernelGGL(kern, dim3(total), dim3(256 * KS), LDS, st, tm ? tm->start : nullptr, tm ? tm->stop : nullptr, 0,
                           (const char *)A, (const char *)W, (char *)out, epi, rows.host_rows, rows.dev_rows, N, K * T::ELEM,
                           tiles_n, total);
     return hipGetLastError();
 }
 
+// Tile configuration per problem shape (all 128 x 128 tiles; larger tiles did not pay on this chip:
+// the direct-load and LDS paths of a CU, not the MFMA rate, bound the main loop):
+//   0: 64-byte stages, 4-deep ring, 4 waves  (any K that is a multiple of 64 bytes)
+//   1: 128-byte stages (whole cache lines per row), 2-deep ring, 4 waves, 2 blocks per CU
+//   2: as 1 with 8 waves (K split inside the block): for shapes with at most one tile per CU
 template <class T, class Epi>
 hipError_t launch(const void *A, const void *W, void *out, const Epi &epi, Rows rows, int N, int K, hipStream_t st,
                   const Timing *tm)
 {
-    return launch_cfg<T, Epi, 2, 2, 4>(A, W, out, epi, rows, N, K, st, tm);
+    int cfg = gemm_config_override;
+    if ((K * T::ELEM) % 128) cfg = 0;
+    else if (cfg < 0) {
+        const long tiles = (long)(N / 128) * ((rows.host_rows + 127) / 128);
+        cfg = tiles <= 256 ? 2 : 1;
+    }
+    switch (cfg) {
+    case 1: return launch_cfg<T, Epi, 2, 2, 128, 2, 1, 2>(A, W, out, epi, rows, N, K, st, tm);
+    case 2: return launch_cfg<T, Epi, 2, 2, 128, 2, 2, 2>(A, W, out, epi, rows, N, K, st, tm);
+    default: return launch_cfg<T, Epi, 2, 2, 64, 4, 1, 2>(A, W, out, epi, rows, N, K, st, tm);
+    }
 }
 
 }  // namespace
+
+int gemm_config_override = -1;                    // tuning aid: force one tile configuration (see launch())
 
 hipError_t launch_gemm_i8(GemmEpilogue epi, const int8_t *A, const int8_t *W, void *out, const float *m, const float *b,
                           float inv_s_out, Rows rows, int N, int K, hipStream_t st, const Timing *tm)

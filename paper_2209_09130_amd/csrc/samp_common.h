@@ -114,6 +114,7 @@ struct Timing { hipEvent_t start, stop; };                 // optional events at
 struct Rows { int host_rows; const int *dev_rows; };
 
 enum GemmEpilogue { EPI_RAW_I32, EPI_REQUANT, EPI_GELU_QUANT };
+extern int gemm_config_override;                           // < 0: choose the tile configuration by shape
 
 hipError_t launch_gemm_i8(GemmEpilogue epi, const int8_t *A, const int8_t *W, void *out, const float *m, const float *b,
                           float inv_s_out, Rows rows, int N, int K, hipStream_t st, const Timing *tm);
