@@ -36,6 +36,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--groups", type=int, default=0, help="batch groups run concurrently (0 = library default)")
     ap.add_argument("--only-mode", default=None, help="time a single precision mode (FULL_INT8, FP16, ...)")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -81,6 +82,7 @@ def main() -> int:
         modes = w0.modes if mode is None else (mode,) * w0.layers
         enc = enc16 if (mode == P.FP16) else P.Encoder(*cfg, modes, wts, scales, max_batch=w0.batch, max_seq=w0.seq)
         out = torch.empty_like(hid)
+        enc.set_groups(a.groups)
         for _ in range(a.warmup):
             enc.forward(hid, mask, out)
         headline = (name in ("FULL_INT8", "CONFIG"))
@@ -97,19 +99,22 @@ def main() -> int:
             # to that kernel's dispatches (an event-carrying dispatch costs a few microseconds of queue
             # time, so this pass is kept out of the throughput figure above).
             enc.profile(P.PROF_FFN1)
-            for _ in range(a.steps):
+            prof_steps = min(a.steps, 100)
+            for _ in range(prof_steps):
                 enc.forward(hid, mask, out)
             torch.cuda.synchronize()
             kms, launches = enc.profile_read()
             enc.profile(P.PROF_OFF)
             ffn_int8 = bool(modes[0] & 2)
-            ops = 2.0 * T * w0.ffn * w0.hidden
+            # the batch may be cut into groups that run concurrently: one launch covers tokens / groups
+            per_forward = launches / prof_steps
+            ops = 2.0 * T * w0.ffn * w0.hidden * w0.layers / per_forward
             achieved = ops / (kms * 1e-3) / 1e12 if kms > 0 else 0.0
             peak = INT8_PEAK_TOPS if ffn_int8 else FP16_PEAK_TFLOPS
             roof = {"kernel": "gemm_nt_kernel<I8,EpiGeluQuant> (FFN1 GEMM + bias + GELU + quantise)" if ffn_int8
                     else "gemm_nt_kernel<F16,EpiF16> (FFN1)",
                     "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TOP/s" if ffn_int8 else "TFLOP/s",
-                    "frac": achieved / peak, "traffic": None, "launches_timed": launches,
+                    "frac": achieved / peak, "traffic": None, "launches_timed": launches, "launches_per_step": per_forward,
                     "mean_launch_us": kms * 1e3, "ops_per_launch": ops}
         if enc is not enc16:
             enc.close()

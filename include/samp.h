@@ -112,6 +112,18 @@ SAMP_API size_t samp_encoder_workspace_bytes(const samp_encoder_t *enc, int32_t 
 SAMP_API int samp_encoder_forward(samp_encoder_t *enc, const void *hidden, const int32_t *mask, int32_t B, int32_t S,
                                   void *out, void *workspace, size_t workspace_bytes, void *stream);
 
+/* Sequences are independent (all scales are static, Appendix B), so a forward may cut a small batch
+ * into up to 4 groups of sequences that run concurrently on streams owned by the encoder, forked
+ * from and joined back into the caller's stream; results do not depend on the split.  groups = 0
+ * (default) chooses by size, 1 disables the split, 2..4 force it.                                  */
+SAMP_API int samp_encoder_set_groups(samp_encoder_t *enc, int32_t groups);
+
+/* A forward is a few hundred short kernels, so by default the library records them once per distinct
+ * argument set (pointers, B, S) into a HIP graph -- on the second call with those arguments, on a
+ * stream of its own -- and replays that graph on the caller's stream afterwards.  enabled = 0 keeps
+ * plain launches.  Timing via samp_encoder_profile always uses plain launches.                     */
+SAMP_API int samp_encoder_set_graph(samp_encoder_t *enc, int32_t enabled);
+
 /* Min-max calibration (Table 2 caption; Appendix B): runs the all-FP16 encoder `enc` (every mode
  * must be SAMP_FP16) on a calibration batch and returns, per layer, absmax/127 of the ten tensors
  * of samp_layer_scales_t.  Same argument rules as samp_encoder_forward; no output tensor.
@@ -168,7 +180,7 @@ SAMP_API int samp_attention_f16(const uint16_t *qkv, const int32_t *cu_seqlens, 
 
 /* The fused step of Section 3.2: z = deq(in) + bias + deq(res); y = LayerNorm(z; gamma, beta, eps);
  * out = quantised y (int8, step s_out) or fp16 y.  in/res/out: dev [M,H], int8 when the matching
- * *_i8 flag is set (then s_in / s_res / s_out are their steps), else fp16.  H % 4 == 0, H <= 2048.  */
+ * *_i8 flag is set (then s_in / s_res / s_out are their steps), else fp16.  H % 16 == 0, H <= 2048. */
 SAMP_API int samp_add_ln(const void *in, int32_t in_i8, float s_in, const float *bias, const void *res, int32_t res_i8,
                          float s_res, const float *gamma, const float *beta, float eps, void *out, int32_t out_i8,
                          float s_out, int32_t M, int32_t H, void *stream);

@@ -148,6 +148,12 @@ class Encoder:
                                             _stream(), out))
         return np.array([[getattr(out[i], n) for n in SCALE_FIELDS] for i in range(self.layers)], np.float32)
 
+    def set_groups(self, groups: int):
+        _check(lib().samp_encoder_set_groups(self._h, int(groups)))
+
+    def set_graph(self, enabled: bool):
+        _check(lib().samp_encoder_set_graph(self._h, int(bool(enabled))))
+
     def profile(self, which: int):
         _check(lib().samp_encoder_profile(self._h, int(which)))
 

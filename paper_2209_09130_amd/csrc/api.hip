@@ -84,6 +84,8 @@ constexpr int MAX_EVENTS = 4096;
 
 }  // namespace
 
+constexpr int MAX_GROUPS = 4;
+
 struct samp_encoder {
     samp_config_t cfg;
     std::vector<Layer> L;
@@ -91,6 +93,18 @@ struct samp_encoder {
     int prof_which = SAMP_PROF_OFF;
     std::vector<Timing> events;                     // pool, created on first use
     int events_used = 0;
+    // batch-group concurrency: sequences are independent, so a small batch is cut into groups that
+    // run on side streams at the same time (their kernels are far too short to fill the chip alone)
+    int groups_wanted = 0;                          // 0 = choose by size
+    hipStream_t side[MAX_GROUPS - 1] = {};
+    hipEvent_t fork = nullptr, join[MAX_GROUPS - 1] = {};
+    bool streams_ready = false;
+    // whole-forward HIP graphs, one per distinct argument set (the forward is launch-bound: a few
+    // hundred kernels of 5..30 microseconds); captured on an internal stream, replayed on the caller's
+    struct Graph { const void *hidden, *mask, *out, *ws; int B, S, G; int seen; hipGraphExec_t exec; };
+    std::vector<Graph> graphs;
+    bool graphs_enabled = true;
+    hipStream_t cap = nullptr;
 };
 
 namespace {
@@ -104,6 +118,15 @@ const Timing *timing(samp_encoder *e, int which)
         e->events.push_back(t);
     }
     return &e->events[e->events_used++];
+}
+
+int choose_groups(const samp_encoder *e, int B, int S)
+{
+    int g = e->groups_wanted;
+    if (g <= 0) g = ((long)B * S <= 16384) ? 2 : 1;   // measured: two groups help small batches, more do not
+    if (g > MAX_GROUPS) g = MAX_GROUPS;
+    if (g > B) g = B;
+    return g;
 }
 
 struct Workspace {
@@ -360,7 +383,55 @@ int samp_encoder_create(const samp_config_t *cfg, const uint8_t *modes, const sa
 size_t samp_encoder_workspace_bytes(const samp_encoder_t *enc, int32_t B, int32_t S)
 {
     if (!enc || B < 1 || S < 1) { fail(SAMP_ERR_ARG, "encoder is NULL or B, S < 1"); return 0; }
-    return carve(enc->cfg, B, S, nullptr).bytes;
+    // enough for the whole batch in one piece and for any split into up to MAX_GROUPS groups
+    size_t need = carve(enc->cfg, B, S, nullptr).bytes;
+    for (int g = 2; g <= MAX_GROUPS && g <= B; g++) {
+        const size_t split = (size_t)g * carve(enc->cfg, (B + g - 1) / g, S, nullptr).bytes;
+        if (split > need) need = split;
+    }
+    return need;
+}
+
+int samp_encoder_set_groups(samp_encoder_t *enc, int32_t groups)
+{
+    if (!enc) return fail(SAMP_ERR_ARG, "encoder is NULL");
+    if (groups < 0 || groups > MAX_GROUPS) return fail(SAMP_ERR_ARG, "groups must be in [0, %d]", MAX_GROUPS);
+    enc->groups_wanted = groups;
+    return SAMP_OK;
+}
+
+static int forward_eager(samp_encoder_t *enc, const void *hidden, const int32_t *mask, int32_t B, int32_t S, void *out,
+                         void *workspace, hipStream_t st)
+{
+    const int G = choose_groups(enc, B, S);
+    if (G == 1) return run(enc, hidden, mask, B, S, out, workspace, st, false);
+    if (!enc->streams_ready) {
+        for (int i = 0; i < MAX_GROUPS - 1; i++) {
+            HIP_TRY(hipStreamCreateWithFlags(&enc->side[i], hipStreamNonBlocking));
+            HIP_TRY(hipEventCreateWithFlags(&enc->join[i], hipEventDisableTiming));
+        }
+        HIP_TRY(hipEventCreateWithFlags(&enc->fork, hipEventDisableTiming));
+        enc->streams_ready = true;
+    }
+    // group g owns sequences [g*Bg, ...): its slice of hidden / mask / out and its own workspace piece
+    const int Bg = (B + G - 1) / G;
+    const size_t piece = carve(enc->cfg, Bg, S, nullptr).bytes;
+    const size_t seq_elems = (size_t)S * enc->cfg.hidden;
+    HIP_TRY(hipEventRecord(enc->fork, st));
+    for (int g = 0; g < G; g++) {
+        const int b0 = g * Bg, nb = std::min(Bg, B - b0);
+        if (nb <= 0) break;
+        hipStream_t gs = g == 0 ? st : enc->side[g - 1];
+        if (g > 0) HIP_TRY(hipStreamWaitEvent(gs, enc->fork, 0));
+        const int rc = run(enc, (const __half *)hidden + b0 * seq_elems, mask ? mask + (size_t)b0 * S : nullptr, nb, S,
+                           (__half *)out + b0 * seq_elems, (char *)workspace + g * piece, gs, false);
+        if (rc != SAMP_OK) return rc;
+        if (g > 0) {
+            HIP_TRY(hipEventRecord(enc->join[g - 1], gs));
+            HIP_TRY(hipStreamWaitEvent(st, enc->join[g - 1], 0));
+        }
+    }
+    return SAMP_OK;
 }
 
 int samp_encoder_forward(samp_encoder_t *enc, const void *hidden, const int32_t *mask, int32_t B, int32_t S, void *out,
@@ -370,7 +441,48 @@ int samp_encoder_forward(samp_encoder_t *enc, const void *hidden, const int32_t 
     if (!out) return fail(SAMP_ERR_ARG, "out is NULL");
     if (out == hidden) return fail(SAMP_ERR_ARG, "out must not alias hidden");
     if (!aligned(out, 16)) return fail(SAMP_ERR_ARG, "out must be 16-byte aligned");
-    return run(enc, hidden, mask, B, S, out, workspace, static_cast<hipStream_t>(stream), false);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (!enc->graphs_enabled || enc->prof_which != SAMP_PROF_OFF) return forward_eager(enc, hidden, mask, B, S, out, workspace, st);
+
+    const int G = choose_groups(enc, B, S);
+    samp_encoder::Graph *g = nullptr;
+    for (auto &e : enc->graphs)
+        if (e.hidden == hidden && e.mask == mask && e.out == out && e.ws == workspace && e.B == B && e.S == S && e.G == G) g = &e;
+    if (g && g->exec) { HIP_TRY(hipGraphLaunch(g->exec, st)); return SAMP_OK; }
+    if (!g) {                                       // first sight of these arguments: run eagerly (one-off set-up happens here)
+        if (enc->graphs.size() >= 8) {
+            if (enc->graphs.front().exec) (void)hipGraphExecDestroy(enc->graphs.front().exec);
+            enc->graphs.erase(enc->graphs.begin());
+        }
+        enc->graphs.push_back({hidden, mask, out, workspace, B, S, G, 1, nullptr});
+        return forward_eager(enc, hidden, mask, B, S, out, workspace, st);
+    }
+    // second sight: record the same launches into a graph on an internal stream, then replay it
+    if (!enc->cap) HIP_TRY(hipStreamCreateWithFlags(&enc->cap, hipStreamNonBlocking));
+    hipGraph_t graph = nullptr;
+    hipError_t e = hipStreamBeginCapture(enc->cap, hipStreamCaptureModeRelaxed);
+    int rc = SAMP_OK;
+    if (e == hipSuccess) {
+        rc = forward_eager(enc, hidden, mask, B, S, out, workspace, enc->cap);
+        e = hipStreamEndCapture(enc->cap, &graph);
+    }
+    if (e == hipSuccess && rc == SAMP_OK) e = hipGraphInstantiate(&g->exec, graph, nullptr, nullptr, 0);
+    if (graph) (void)hipGraphDestroy(graph);
+    if (e != hipSuccess || rc != SAMP_OK || !g->exec) {  // capture not possible here: stay with plain launches
+        (void)hipGetLastError();
+        g->exec = nullptr;
+        enc->graphs_enabled = false;
+        return forward_eager(enc, hidden, mask, B, S, out, workspace, st);
+    }
+    HIP_TRY(hipGraphLaunch(g->exec, st));
+    return SAMP_OK;
+}
+
+int samp_encoder_set_graph(samp_encoder_t *enc, int32_t enabled)
+{
+    if (!enc) return fail(SAMP_ERR_ARG, "encoder is NULL");
+    enc->graphs_enabled = enabled != 0;
+    return SAMP_OK;
 }
 
 int samp_encoder_calibrate(samp_encoder_t *enc, const void *hidden, const int32_t *mask, int32_t B, int32_t S,
@@ -395,6 +507,12 @@ int samp_encoder_destroy(samp_encoder_t *enc)
 {
     if (!enc) return SAMP_OK;
     for (Timing &t : enc->events) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
+    if (enc->streams_ready) {
+        for (int i = 0; i < MAX_GROUPS - 1; i++) { (void)hipStreamDestroy(enc->side[i]); (void)hipEventDestroy(enc->join[i]); }
+        (void)hipEventDestroy(enc->fork);
+    }
+    for (auto &g : enc->graphs) if (g.exec) (void)hipGraphExecDestroy(g.exec);
+    if (enc->cap) (void)hipStreamDestroy(enc->cap);
     delete enc;
     return SAMP_OK;
 }
@@ -504,7 +622,7 @@ int samp_add_ln(const void *in, int32_t in_i8, float s_in, const float *bias, co
                 void *stream)
 {
     if (!in || !bias || !res || !gamma || !beta || !out) return fail(SAMP_ERR_ARG, "NULL pointer");
-    if (M < 1 || H < 4 || H % 4 || H > 2048) return fail(SAMP_ERR_SHAPE, "M >= 1, H %% 4 == 0, H <= 2048 required");
+    if (M < 1 || H < 16 || H % 16 || H > 2048) return fail(SAMP_ERR_SHAPE, "M >= 1, H %% 16 == 0, H <= 2048 required");
     if ((in_i8 && !good_scale(s_in)) || (res_i8 && !good_scale(s_res)) || (out_i8 && !good_scale(s_out)))
         return fail(SAMP_ERR_SCALE, "a step of an int8 operand is not finite and positive");
     AddLnArgs a{in, in_i8 != 0, s_in, bias, res, res_i8 != 0, s_res, gamma, beta, eps, out, out_i8 != 0, s_out,

@@ -24,6 +24,31 @@ constexpr int QB = 32;                 // queries per block
 constexpr int VT_STRIDE_I8 = 36;       // bytes per V^T row (32 keys + pad), int8
 constexpr int VT_STRIDE_F16 = 72;      // bytes per V^T row (32 keys + pad), fp16
 
+// exp(x) for x <= 0 in binary64: x = k ln2 + r with |r| <= ln2 / 2 (two-part ln2), Taylor polynomial
+// of degree 11 in r (truncation below 2^-47), scaled by 2^k.  Its error is far below a binary32
+// ulp, so rounding the result to binary32 gives the correctly rounded exponential (up to ties
+// narrower than 2^-45), which is what the quantiser's decision is defined on.
+__device__ __forceinline__ double exp_nonpos(double x)
+{
+    x = __builtin_fmax(x, -746.0);                       // also maps -inf (masked keys) to an underflowing value
+    const double k = __builtin_rint(x * 1.44269504088896338700e+00);
+    double r = __builtin_fma(k, -6.93147180369123816490e-01, x);
+    r = __builtin_fma(k, -1.90821492927058770002e-10, r);
+    double p = 2.50521083854417187751e-08;               // 1/11!
+    p = __builtin_fma(p, r, 2.75573192239858906526e-07); // 1/10!
+    p = __builtin_fma(p, r, 2.75573192239858906526e-06); // 1/9!
+    p = __builtin_fma(p, r, 2.48015873015873015873e-05); // 1/8!
+    p = __builtin_fma(p, r, 1.98412698412698412698e-04); // 1/7!
+    p = __builtin_fma(p, r, 1.38888888888888888889e-03); // 1/6!
+    p = __builtin_fma(p, r, 8.33333333333333333333e-03); // 1/5!
+    p = __builtin_fma(p, r, 4.16666666666666666667e-02); // 1/4!
+    p = __builtin_fma(p, r, 1.66666666666666666667e-01); // 1/3!
+    p = __builtin_fma(p, r, 5.00000000000000000000e-01);
+    p = __builtin_fma(p, r, 1.0);
+    p = __builtin_fma(p, r, 1.0);
+    return __builtin_ldexp(p, (int)k);
+}
+
 struct SeqInfo { int t0, n; };
 __device__ __forceinline__ SeqInfo seq_info(const int *cu, int b, int max_len)
 {
@@ -69,15 +94,23 @@ __global__ __launch_bounds__(256) void attention_i8_kernel(const int8_t *__restr
 #pragma unroll
             for (int ks = 0; ks < 2; ks++)
                 acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(*reinterpret_cast<const v4i *>(kp + ks * 32 + g * 16), qf[ks], acc, 0, 0, 0);
-            // stage V^T of this key tile: lane copies 2 x 16 channels of one key, byte by byte
+            // stage V^T of this key tile: a lane transposes two 4 keys x 4 channels byte blocks in
+            // registers (v_perm_b32) and stores them as dwords of 4 consecutive keys per channel
             const int8_t *vp = base + 2 * H;
 #pragma unroll
             for (int u = 0; u < 2; u++) {
-                const int idx = lane + 64 * u, key = idx >> 2, c0 = (idx & 3) * 16;
-                const v4i v = *reinterpret_cast<const v4i *>(vp + (size_t)min(j0 + key, n - 1) * ld + c0);
+                const int cq = lane & 15, kq = (lane >> 4) + 4 * u;
+                unsigned d[4];
 #pragma unroll
-                for (int e = 0; e < 16; e++)
-                    vt[w][i][(c0 + e) * VT_STRIDE_I8 + key] = (int8_t)(v[e >> 2] >> (8 * (e & 3)));
+                for (int t = 0; t < 4; t++)
+                    d[t] = *reinterpret_cast<const unsigned *>(vp + (size_t)min(j0 + 4 * kq + t, n - 1) * ld + 4 * cq);
+                const unsigned t01l = __builtin_amdgcn_perm(d[1], d[0], 0x05010400u), t23l = __builtin_amdgcn_perm(d[3], d[2], 0x05010400u);
+                const unsigned t01h = __builtin_amdgcn_perm(d[1], d[0], 0x07030602u), t23h = __builtin_amdgcn_perm(d[3], d[2], 0x07030602u);
+                unsigned *dst = reinterpret_cast<unsigned *>(&vt[w][i][(4 * cq) * VT_STRIDE_I8 + 4 * kq]);
+                dst[0 * (VT_STRIDE_I8 / 4)] = __builtin_amdgcn_perm(t23l, t01l, 0x05040100u);
+                dst[1 * (VT_STRIDE_I8 / 4)] = __builtin_amdgcn_perm(t23l, t01l, 0x07060302u);
+                dst[2 * (VT_STRIDE_I8 / 4)] = __builtin_amdgcn_perm(t23h, t01h, 0x05040100u);
+                dst[3 * (VT_STRIDE_I8 / 4)] = __builtin_amdgcn_perm(t23h, t01h, 0x07060302u);
             }
 #pragma unroll
             for (int e = 0; e < 16; e++) {
@@ -100,7 +133,7 @@ __global__ __launch_bounds__(256) void attention_i8_kernel(const int8_t *__restr
     for (int i = 0; i < NT; i++)
 #pragma unroll
         for (int e = 0; e < 16; e++) {
-            const float ev = (float)exp((double)(sc[i][e] - mx));     // exp(-inf) = 0 for masked keys
+            const float ev = (float)exp_nonpos((double)(sc[i][e] - mx));   // 0 for masked keys (score -inf)
             sc[i][e] = ev;
             part += (double)ev;
         }
@@ -284,13 +317,12 @@ hipError_t launch_attention_i8(const int8_t *qkv, const int *cu, int B, int max_
                                float inv_sp, float m_ctx, int8_t *ctx, hipStream_t st, const Timing *tm)
 {
     dim3 grid((max_len + QB - 1) / QB, heads, B), block(256);
-    hipEvent_t e0 = tm ? tm->start : nullptr, e1 = tm ? tm->stop : nullptr;
     if (max_len <= 128)
-        hipExtLaunchKernelGGL((attention_i8_kernel<1>), grid, block, 0, st, e0, e1, 0, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx);
+        launch_kernel(attention_i8_kernel<1>, grid, block, 0, st, tm, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx);
     else if (max_len <= 256)
-        hipExtLaunchKernelGGL((attention_i8_kernel<2>), grid, block, 0, st, e0, e1, 0, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx);
+        launch_kernel(attention_i8_kernel<2>, grid, block, 0, st, tm, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx);
     else
-        hipExtLaunchKernelGGL((attention_i8_kernel<4>), grid, block, 0, st, e0, e1, 0, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx);
+        launch_kernel(attention_i8_kernel<4>, grid, block, 0, st, tm, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx);
     return hipGetLastError();
 }
 
@@ -298,13 +330,12 @@ hipError_t launch_attention_f16(const __half *qkv, const int *cu, int B, int max
                                 __half *ctx, float *p_absmax, hipStream_t st, const Timing *tm)
 {
     dim3 grid((max_len + QB - 1) / QB, heads, B), block(256);
-    hipEvent_t e0 = tm ? tm->start : nullptr, e1 = tm ? tm->stop : nullptr;
     if (max_len <= 128)
-        hipExtLaunchKernelGGL((attention_f16_kernel<1>), grid, block, 0, st, e0, e1, 0, qkv, cu, max_len, H, scale, ctx, p_absmax);
+        launch_kernel(attention_f16_kernel<1>, grid, block, 0, st, tm, qkv, cu, max_len, H, scale, ctx, p_absmax);
     else if (max_len <= 256)
-        hipExtLaunchKernelGGL((attention_f16_kernel<2>), grid, block, 0, st, e0, e1, 0, qkv, cu, max_len, H, scale, ctx, p_absmax);
+        launch_kernel(attention_f16_kernel<2>, grid, block, 0, st, tm, qkv, cu, max_len, H, scale, ctx, p_absmax);
     else
-        hipExtLaunchKernelGGL((attention_f16_kernel<4>), grid, block, 0, st, e0, e1, 0, qkv, cu, max_len, H, scale, ctx, p_absmax);
+        launch_kernel(attention_f16_kernel<4>, grid, block, 0, st, tm, qkv, cu, max_len, H, scale, ctx, p_absmax);
     return hipGetLastError();
 }
 

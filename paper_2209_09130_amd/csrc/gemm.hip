@@ -391,7 +391,7 @@ hipError_t launch_cfg(const void *A, const void *W, void *out, const Epi &epi, R
         attr_set = true;
     }
     const int tiles_n = N / BN, tiles_m = (rows.host_rows + BM - 1) / BM, total = tiles_n * tiles_m;
-    hipExtLaunchKernelGGL(kern, dim3(total), dim3(256 * KS), LDS, st, tm ? tm->start : nullptr, tm ? tm->stop : nullptr, 0,
+    launch_kernel(kern, dim3(total), dim3(256 * KS), LDS, st, tm,
                           (const char *)A, (const char *)W, (char *)out, epi, rows.host_rows, rows.dev_rows, N, K * T::ELEM,
                           tiles_n, total);
     return hipGetLastError();

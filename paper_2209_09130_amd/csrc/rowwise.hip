@@ -9,63 +9,99 @@ namespace samp {
 namespace {
 
 // ---------------------------------------------------------------------------------------------
-// Fused step: one wave per token row, lane l owns channels 4l..4l+3 of every 256-channel slab.
+// Fused step: 16 lanes per token row (4 rows per wave); a lane owns 16 consecutive channels of
+// every 256-channel slab, so that a row is read with 16-byte (int8) / 32-byte (fp16) accesses
+// and its statistics are reduced inside one DPP row (four register-to-register steps).
 //   z = fmaf(in_q, s_in, bias) or in + bias;  z = fmaf(res_q, s_res, z) or z + res
 //   mean / variance in binary64 (two passes over registers), rounded once to binary32
 //   y = fmaf((z - mu) * rstd, gamma, beta);  out = rne(y / s_out) or fp16(y)
 // ---------------------------------------------------------------------------------------------
+template <int CTRL> __device__ __forceinline__ int dpp_mov(int v)
+{ return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true); }
+
+template <int CTRL> __device__ __forceinline__ double dpp_mov(double v)
+{
+    const long long b = __double_as_longlong(v);
+    const int lo = dpp_mov<CTRL>((int)b), hi = dpp_mov<CTRL>((int)(b >> 32));
+    return __longlong_as_double(((long long)hi << 32) | (unsigned)lo);
+}
+
+// sum over the 16 lanes of a DPP row; every lane ends with the same bits (the adds commute)
+__device__ __forceinline__ double row16_sum(double v)
+{
+    v += dpp_mov<0xB1>(v);            // quad_perm [1,0,3,2]
+    v += dpp_mov<0x4E>(v);            // quad_perm [2,3,0,1]
+    v += dpp_mov<0x141>(v);           // row_half_mirror
+    v += dpp_mov<0x140>(v);           // row_mirror
+    return v;
+}
+__device__ __forceinline__ float row16_max(float v)
+{
+    v = __builtin_fmaxf(v, __int_as_float(dpp_mov<0xB1>(__float_as_int(v))));
+    v = __builtin_fmaxf(v, __int_as_float(dpp_mov<0x4E>(__float_as_int(v))));
+    v = __builtin_fmaxf(v, __int_as_float(dpp_mov<0x141>(__float_as_int(v))));
+    v = __builtin_fmaxf(v, __int_as_float(dpp_mov<0x140>(__float_as_int(v))));
+    return v;
+}
+
+template <bool I8> __device__ __forceinline__ void load16(const void *p, size_t elem, float (&v)[16])
+{
+    if (I8) {
+        const v4i q = *reinterpret_cast<const v4i *>((const int8_t *)p + elem);
+#pragma unroll
+        for (int e = 0; e < 16; e++) v[e] = (float)(int8_t)(q[e >> 2] >> (8 * (e & 3)));
+    } else {
+        const v8h a = *reinterpret_cast<const v8h *>((const __half *)p + elem);
+        const v8h b = *reinterpret_cast<const v8h *>((const __half *)p + elem + 8);
+#pragma unroll
+        for (int e = 0; e < 8; e++) { v[e] = (float)a[e]; v[8 + e] = (float)b[e]; }
+    }
+}
+
 template <int NJ, bool IN_I8, bool RES_I8, bool OUT_I8>
 __global__ __launch_bounds__(256) void add_ln_kernel(AddLnArgs a)
 {
     const int M = a.rows.dev_rows ? *a.rows.dev_rows : a.rows.host_rows;
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= M) return;
-    const int lane = threadIdx.x & 63, H = a.H;
+    const int row = blockIdx.x * 16 + (threadIdx.x >> 4);
+    if (row >= M) return;                               // whole 16-lane rows leave together
+    const int sub = threadIdx.x & 15, H = a.H;
     const size_t base = (size_t)row * H;
 
-    float z[NJ][4];
+    float z[NJ][16];
     double sum = 0.0;
 #pragma unroll
     for (int j = 0; j < NJ; j++) {
-        const int c = j * 256 + lane * 4;
+        const int c = j * 256 + sub * 16;
         if (c < H) {
-            const v4f bb = *reinterpret_cast<const v4f *>(a.bias + c);
-            float t[4];
-            if (IN_I8) {
-                const int p = *reinterpret_cast<const int *>((const int8_t *)a.in + base + c);
+            float x[16], r[16];
+            load16<IN_I8>(a.in, base + c, x);
+            load16<RES_I8>(a.res, base + c, r);
 #pragma unroll
-                for (int e = 0; e < 4; e++) t[e] = __builtin_fmaf((float)(int8_t)(p >> (8 * e)), a.s_in, bb[e]);
-            } else {
-                const v4h p = *reinterpret_cast<const v4h *>((const __half *)a.in + base + c);
+            for (int q = 0; q < 4; q++) {
+                const v4f bb = *reinterpret_cast<const v4f *>(a.bias + c + 4 * q);
 #pragma unroll
-                for (int e = 0; e < 4; e++) t[e] = (float)p[e] + bb[e];
+                for (int t = 0; t < 4; t++) {
+                    const int e = 4 * q + t;
+                    const float u = IN_I8 ? __builtin_fmaf(x[e], a.s_in, bb[t]) : x[e] + bb[t];
+                    z[j][e] = RES_I8 ? __builtin_fmaf(r[e], a.s_res, u) : u + r[e];
+                    sum += (double)z[j][e];
+                }
             }
-            if (RES_I8) {
-                const int p = *reinterpret_cast<const int *>((const int8_t *)a.res + base + c);
-#pragma unroll
-                for (int e = 0; e < 4; e++) z[j][e] = __builtin_fmaf((float)(int8_t)(p >> (8 * e)), a.s_res, t[e]);
-            } else {
-                const v4h p = *reinterpret_cast<const v4h *>((const __half *)a.res + base + c);
-#pragma unroll
-                for (int e = 0; e < 4; e++) z[j][e] = t[e] + (float)p[e];
-            }
-#pragma unroll
-            for (int e = 0; e < 4; e++) sum += (double)z[j][e];
         } else {
 #pragma unroll
-            for (int e = 0; e < 4; e++) z[j][e] = 0.0f;
+            for (int e = 0; e < 16; e++) z[j][e] = 0.0f;
         }
     }
-    const double mu = wave_sum(sum) / (double)H;
+    const double mu = row16_sum(sum) / (double)H;
     double sq = 0.0;
 #pragma unroll
     for (int j = 0; j < NJ; j++) {
-        if (j * 256 + lane * 4 < H) {
+        if (j * 256 + sub * 16 < H) {
 #pragma unroll
-            for (int e = 0; e < 4; e++) { const double d = (double)z[j][e] - mu; sq += d * d; }
+            for (int e = 0; e < 16; e++) { const double d = (double)z[j][e] - mu; sq += d * d; }
         }
     }
-    const double var = wave_sum(sq) / (double)H;
+    const double var = row16_sum(sq) / (double)H;
     const float mu32 = (float)mu;
     const float rstd32 = (float)(1.0 / sqrt(var + (double)a.eps));
     const float inv_s = OUT_I8 ? 1.0f / a.s_out : 0.0f;
@@ -73,40 +109,50 @@ __global__ __launch_bounds__(256) void add_ln_kernel(AddLnArgs a)
     float amax = 0.0f;
 #pragma unroll
     for (int j = 0; j < NJ; j++) {
-        const int c = j * 256 + lane * 4;
+        const int c = j * 256 + sub * 16;
         if (c < H) {
-            const v4f gg = *reinterpret_cast<const v4f *>(a.gamma + c);
-            const v4f be = *reinterpret_cast<const v4f *>(a.beta + c);
-            float y[4];
+            float y[16];
 #pragma unroll
-            for (int e = 0; e < 4; e++) y[e] = __builtin_fmaf((z[j][e] - mu32) * rstd32, gg[e], be[e]);
+            for (int q = 0; q < 4; q++) {
+                const v4f gg = *reinterpret_cast<const v4f *>(a.gamma + c + 4 * q);
+                const v4f be = *reinterpret_cast<const v4f *>(a.beta + c + 4 * q);
+#pragma unroll
+                for (int t = 0; t < 4; t++)
+                    y[4 * q + t] = __builtin_fmaf((z[j][4 * q + t] - mu32) * rstd32, gg[t], be[t]);
+            }
             if (OUT_I8) {
-                *reinterpret_cast<int *>((int8_t *)a.out + obase + c) =
-                    pack4(qcode(y[0] * inv_s), qcode(y[1] * inv_s), qcode(y[2] * inv_s), qcode(y[3] * inv_s));
+                v4i o;
+#pragma unroll
+                for (int q = 0; q < 4; q++)
+                    o[q] = pack4(qcode(y[4 * q] * inv_s), qcode(y[4 * q + 1] * inv_s), qcode(y[4 * q + 2] * inv_s), qcode(y[4 * q + 3] * inv_s));
+                *reinterpret_cast<v4i *>((int8_t *)a.out + obase + c) = o;
             } else {
-                const v4h h = {to_half(y[0]), to_half(y[1]), to_half(y[2]), to_half(y[3])};
-                *reinterpret_cast<v4h *>((__half *)a.out + obase + c) = h;
+                v8h h0, h1;
+#pragma unroll
+                for (int e = 0; e < 8; e++) { h0[e] = to_half(y[e]); h1[e] = to_half(y[8 + e]); }
+                *reinterpret_cast<v8h *>((__half *)a.out + obase + c) = h0;
+                *reinterpret_cast<v8h *>((__half *)a.out + obase + c + 8) = h1;
                 if (a.absmax_out) {
 #pragma unroll
-                    for (int e = 0; e < 4; e++) amax = __builtin_fmaxf(amax, __builtin_fabsf((float)h[e]));
+                    for (int e = 0; e < 8; e++)
+                        amax = __builtin_fmaxf(amax, __builtin_fmaxf(__builtin_fabsf((float)h0[e]), __builtin_fabsf((float)h1[e])));
                 }
             }
         }
     }
     if (!OUT_I8 && a.absmax_out) {
-        amax = wave_max(amax);
-        if (lane == 0) atomicMax(reinterpret_cast<int *>(a.absmax_out), __float_as_int(amax));   // values >= 0
+        amax = row16_max(amax);
+        if (sub == 0) atomicMax(reinterpret_cast<int *>(a.absmax_out), __float_as_int(amax));   // values >= 0
     }
 }
 
 template <int NJ>
 hipError_t launch_add_ln_nj(const AddLnArgs &a, hipStream_t st, const Timing *tm)
 {
-    dim3 grid((a.rows.host_rows + 3) / 4), block(256);
-    hipEvent_t e0 = tm ? tm->start : nullptr, e1 = tm ? tm->stop : nullptr;
+    dim3 grid((a.rows.host_rows + 15) / 16), block(256);
 #define SAMP_LN_CASE(I, R, O)                                                                              \
     if (a.in_i8 == I && a.res_i8 == R && a.out_i8 == O) {                                                  \
-        hipExtLaunchKernelGGL((add_ln_kernel<NJ, I, R, O>), grid, block, 0, st, e0, e1, 0, a);             \
+        launch_kernel(add_ln_kernel<NJ, I, R, O>, grid, block, 0, st, tm, a);                           \
         return hipGetLastError();                                                                          \
     }
     SAMP_LN_CASE(true, true, true) SAMP_LN_CASE(true, true, false) SAMP_LN_CASE(false, false, true)
@@ -295,7 +341,7 @@ hipError_t launch_pack_rows(const __half *hidden, const int *cu, int B, int S, i
                             int *row_map, __half *out_zero_pad, hipStream_t st, const Timing *tm)
 {
     dim3 grid((B * S + 3) / 4), block(256);
-    hipExtLaunchKernelGGL(pack_rows_kernel, grid, block, 0, st, tm ? tm->start : nullptr, tm ? tm->stop : nullptr, 0,
+    launch_kernel(pack_rows_kernel, grid, block, 0, st, tm,
                           hidden, cu, B, S, H, s_x, packed, row_map, out_zero_pad);
     return hipGetLastError();
 }
@@ -305,8 +351,7 @@ hipError_t launch_quantize_rows(const __half *x, size_t n, float s_x, int8_t *ou
     const size_t n8 = n / 8;
     size_t blocks = (n8 + 255) / 256;
     if (blocks > 8192) blocks = 8192;
-    hipExtLaunchKernelGGL(quantize_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, st, tm ? tm->start : nullptr,
-                          tm ? tm->stop : nullptr, 0, x, n8, s_x, out);
+    launch_kernel(quantize_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, st, tm, x, n8, s_x, out);
     return hipGetLastError();
 }
 

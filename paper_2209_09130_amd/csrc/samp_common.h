@@ -110,6 +110,15 @@ __device__ __forceinline__ float wave_max(float v)
 // ---- host-side launcher interface (implemented in the .hip files) -------------------------------
 struct Timing { hipEvent_t start, stop; };                 // optional events attached to one dispatch
 
+// Plain launch, or (tm != nullptr) a launch whose dispatch carries start/stop events.  Event-carrying
+// dispatches cannot be captured into a graph, so they are only used when timing was asked for.
+template <class K, class... Args>
+inline void launch_kernel(K kern, dim3 grid, dim3 block, size_t lds, hipStream_t st, const Timing *tm, Args... args)
+{
+    if (tm) hipExtLaunchKernelGGL(kern, grid, block, lds, st, tm->start, tm->stop, 0, args...);
+    else hipLaunchKernelGGL(kern, grid, block, lds, st, args...);
+}
+
 // Row limit of a launch: rows = *dev_rows if dev_rows != nullptr, else host_rows.
 struct Rows { int host_rows; const int *dev_rows; };
 

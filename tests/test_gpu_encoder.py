@@ -47,11 +47,17 @@ def run_gpu(P, w, wts, sc, hid, mask):
     enc = P.Encoder(*args(w), w.modes, wts, sc, max_batch=hid.shape[0], max_seq=hid.shape[1])
     h = torch.from_numpy(hid).cuda()
     m = None if mask is None else torch.from_numpy(mask).cuda()
-    out = enc.forward(h, m)
+    res = torch.empty_like(h)
+    out = enc.forward(h, m, res).clone()        # first call: plain launches
     torch.cuda.synchronize()
-    out2 = enc.forward(h, m)            # determinism: a second run is bit-identical
-    torch.cuda.synchronize()
-    assert torch.equal(out, out2)
+    # second call records a HIP graph and replays it, later calls replay it; eager work and
+    # synchronisations in between; every result must be bit-identical to the first
+    for _ in range(3):
+        res.fill_(7.0)
+        torch.cuda.synchronize()
+        out2 = enc.forward(h, m, res)
+        torch.cuda.synchronize()
+        assert torch.equal(out, out2)
     enc.close()
     return out.cpu().numpy()
 
@@ -264,6 +270,37 @@ def test_gpu_calibration_matches_the_oracle_calibration(P):
     # the GPU calibrates on its fp16 forward, the oracle on the unrounded model: steps agree to fp16 accuracy
     assert np.abs(got / want - 1).max() < 1e-2
     assert got[0, 0] == want[0, 0]                       # the input's absmax is exact
+
+
+@pytest.mark.parametrize("varlen", [False, True])
+def test_batch_groups_and_graph_replay_do_not_change_results(P, varlen):
+    """The forward may split the batch over concurrent streams and replay a recorded graph; neither
+    may change a bit (sequences are independent: all scales are static)."""
+    import torch
+    w = W.bert_base("grp", 2, 7, 64, (FULL_INT8, FFN_INT8), varlen=varlen, plain_params=False)
+    wts = W.make_weights(w)
+    hid, lens, mask = W.make_hidden(w)
+    sc = oracle.calibrate(*args(w), wts, W.make_calibration_batch(w))
+    h = torch.from_numpy(hid).cuda()
+    m = torch.from_numpy(mask).cuda() if varlen else None
+    enc = P.Encoder(*args(w), w.modes, wts, sc, max_batch=w.batch, max_seq=w.seq)
+    enc.set_graph(False)
+    enc.set_groups(1)
+    base = enc.forward(h, m).clone()
+    torch.cuda.synchronize()
+    for groups in (2, 3, 4, 0):
+        for graph in (False, True):
+            enc.set_groups(groups)
+            enc.set_graph(graph)
+            res = torch.empty_like(h)
+            for rep in range(4):
+                res.fill_(-3.0)
+                out = enc.forward(h, m, res)
+                torch.cuda.synchronize()
+                assert torch.equal(out, base), (groups, graph, rep)
+    enc.close()
+    want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid, lens)
+    compare(base.cpu().numpy(), want, lens, False, f"groups/graph varlen={varlen}")
 
 
 def test_error_paths_on_the_device_side(P):
