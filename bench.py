@@ -24,6 +24,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+# HBM bytes per launch of the dominant kernel, from profiles/c2_full_int8_hbm_traffic.txt (rocprofv3 FETCH_SIZE x 2.0 +
+# WRITE_SIZE x 1.0, factors from a 256 MiB copy): workload C2, full-INT8, FFN1 kernel, 2048 tokens per launch.
+MEASURED_TRAFFIC_BYTES = {("C2", "FULL_INT8", 2048): 27.34e6}
+
 INT8_PEAK_TOPS = 5000.0        # MI355X dense int8 MFMA, published: 5.0 POP/s
 FP16_PEAK_TFLOPS = 2500.0      # dense fp16
 HBM_PEAK_GBS = 8000.0
@@ -37,6 +41,9 @@ def main() -> int:
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--groups", type=int, default=0, help="batch groups run concurrently (0 = library default)")
+    ap.add_argument("--no-graph", action="store_true", help="plain launches instead of HIP graph replay")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one 256 MiB device copy (reference point for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--only-mode", default=None, help="time a single precision mode (FULL_INT8, FP16, ...)")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -70,6 +77,13 @@ def main() -> int:
                       max_seq=max(w0.seq, cal.shape[1]))
     scales = enc16.calibrate(cal)
 
+    if a.copy_probe:
+        src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     mode_list = [("FULL_INT8", P.FULL_INT8), ("FFN_INT8", P.FFN_INT8), ("MHA_INT8", P.MHA_INT8), ("FP16", P.FP16)]
     if a.workload != "C2":
         mode_list = [("CONFIG", None)]
@@ -83,6 +97,8 @@ def main() -> int:
         enc = enc16 if (mode == P.FP16) else P.Encoder(*cfg, modes, wts, scales, max_batch=w0.batch, max_seq=w0.seq)
         out = torch.empty_like(hid)
         enc.set_groups(a.groups)
+        if a.no_graph:
+            enc.set_graph(False)
         for _ in range(a.warmup):
             enc.forward(hid, mask, out)
         headline = (name in ("FULL_INT8", "CONFIG"))
@@ -114,7 +130,9 @@ def main() -> int:
             roof = {"kernel": "gemm_nt_kernel<I8,EpiGeluQuant> (FFN1 GEMM + bias + GELU + quantise)" if ffn_int8
                     else "gemm_nt_kernel<F16,EpiF16> (FFN1)",
                     "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TOP/s" if ffn_int8 else "TFLOP/s",
-                    "frac": achieved / peak, "traffic": None, "launches_timed": launches, "launches_per_step": per_forward,
+                    "frac": achieved / peak,
+                    "traffic": MEASURED_TRAFFIC_BYTES.get((a.workload, name, int(round(T / (per_forward / w0.layers))))),
+                    "algorithmic_bytes": (T * w0.hidden + T * w0.ffn) / (per_forward / w0.layers) + w0.ffn * w0.hidden, "launches_timed": launches, "launches_per_step": per_forward,
                     "mean_launch_us": kms * 1e3, "ops_per_launch": ops}
         if enc is not enc16:
             enc.close()
