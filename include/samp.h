@@ -136,7 +136,9 @@ SAMP_API int samp_encoder_calibrate(samp_encoder_t *enc, const void *hidden, con
 SAMP_API int samp_encoder_destroy(samp_encoder_t *enc);
 
 /* Kernel timing for benchmarks.  which = one of SAMP_PROF_*; the chosen kernel's launches inside
- * subsequent forwards get start/stop events attached to the dispatch itself.  SAMP_PROF_OFF stops.
+ * subsequent forwards get start/stop events attached to the dispatch itself; while timing is on,
+ * forwards use plain launches and run their sequence groups one after another on the caller's
+ * stream, so every timed launch has the device to itself.  SAMP_PROF_OFF stops.
  * samp_encoder_profile_read synchronises the events recorded so far, returns their mean duration
  * in milliseconds and their number, and clears them.                                             */
 enum { SAMP_PROF_OFF = 0, SAMP_PROF_QKV = 1, SAMP_PROF_ATTN = 2, SAMP_PROF_ATTN_OUT = 3, SAMP_PROF_LN1 = 4,

@@ -417,16 +417,19 @@ static int forward_eager(samp_encoder_t *enc, const void *hidden, const int32_t 
     const int Bg = (B + G - 1) / G;
     const size_t piece = carve(enc->cfg, Bg, S, nullptr).bytes;
     const size_t seq_elems = (size_t)S * enc->cfg.hidden;
-    HIP_TRY(hipEventRecord(enc->fork, st));
+    // while a kernel is being timed the groups run one after another on the caller's stream, so that
+    // each timed launch has the device to itself (same launch shapes, no overlap in the figures)
+    const bool serial = enc->prof_which != SAMP_PROF_OFF;
+    if (!serial) HIP_TRY(hipEventRecord(enc->fork, st));
     for (int g = 0; g < G; g++) {
         const int b0 = g * Bg, nb = std::min(Bg, B - b0);
         if (nb <= 0) break;
-        hipStream_t gs = g == 0 ? st : enc->side[g - 1];
-        if (g > 0) HIP_TRY(hipStreamWaitEvent(gs, enc->fork, 0));
+        hipStream_t gs = (g == 0 || serial) ? st : enc->side[g - 1];
+        if (g > 0 && !serial) HIP_TRY(hipStreamWaitEvent(gs, enc->fork, 0));
         const int rc = run(enc, (const __half *)hidden + b0 * seq_elems, mask ? mask + (size_t)b0 * S : nullptr, nb, S,
                            (__half *)out + b0 * seq_elems, (char *)workspace + g * piece, gs, false);
         if (rc != SAMP_OK) return rc;
-        if (g > 0) {
+        if (g > 0 && !serial) {
             HIP_TRY(hipEventRecord(enc->join[g - 1], gs));
             HIP_TRY(hipStreamWaitEvent(st, enc->join[g - 1], 0));
         }

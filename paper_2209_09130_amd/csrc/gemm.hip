@@ -82,18 +82,19 @@ struct EpiRequant {                               // code = rne(fmaf(acc, m[n], 
             const int n = n_loc + 8 * q + 4 * g;
             const v4f mm = *reinterpret_cast<const v4f *>(tab + n);
             const v4f bb = *reinterpret_cast<const v4f *>(tab + bn + n);
-            pk[q] = pack4(qcode(__builtin_fmaf((float)acc[4 * q + 0], mm.x, bb.x)),
-                          qcode(__builtin_fmaf((float)acc[4 * q + 1], mm.y, bb.y)),
-                          qcode(__builtin_fmaf((float)acc[4 * q + 2], mm.z, bb.z)),
-                          qcode(__builtin_fmaf((float)acc[4 * q + 3], mm.w, bb.w)));
+            pk[q] = pack_codes(code_bits(__builtin_fmaf((float)acc[4 * q + 0], mm.x, bb.x)),
+                               code_bits(__builtin_fmaf((float)acc[4 * q + 1], mm.y, bb.y)),
+                               code_bits(__builtin_fmaf((float)acc[4 * q + 2], mm.z, bb.z)),
+                               code_bits(__builtin_fmaf((float)acc[4 * q + 3], mm.w, bb.w)));
         }
     }
 };
 
 // y = fmaf(acc, m[n], bias[n]); code = rne(GELU(y) / s_out), decided exactly: the fast binary32
-// GELU is used wherever it provably rounds like the binary64 definition; the few elements that sit
-// within the fast path's error bound of a rounding tie are collected in a per-lane bit mask and
-// redone in binary64 by one compact loop (one copy of the slow code per tile, rarely entered).
+// GELU is used wherever it provably rounds like the binary64 definition.  The tie tests leave one
+// wave-wide lane mask per accumulator in scalar registers and cost no vector work; only when some
+// mask is non-zero (a few percent of the tiles) are they turned into a per-lane bit mask, and the
+// flagged elements redone in binary64 by one compact loop (one copy of the slow code per tile).
 struct EpiGeluQuant {
     const float *m, *bias; float inv_s;
     static constexpr int OUT_BYTES = 1;
@@ -104,23 +105,29 @@ struct EpiGeluQuant {
     { copy_table(tab, m, n0, bn, tid, nthreads); copy_table(tab + bn, bias, n0, bn, tid, nthreads); }
     __device__ __forceinline__ void tile(const v16i &acc, const float *tab, int bn, int n_loc, int n_glob, int g, int (&pk)[4]) const
     {
-        unsigned slow = 0;
+        unsigned long long tie[16], any = 0;
 #pragma unroll
         for (int q = 0; q < 4; q++) {
             const int n = n_loc + 8 * q + 4 * g;
             const v4f mm = *reinterpret_cast<const v4f *>(tab + n);
             const v4f bb = *reinterpret_cast<const v4f *>(tab + bn + n);
-            int c[4];
+            float f[4];
 #pragma unroll
             for (int t = 0; t < 4; t++) {
                 const float y = __builtin_fmaf((float)acc[4 * q + t], mm[t], bb[t]);
                 bool near_tie;
-                c[t] = gelu_quant_code_fast(y, inv_s, near_tie);
-                slow |= (unsigned)near_tie << (4 * q + t);
+                f[t] = gelu_code_bits_fast(y, inv_s, near_tie);
+                tie[4 * q + t] = __builtin_amdgcn_ballot_w64(near_tie);
+                any |= tie[4 * q + t];
             }
-            pk[q] = pack4(c[0], c[1], c[2], c[3]);
+            pk[q] = pack_codes(f[0], f[1], f[2], f[3]);
         }
-        while (__builtin_amdgcn_ballot_w64(slow != 0) != 0) {          // wave-uniform loop, rarely entered
+        if (any == 0) return;                                          // wave-uniform
+        const int lane = threadIdx.x & 63;
+        unsigned slow = 0;
+#pragma unroll
+        for (int k = 0; k < 16; k++) slow |= (unsigned)((tie[k] >> lane) & 1) << k;
+        while (__builtin_amdgcn_ballot_w64(slow != 0) != 0) {          // wave-uniform loop
             const bool active = slow != 0;
             const int e = active ? __builtin_ctz(slow) : 0;
             int a = acc[0];

@@ -37,29 +37,50 @@ __device__ __forceinline__ int pack4(int a, int b, int c, int d)
     return (a & 0xff) | ((b & 0xff) << 8) | ((c & 0xff) << 16) | ((unsigned)(d & 0xff) << 24);
 }
 
-// ---- GELU -------------------------------------------------------------------------------------
-// 1 + erf(u) for binary32 u through the five-term rational/exponential approximation of
-// Abramowitz & Stegun 7.1.26 (|error| <= 1.5e-7 in exact arithmetic), arranged as erfc on the
-// negative side so that no cancellation occurs there.
-__device__ __forceinline__ float one_plus_erf_fast(float u)
+// The quantiser without integer conversions.  Clamping before rounding gives the same code as
+// clamping after it (the bounds are integers), and adding 1.5 * 2^23 to a value of magnitude below
+// 2^22 rounds it to an integer, ties to even, in the adder itself; the sum's bit pattern then holds
+// the code in two's complement in its low byte.  code_bits() returns that pattern, pack_codes()
+// gathers the low bytes of four of them into one dword with byte permutes.
+#define SAMP_RNE_MAGIC 12582912.0f
+__device__ __forceinline__ float code_bits(float v)
 {
-    const float au = __builtin_fabsf(u);
-    const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(0.3275911f, au, 1.0f));
-    float p = 1.061405429f;
-    p = __builtin_fmaf(p, t, -1.453152027f);
-    p = __builtin_fmaf(p, t, 1.421413741f);
-    p = __builtin_fmaf(p, t, -0.284496736f);
-    p = __builtin_fmaf(p, t, 0.254829592f);
-    p = p * t;
-    const float ex = __builtin_amdgcn_exp2f(-au * au * 1.44269504088896341f);
-    const float tail = p * ex;                            // erfc(|u|)
-    return u < 0.0f ? tail : 2.0f - tail;
+    return __builtin_amdgcn_fmed3f(v, -127.0f, 127.0f) + SAMP_RNE_MAGIC;
+}
+__device__ __forceinline__ int pack_codes(float f0, float f1, float f2, float f3)
+{
+    const unsigned lo = __builtin_amdgcn_perm(__float_as_uint(f1), __float_as_uint(f0), 0x0c0c0400u);
+    const unsigned hi = __builtin_amdgcn_perm(__float_as_uint(f3), __float_as_uint(f2), 0x0c0c0400u);
+    return (int)__builtin_amdgcn_perm(hi, lo, 0x05040100u);
+}
+__device__ __forceinline__ int code_of_bits(float f) { return (int)(int8_t)(__float_as_uint(f) & 0xffu); }
+
+// ---- GELU -------------------------------------------------------------------------------------
+// erfc(|u|) / 2 at u = y / sqrt(2) through the five-term rational/exponential approximation of
+// Abramowitz & Stegun 7.1.26 (|error| <= 1.5e-7 on erfc in exact arithmetic).  The argument is
+// pre-scaled by sqrt(log2 e) so that the exponential is a bare exp2 of -(v*v), and the halving is
+// folded into the polynomial's coefficients.
+__device__ __forceinline__ float half_erfc_fast(float y)
+{
+    const float v = y * 0.84932180028801904f;              // y / sqrt(2) * sqrt(log2 e)
+    const float ex = __builtin_amdgcn_exp2f(-(v * v));
+    const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(0.27273748087922248f, __builtin_fabsf(v), 1.0f));
+    float p = 0.5307027145f;
+    p = __builtin_fmaf(p, t, -0.7265760135f);
+    p = __builtin_fmaf(p, t, 0.7107068705f);
+    p = __builtin_fmaf(p, t, -0.142248368f);
+    p = __builtin_fmaf(p, t, 0.127414796f);
+    return (p * t) * ex;
 }
 
-__device__ __forceinline__ float gelu_fast(float y)
+// k * GELU(y) from yk = k * y (k > 0), as relu(yk) - |yk| * erfc(|u|)/2: no cancellation on either
+// side of zero, and the scale rides along for free.
+__device__ __forceinline__ float gelu_scaled_fast(float y, float yk)
 {
-    return 0.5f * y * one_plus_erf_fast(y * 0.70710678118654752440f);
+    return __builtin_fmaf(-__builtin_fabsf(yk), half_erfc_fast(y), __builtin_fmaxf(yk, 0.0f));
 }
+
+__device__ __forceinline__ float gelu_fast(float y) { return gelu_scaled_fast(y, y); }
 
 // GELU evaluated in binary64 and rounded once: the value the quantiser's decision is defined on.
 __device__ __forceinline__ float gelu_exact(float y)
@@ -69,28 +90,30 @@ __device__ __forceinline__ float gelu_exact(float y)
     return (float)g;
 }
 
-// Bound on |gelu_fast(y) - GELU(y)|, validated exhaustively by the GPU tests.
+// Bound on |gelu_fast(y) - GELU(y)| per unit of |y|, validated by a dense sweep in the GPU tests; the
+// tie test below adds 6e-7 per unit for the binary32 roundings on either side of the comparison.
 #define SAMP_GELU_FAST_ABS_ERR_PER_UNIT 8.0e-7f
+#define SAMP_GELU_TIE_MARGIN_PER_UNIT (SAMP_GELU_FAST_ABS_ERR_PER_UNIT + 6.0e-7f)
 
-// code = rne(GELU(y) * inv_s) from the fast GELU, plus a flag telling whether the value lies within
-// the fast path's error bound of a rounding tie (then the binary64 definition has to decide).
-__device__ __forceinline__ int gelu_quant_code_fast(float y, float inv_s, bool &near_tie)
+// code_bits of rne(GELU(y) * inv_s) from the fast GELU, plus a flag telling whether the scaled value
+// lies within the fast path's error bound of a rounding tie (then the binary64 definition decides).
+// |GELU(y)| <= |y|, so |y| * inv_s bounds both error terms.
+__device__ __forceinline__ float gelu_code_bits_fast(float y, float inv_s, bool &near_tie)
 {
-    const float c = gelu_fast(y) * inv_s;
-    const float r = __builtin_rintf(c);
-    const float dist = __builtin_fabsf(__builtin_fabsf(c - r) - 0.5f);   // distance to the nearest tie
-    const float margin = __builtin_fabsf(y) * inv_s * SAMP_GELU_FAST_ABS_ERR_PER_UNIT
-                       + __builtin_fabsf(c) * 6.0e-7f + 1.0e-30f;
-    near_tie = dist <= margin;
-    return (int)__builtin_fminf(__builtin_fmaxf(r, -127.0f), 127.0f);
+    const float yk = y * inv_s;
+    const float c = __builtin_amdgcn_fmed3f(gelu_scaled_fast(y, yk), -127.0f, 127.0f);
+    const float f = c + SAMP_RNE_MAGIC;
+    const float d = c - (f - SAMP_RNE_MAGIC);
+    near_tie = __builtin_fabsf(__builtin_fabsf(d) - 0.5f) <= __builtin_fabsf(yk) * SAMP_GELU_TIE_MARGIN_PER_UNIT;
+    return f;
 }
 
 // The same decision for one value on its own.
 __device__ __forceinline__ int gelu_quant_code(float y, float inv_s)
 {
     bool near_tie;
-    const int c = gelu_quant_code_fast(y, inv_s, near_tie);
-    return near_tie ? qcode(gelu_exact(y) * inv_s) : c;
+    const float f = gelu_code_bits_fast(y, inv_s, near_tie);
+    return near_tie ? qcode(gelu_exact(y) * inv_s) : code_of_bits(f);
 }
 
 // ---- wave reductions (64 lanes) ----------------------------------------------------------------
