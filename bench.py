@@ -11,6 +11,9 @@ Extra objects on the JSON line:
                  (2 * tokens * ffn * hidden) over its mean launch duration, measured with HIP events
                  attached to the dispatches over a repeat of the timed steps, against the int8 MFMA dense peak.
   cpu_baseline - the CPU oracle (as it stands, OpenMP over sequences) on the same batch.
+  kernels      - every kernel class of the headline mode timed the same way (one class per pass, launches
+                 isolated): mean launch duration, and its algorithmic ops or bytes over that duration against
+                 the MFMA or HBM peak.
 """
 from __future__ import annotations
 
@@ -31,6 +34,30 @@ MEASURED_TRAFFIC_BYTES = {("C2", "FULL_INT8", 2048): 27.34e6}
 INT8_PEAK_TOPS = 5000.0        # MI355X dense int8 MFMA, published: 5.0 POP/s
 FP16_PEAK_TFLOPS = 2500.0      # dense fp16
 HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_work(w, modes, lens):
+    """Per kernel class, summed over one forward: (ops, bytes, bound, dtype-is-int8) that the method itself
+    needs - operands read once, results written once, weights once per layer."""
+    T = int(lens.sum())
+    H, F = w.hidden, w.ffn
+    att = float((lens.astype("float64") ** 2).sum()) * 4 * H
+    work = {k: [0.0, 0.0] for k in ("qkv", "attention", "attn_out", "ln1", "ffn1", "ffn2", "ln2")}
+    for i, m in enumerate(modes):
+        em = 1 if m & 1 else 2
+        ef = 1 if m & 2 else 2
+        en = 2 if i + 1 == len(modes) else (1 if modes[i + 1] & 1 else 2)
+        for k, ops, byts in (("qkv", 2.0 * T * 3 * H * H, (T * 4 * H + 3 * H * H) * em),
+                             ("attention", att, T * 4 * H * em),
+                             ("attn_out", 2.0 * T * H * H, (T * 2 * H + H * H) * em),
+                             ("ln1", 10.0 * T * H, T * H * (2 * em + ef)),
+                             ("ffn1", 2.0 * T * H * F, (T * (H + F) + H * F) * ef),
+                             ("ffn2", 2.0 * T * H * F, (T * (H + F) + H * F) * ef),
+                             ("ln2", 10.0 * T * H, T * H * (2 * ef + en))):
+            work[k][0] += ops
+            work[k][1] += byts
+    work["entry"] = [0.0, T * H * (2 + (1 if modes[0] & 1 else 2))]
+    return work
 
 
 def main() -> int:
@@ -134,6 +161,31 @@ def main() -> int:
                     "traffic": MEASURED_TRAFFIC_BYTES.get((a.workload, name, int(round(T / (per_forward / w0.layers))))),
                     "algorithmic_bytes": (T * w0.hidden + T * w0.ffn) / (per_forward / w0.layers) + w0.ffn * w0.hidden, "launches_timed": launches, "launches_per_step": per_forward,
                     "mean_launch_us": kms * 1e3, "ops_per_launch": ops}
+            # every kernel class, one pass each
+            work = algorithmic_work(w0, modes, lens)
+            all_i8 = all(m == P.FULL_INT8 for m in modes)
+            kernels = {}
+            for kname, which in (("entry", P.PROF_ENTRY), ("qkv", P.PROF_QKV), ("attention", P.PROF_ATTN),
+                                 ("attn_out", P.PROF_ATTN_OUT), ("ln1", P.PROF_LN1), ("ffn1", P.PROF_FFN1),
+                                 ("ffn2", P.PROF_FFN2), ("ln2", P.PROF_LN2)):
+                enc.profile(which)
+                n_pass = min(a.steps, 20)
+                for _ in range(n_pass):
+                    enc.forward(hid, mask, out)
+                torch.cuda.synchronize()
+                kms, launches = enc.profile_read()
+                enc.profile(P.PROF_OFF)
+                if launches == 0:
+                    continue
+                tot_s = kms * 1e-3 * launches / n_pass          # summed duration of the class in one forward
+                ops_f, bytes_f = work[kname]
+                ent = {"mean_launch_us": round(kms * 1e3, 2), "launches_per_step": launches / n_pass,
+                       "GB/s": round(bytes_f / tot_s / 1e9, 1), "frac_hbm": round(bytes_f / tot_s / 1e9 / HBM_PEAK_GBS, 4)}
+                if kname in ("qkv", "attn_out", "ffn1", "ffn2") and (all_i8 or all(m == P.FP16 for m in modes)):
+                    peak = INT8_PEAK_TOPS if all_i8 else FP16_PEAK_TFLOPS
+                    ent["TOP/s" if all_i8 else "TFLOP/s"] = round(ops_f / tot_s / 1e12, 1)
+                    ent["frac_mfma"] = round(ops_f / tot_s / 1e12 / peak, 4)
+                kernels[kname] = ent
         if enc is not enc16:
             enc.close()
     enc16.close()
@@ -150,6 +202,7 @@ def main() -> int:
     }
     if roof:
         line["roofline"] = roof
+        line["kernels"] = kernels
 
     if not a.no_cpu_baseline:
         import oracle

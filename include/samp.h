@@ -149,6 +149,13 @@ SAMP_API int samp_encoder_profile_read(samp_encoder_t *enc, double *mean_ms, int
 /* Thread-local description of the last failure on this thread ("" if none).                       */
 SAMP_API const char *samp_last_error(void);
 
+/* Tuning aid: force the tile configuration of every GEMM launched afterwards by this process
+ * (0: 128x128 tile with 64-byte K stages, 1: 128x128 with 128-byte stages, 2: 64 tokens x 128
+ * channels), or -1 (default) to choose by problem shape.  Configurations 1 and 2 need the operand
+ * rows to be multiples of 128 bytes and fall back to 0 otherwise.  Results do not depend on it
+ * for INT8; FP16 sums are formed in the same order in all three.                                   */
+SAMP_API int samp_set_gemm_config(int32_t config);
+
 /* ---- single steps of the path (what the encoder is made of; used by the parity tests) --------- */
 
 /* INT8 GEMM with int32 accumulation (Section 3.2): C[M,N] = A[M,K] . W[N,K]^T, exact.

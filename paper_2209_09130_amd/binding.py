@@ -249,6 +249,11 @@ def quantize_weight(W: torch.Tensor):
     return Wq, s_w
 
 
+def set_gemm_config(config: int) -> None:
+    """Force a GEMM tile configuration (0, 1, 2) or -1 to choose by shape again."""
+    _check(lib().samp_set_gemm_config(int(config)))
+
+
 def pack_rows(hidden: torch.Tensor, mask: torch.Tensor, s_x: float = 0.0):
     """Returns (packed [B*S,H] (first T rows valid), cu_seqlens [B+1], row_map [B*S])."""
     B, S, H = hidden.shape

@@ -651,6 +651,13 @@ int samp_quantize_weight(const uint16_t *W, int32_t N, int32_t K, int8_t *Wq, fl
     return SAMP_OK;
 }
 
+int samp_set_gemm_config(int32_t config)
+{
+    if (config < -1 || config > 2) return fail(SAMP_ERR_ARG, "config must be -1, 0, 1 or 2");
+    gemm_config_override = config;
+    return SAMP_OK;
+}
+
 int samp_pack_rows(const uint16_t *hidden, const int32_t *mask, int32_t B, int32_t S, int32_t H, float s_x, void *packed,
                    int32_t *cu, int32_t *row_map, void *stream)
 {

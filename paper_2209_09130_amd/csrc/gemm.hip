@@ -166,11 +166,6 @@ struct EpiF16 {                                   // fp16(act(acc + bias[n]))
     }
 };
 
-__device__ __forceinline__ int to_bits(int v) { return v; }
-__device__ __forceinline__ int to_bits(float v) { return __float_as_int(v); }
-__device__ __forceinline__ int plus_bits(int a, int bits) { return a + bits; }
-__device__ __forceinline__ float plus_bits(float a, int bits) { return a + __int_as_float(bits); }
-
 // wait until at most N vector-memory operations of this wave are outstanding and all of its LDS
 // reads have returned, then barrier.  The "memory" clobber keeps the compiler from moving LDS
 // accesses across it.
@@ -181,17 +176,12 @@ __device__ __forceinline__ void wait_vm_and_barrier()
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-// KS = 1: 4 waves, each multiplies both 32-byte halves of a stage.
-// KS = 2: 8 waves; waves 0-3 take the first half of every stage, waves 4-7 the second half, and the
-//         two partial accumulators of a wave tile are added through LDS before the epilogue (int32
-//         adds are exact, so the split cannot change an INT8 result).  Twice the waves per SIMD for
-//         the shapes that have too few tiles to fill the chip otherwise.
-template <class T, class Epi, int TM, int TN, int BKB, int NSTAGE, int KS, int WAVES_PER_EU>
-__global__ __launch_bounds__(256 * KS) __attribute__((amdgpu_waves_per_eu(WAVES_PER_EU, 8)))
+template <class T, class Epi, int TM, int TN, int BKB, int NSTAGE, int WAVES_PER_EU>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WAVES_PER_EU, 8)))
 void gemm_nt_kernel(const char *__restrict__ A, const char *__restrict__ W, char *__restrict__ out, Epi epi, int host_rows,
                     const int *__restrict__ dev_rows, int N, int Kbytes, int tiles_n, int tiles_total)
 {
-    constexpr int NT = 256 * KS, NWAVES = 4 * KS;
+    constexpr int NT = 256, NWAVES = 4;
     constexpr int BM = 64 * TM, BN = 64 * TN;
     constexpr int A_BYTES = BM * BKB, W_BYTES = BN * BKB, STAGE_BYTES = A_BYTES + W_BYTES;
     constexpr int CH = BKB / 16, RPI = 64 / CH;                  // chunks per row; rows per direct-load instruction
@@ -215,8 +205,7 @@ void gemm_nt_kernel(const char *__restrict__ A, const char *__restrict__ W, char
     if (m0 >= M) return;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int w4 = wave & 3, kgroup = wave >> 2;
-    const int wm = (w4 >> 1) * 32 * TM, wn = (w4 & 1) * 32 * TN;       // wave tile origin inside the block tile
+    const int wm = (wave >> 1) * 32 * TM, wn = (wave & 1) * 32 * TN;       // wave tile origin inside the block tile
     const int r = lane & 31, g = lane >> 5;
 
     // direct loads: instruction j of this wave fills RPI consecutive rows (1 KiB) of an operand tile;
@@ -266,8 +255,7 @@ void gemm_nt_kernel(const char *__restrict__ A, const char *__restrict__ W, char
         if (kt + NSTAGE - 1 < KT) issue(kt + NSTAGE - 1);        // refills the buffer consumed at kt-1
         const char *cur = lds + (kt % NSTAGE) * STAGE_BYTES;
 #pragma unroll
-        for (int kk = 0; kk < CH / 2 / KS; kk++) {
-            const int ks = KS == 2 ? kk * 2 + kgroup : kk;
+        for (int ks = 0; ks < CH / 2; ks++) {
             v4i fa[TM], fw[TN];
 #pragma unroll
             for (int j = 0; j < TM; j++) {
@@ -287,58 +275,17 @@ void gemm_nt_kernel(const char *__restrict__ A, const char *__restrict__ W, char
     }
     wait_vm_and_barrier<0>();                                     // the ring is idle from here on
 
-    // KS = 2: the two K halves of a wave tile are summed through LDS, one MFMA tile per round;
-    // afterwards group 0 owns the channel tiles i < TN/2 of the wave tile, group 1 the others.
-    constexpr int TN_OWN = TN / KS;
-    if constexpr (KS == 2) {
-        static_assert(TN % 2 == 0, "channel tiles must split over the two wave groups");
-        static_assert(NWAVES * 4096 <= RING_BYTES, "exchange buffer does not fit in the ring");
-        v4i *mine = reinterpret_cast<v4i *>(lds + wave * 4096) + lane;
-        const v4i *theirs = reinterpret_cast<const v4i *>(lds + (wave ^ 4) * 4096) + lane;
-#pragma unroll
-        for (int io = 0; io < TN_OWN; io++)
-#pragma unroll
-            for (int j = 0; j < TM; j++) {
-                const int i_send = kgroup == 0 ? io + TN_OWN : io, i_keep = kgroup == 0 ? io : io + TN_OWN;
-#pragma unroll
-                for (int q = 0; q < 4; q++) {
-                    v4i v;
-#pragma unroll
-                    for (int t = 0; t < 4; t++) v[t] = to_bits(kgroup == 0 ? acc[TN_OWN + io][j][4 * q + t] : acc[io][j][4 * q + t]);
-                    mine[q * 64] = v;
-                }
-                __syncthreads();
-#pragma unroll
-                for (int q = 0; q < 4; q++) {
-                    const v4i v = theirs[q * 64];
-#pragma unroll
-                    for (int t = 0; t < 4; t++) {
-                        const int bits = t == 0 ? v.x : t == 1 ? v.y : t == 2 ? v.z : v.w;
-                        if (kgroup == 0) acc[io][j][4 * q + t] = plus_bits(acc[io][j][4 * q + t], bits);
-                        else acc[TN_OWN + io][j][4 * q + t] = plus_bits(acc[TN_OWN + io][j][4 * q + t], bits);
-                    }
-                }
-                __syncthreads();
-                (void)i_send; (void)i_keep;
-            }
-    }
-
     if constexpr (!Epi::STAGED) {
 #pragma unroll
-        for (int io = 0; io < TN_OWN; io++)
+        for (int io = 0; io < TN; io++)
 #pragma unroll
             for (int j = 0; j < TM; j++) {
                 const int row = m0 + wm + j * 32 + r;
                 if (row < M) {
 #pragma unroll
                     for (int q = 0; q < 4; q++) {
-                        if (KS == 2 && kgroup == 1) {
-                            const int n = n0 + wn + (io + TN_OWN) * 32 + 8 * q + 4 * g;
-                            epi.direct(row, n, acc[io + TN_OWN][j][4 * q], acc[io + TN_OWN][j][4 * q + 1], acc[io + TN_OWN][j][4 * q + 2], acc[io + TN_OWN][j][4 * q + 3]);
-                        } else {
-                            const int n = n0 + wn + io * 32 + 8 * q + 4 * g;
-                            epi.direct(row, n, acc[io][j][4 * q], acc[io][j][4 * q + 1], acc[io][j][4 * q + 2], acc[io][j][4 * q + 3]);
-                        }
+                        const int n = n0 + wn + io * 32 + 8 * q + 4 * g;
+                        epi.direct(row, n, acc[io][j][4 * q], acc[io][j][4 * q + 1], acc[io][j][4 * q + 2], acc[io][j][4 * q + 3]);
                     }
                 }
             }
@@ -348,24 +295,16 @@ void gemm_nt_kernel(const char *__restrict__ A, const char *__restrict__ W, char
         constexpr int STRIDE = BN * OB + 16;
         static_assert(BM * STRIDE <= RING_BYTES, "staging tile does not fit in the ring");
 #pragma unroll
-        for (int io = 0; io < TN_OWN; io++)
+        for (int io = 0; io < TN; io++)
 #pragma unroll
             for (int j = 0; j < TM; j++) {
                 typename Epi::pack_t pk[4];
                 const int lrow = wm + j * 32 + r;
-                if (KS == 2 && kgroup == 1) {
-                    const int nl = wn + (io + TN_OWN) * 32;
-                    epi.tile(acc[io + TN_OWN][j], tab, BN, nl, n0 + nl, g, pk);
+                const int nl = wn + io * 32;
+                epi.tile(acc[io][j], tab, BN, nl, n0 + nl, g, pk);
 #pragma unroll
-                    for (int q = 0; q < 4; q++)
-                        *reinterpret_cast<typename Epi::pack_t *>(lds + lrow * STRIDE + (nl + 8 * q + 4 * g) * OB) = pk[q];
-                } else {
-                    const int nl = wn + io * 32;
-                    epi.tile(acc[io][j], tab, BN, nl, n0 + nl, g, pk);
-#pragma unroll
-                    for (int q = 0; q < 4; q++)
-                        *reinterpret_cast<typename Epi::pack_t *>(lds + lrow * STRIDE + (nl + 8 * q + 4 * g) * OB) = pk[q];
-                }
+                for (int q = 0; q < 4; q++)
+                    *reinterpret_cast<typename Epi::pack_t *>(lds + lrow * STRIDE + (nl + 8 * q + 4 * g) * OB) = pk[q];
             }
         __syncthreads();
         constexpr int CHUNKS = BN * OB / 16;                      // 16-byte chunks per output row
@@ -382,7 +321,7 @@ void gemm_nt_kernel(const char *__restrict__ A, const char *__restrict__ W, char
     }
 }
 
-template <class T, class Epi, int TM, int TN, int BKB, int NSTAGE, int KS, int WPE>
+template <class T, class Epi, int TM, int TN, int BKB, int NSTAGE, int WPE>
 hipError_t launch_cfg(const void *A, const void *W, void *out, const Epi &epi, Rows rows, int N, int K, hipStream_t st,
                       const Timing *tm)
 {
@@ -390,7 +329,7 @@ hipError_t launch_cfg(const void *A, const void *W, void *out, const Epi &epi, R
     constexpr size_t LDS = (size_t)NSTAGE * (BM + BN) * BKB + (size_t)Epi::NTAB * BN * sizeof(float);
     if (N % BN) return hipErrorInvalidValue;
     if ((K * T::ELEM) % BKB) return hipErrorInvalidValue;
-    auto kern = gemm_nt_kernel<T, Epi, TM, TN, BKB, NSTAGE, KS, WPE>;
+    auto kern = gemm_nt_kernel<T, Epi, TM, TN, BKB, NSTAGE, WPE>;
     static bool attr_set = false;                                 // > 64 KiB of dynamic LDS must be enabled once
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
@@ -398,17 +337,18 @@ hipError_t launch_cfg(const void *A, const void *W, void *out, const Epi &epi, R
         attr_set = true;
     }
     const int tiles_n = N / BN, tiles_m = (rows.host_rows + BM - 1) / BM, total = tiles_n * tiles_m;
-    launch_kernel(kern, dim3(total), dim3(256 * KS), LDS, st, tm,
+    launch_kernel(kern, dim3(total), dim3(256), LDS, st, tm,
                           (const char *)A, (const char *)W, (char *)out, epi, rows.host_rows, rows.dev_rows, N, K * T::ELEM,
                           tiles_n, total);
     return hipGetLastError();
 }
 
-// Tile configuration per problem shape (all 128 x 128 tiles; larger tiles did not pay on this chip:
-// the direct-load and LDS paths of a CU, not the MFMA rate, bound the main loop):
-//   0: 64-byte stages, 4-deep ring, 4 waves  (any K that is a multiple of 64 bytes)
-//   1: 128-byte stages (whole cache lines per row), 2-deep ring, 4 waves, 2 blocks per CU
-//   2: as 1 with 8 waves (K split inside the block): for shapes with at most one tile per CU
+// Tile configuration per problem shape.  What bounds the main loop on this chip is the rate at which
+// a CU pulls operand stages out of L2 (about 37 bytes per clock per CU, whichever way they are loaded),
+// so small problems want many small tiles (more CUs pulling), large ones the larger tile (less traffic):
+//   0: 128 x 128 tile, 64-byte stages, 4-deep ring  (any K that is a multiple of 64 bytes)
+//   1: 128 x 128 tile, 128-byte stages (whole cache lines per row), 2-deep ring, 2 blocks per CU
+//   2: 64 tokens x 128 channels, otherwise as 1: up to about two and a half 128 x 128 tiles per CU
 template <class T, class Epi>
 hipError_t launch(const void *A, const void *W, void *out, const Epi &epi, Rows rows, int N, int K, hipStream_t st,
                   const Timing *tm)
@@ -417,12 +357,12 @@ hipError_t launch(const void *A, const void *W, void *out, const Epi &epi, Rows 
     if ((K * T::ELEM) % 128) cfg = 0;
     else if (cfg < 0) {
         const long tiles = (long)(N / 128) * ((rows.host_rows + 127) / 128);
-        cfg = tiles <= 256 ? 2 : 1;
+        cfg = tiles <= 640 ? 2 : 1;
     }
     switch (cfg) {
-    case 1: return launch_cfg<T, Epi, 2, 2, 128, 2, 1, 2>(A, W, out, epi, rows, N, K, st, tm);
-    case 2: return launch_cfg<T, Epi, 2, 2, 128, 2, 2, 2>(A, W, out, epi, rows, N, K, st, tm);
-    default: return launch_cfg<T, Epi, 2, 2, 64, 4, 1, 2>(A, W, out, epi, rows, N, K, st, tm);
+    case 1: return launch_cfg<T, Epi, 2, 2, 128, 2, 2>(A, W, out, epi, rows, N, K, st, tm);
+    case 2: return launch_cfg<T, Epi, 1, 2, 128, 2, 2>(A, W, out, epi, rows, N, K, st, tm);
+    default: return launch_cfg<T, Epi, 2, 2, 64, 4, 2>(A, W, out, epi, rows, N, K, st, tm);
     }
 }
 

@@ -79,6 +79,37 @@ def test_int8_gemm_requant_epilogue_bit_exact(P, M, N, K, with_bias):
     assert np.abs(want).max() == 127 and (np.abs(want) < 127).mean() > 0.5      # clamp and interior both hit
 
 
+@pytest.mark.parametrize("config", [0, 1, 2])
+def test_every_gemm_tile_configuration_gives_the_same_results(P, config):
+    """The library picks a tile configuration by problem size; force each one in turn on a problem that
+    spans several tiles and a ragged last row tile, for all three INT8 epilogues and the FP16 GEMM."""
+    rng = np.random.default_rng(77)
+    M, N, K = 333, 384, 768
+    A = rng.integers(-127, 128, (M, K), dtype=np.int8)
+    W = rng.integers(-127, 128, (N, K), dtype=np.int8)
+    s_w, bias = _tables(rng, N)
+    m, b = oracle.fold_requant(0.037, s_w, bias, 0.021)
+    md = oracle.fold_dequant(0.05, s_w)
+    Ah = (rng.standard_normal((M, K)) * 0.5).astype(np.float16)
+    Wh = (rng.standard_normal((N, K)) * 0.05).astype(np.float16)
+    acc = oracle.gemm_i8_i32(A, W)
+    P.set_gemm_config(config)
+    try:
+        raw = host(P.gemm_i8_i32(dev(A), dev(W)))
+        req = host(P.gemm_i8_requant(dev(A), dev(W), dev(m), dev(b)))
+        gel = host(P.gemm_i8_gelu_quant(dev(A), dev(W), dev(md), dev(bias), 0.0147))
+        f16 = host(P.gemm_f16(dev(Ah), dev(Wh), dev(bias), False)).astype(np.float64)
+    finally:
+        P.set_gemm_config(-1)
+    assert np.array_equal(raw, acc)
+    assert np.array_equal(req, oracle.epilogue_requant(acc, m, b))
+    assert np.array_equal(gel, oracle.epilogue_gelu_quant(acc, md, bias, 0.0147))
+    want = oracle.gemm_f16(Ah, Wh, bias, False).astype(np.float64)
+    assert (np.abs(f16 - want) <= np.maximum(np.abs(want), 2.0 ** -14) * 2.0 ** -10 + 1e-6).all()
+    with pytest.raises(P.SampError):
+        P.set_gemm_config(3)
+
+
 def test_int8_gemm_gelu_quant_epilogue_bit_exact(P):
     rng = np.random.default_rng(21)
     M, N, K = 260, 384, 768
