@@ -29,7 +29,7 @@ if ROOT not in sys.path:
 
 # HBM bytes per launch of the dominant kernel, from profiles/c2_full_int8_hbm_traffic.txt (rocprofv3 FETCH_SIZE x 2.0 +
 # WRITE_SIZE x 1.0, factors from a 256 MiB copy): workload C2, full-INT8, FFN1 kernel, 2048 tokens per launch.
-MEASURED_TRAFFIC_BYTES = {("C2", "FULL_INT8", 2048): 27.34e6}
+MEASURED_TRAFFIC_BYTES = {("C2", "FULL_INT8", 2048): 27.15e6}
 
 INT8_PEAK_TOPS = 5000.0        # MI355X dense int8 MFMA, published: 5.0 POP/s
 FP16_PEAK_TFLOPS = 2500.0      # dense fp16
