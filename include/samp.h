@@ -149,6 +149,26 @@ SAMP_API int samp_encoder_profile_read(samp_encoder_t *enc, double *mean_ms, int
 /* Thread-local description of the last failure on this thread ("" if none).                       */
 SAMP_API const char *samp_last_error(void);
 
+/* ---- choosing the per-layer modes (host functions, no GPU work) -------------------------------- */
+
+/* Accuracy-Decay-Aware allocator (Section 3.2, Algorithm 1).  accuracy[i], latency[i], i = 0..n-1,
+ * describe the settings of one mode in order of increasing number of quantised layers; setting 0
+ * is all-FP16.  Latency is a time (Table 2's speedups enter as 1/speedup); both arrays are host
+ * memory, finite, n in [1, 64].  Walking the settings in order, the recommended one moves to i
+ * when dr = (A_i - A_rec) / (L_i - L_rec) is negative or smaller than every rate accepted before;
+ * where L_i == L_rec the sign of the accuracy change decides (gain: accept, loss: reject, none:
+ * skip).  *setting_out receives the index of the recommended setting.                            */
+SAMP_API int samp_allocate_decay_aware(const double *accuracy, const double *latency, int32_t n, int32_t *setting_out);
+
+/* Threshold rules (Appendix A) over the same arrays.  max_latency not NaN: the most accurate
+ * setting with latency <= max_latency.  Else min_accuracy not NaN: the fastest setting with
+ * accuracy >= min_accuracy.  Else up to five settings i >= 1 ranked by speedup over accuracy loss,
+ * (L_0 / L_i) / (A_0 - A_i), settings that lose nothing first (by speedup).  Ties keep the setting
+ * with the smaller index.  settings_out: host [capacity]; *count_out = number written (0 if no
+ * setting qualifies).                                                                             */
+SAMP_API int samp_recommend(const double *accuracy, const double *latency, int32_t n, double max_latency,
+                            double min_accuracy, int32_t *settings_out, int32_t capacity, int32_t *count_out);
+
 /* Tuning aid: force the tile configuration of every GEMM launched afterwards by this process
  * (0: 128x128 tile with 64-byte K stages, 1: 128x128 with 128-byte stages, 2: 64 tokens x 128
  * channels), or -1 (default) to choose by problem shape.  Configurations 1 and 2 need the operand

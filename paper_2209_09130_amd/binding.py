@@ -3,7 +3,7 @@ from __future__ import annotations
 
 import ctypes as C
 import os
-from typing import Dict, Optional, Sequence
+from typing import List, Dict, Optional, Sequence
 
 import numpy as np
 import torch
@@ -247,6 +247,32 @@ def quantize_weight(W: torch.Tensor):
     s_w = torch.empty(N, dtype=torch.float32, device=W.device)
     _check(lib().samp_quantize_weight(_dp(W), N, K, _dp(Wq), _dp(s_w), _stream()))
     return Wq, s_w
+
+
+def allocate_decay_aware(accuracy: Sequence[float], latency: Sequence[float]) -> int:
+    """samp_allocate_decay_aware: index of the setting Algorithm 1 recommends."""
+    n = len(accuracy)
+    assert n == len(latency)
+    a = (C.c_double * n)(*[float(v) for v in accuracy])
+    l = (C.c_double * n)(*[float(v) for v in latency])
+    out = C.c_int32(-1)
+    _check(lib().samp_allocate_decay_aware(a, l, n, C.byref(out)))
+    return int(out.value)
+
+
+def recommend(accuracy: Sequence[float], latency: Sequence[float], max_latency: Optional[float] = None,
+              min_accuracy: Optional[float] = None) -> List[int]:
+    """samp_recommend: the Appendix A rules; thresholds left None are unset."""
+    n = len(accuracy)
+    assert n == len(latency)
+    a = (C.c_double * n)(*[float(v) for v in accuracy])
+    l = (C.c_double * n)(*[float(v) for v in latency])
+    out = (C.c_int32 * 8)()
+    cnt = C.c_int32(0)
+    nan = float("nan")
+    _check(lib().samp_recommend(a, l, n, C.c_double(nan if max_latency is None else max_latency),
+                                C.c_double(nan if min_accuracy is None else min_accuracy), out, 8, C.byref(cnt)))
+    return [int(out[i]) for i in range(cnt.value)]
 
 
 def set_gemm_config(config: int) -> None:

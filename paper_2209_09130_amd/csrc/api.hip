@@ -651,6 +651,36 @@ int samp_quantize_weight(const uint16_t *W, int32_t N, int32_t K, int8_t *Wq, fl
     return SAMP_OK;
 }
 
+static int check_curves(const double *accuracy, const double *latency, int32_t n)
+{
+    if (!accuracy || !latency) return fail(SAMP_ERR_ARG, "accuracy or latency is NULL");
+    if (n < 1 || n > 64) return fail(SAMP_ERR_SHAPE, "n must be in [1, 64]");
+    for (int i = 0; i < n; i++) {
+        if (!std::isfinite(accuracy[i]) || !std::isfinite(latency[i])) return fail(SAMP_ERR_ARG, "setting %d: accuracy and latency must be finite", i);
+        if (!(latency[i] > 0.0)) return fail(SAMP_ERR_ARG, "setting %d: latency must be positive", i);
+    }
+    return SAMP_OK;
+}
+
+int samp_allocate_decay_aware(const double *accuracy, const double *latency, int32_t n, int32_t *setting_out)
+{
+    if (int rc = check_curves(accuracy, latency, n)) return rc;
+    if (!setting_out) return fail(SAMP_ERR_ARG, "setting_out is NULL");
+    *setting_out = allocate_decay_aware(accuracy, latency, n);
+    return SAMP_OK;
+}
+
+int samp_recommend(const double *accuracy, const double *latency, int32_t n, double max_latency, double min_accuracy,
+                   int32_t *settings_out, int32_t capacity, int32_t *count_out)
+{
+    if (int rc = check_curves(accuracy, latency, n)) return rc;
+    if (!settings_out || !count_out) return fail(SAMP_ERR_ARG, "settings_out or count_out is NULL");
+    if (capacity < 1) return fail(SAMP_ERR_ARG, "capacity must be >= 1");
+    if (std::isinf(max_latency) || std::isinf(min_accuracy)) return fail(SAMP_ERR_ARG, "thresholds must be finite or NaN (unset)");
+    *count_out = recommend_settings(accuracy, latency, n, max_latency, min_accuracy, settings_out, capacity);
+    return SAMP_OK;
+}
+
 int samp_set_gemm_config(int32_t config)
 {
     if (config < -1 || config > 2) return fail(SAMP_ERR_ARG, "config must be -1, 0, 1 or 2");
