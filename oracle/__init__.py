@@ -174,7 +174,9 @@ def epilogue_gelu_quant(acc: np.ndarray, m: np.ndarray, bias: np.ndarray, s_out:
     return out
 
 
-def attention_i8(qkv: np.ndarray, cu: np.ndarray, heads: int, s_q, s_k, s_v, s_p, s_ctx, dump_p: bool = False):
+def attention_i8(qkv: np.ndarray, cu: np.ndarray, heads: int, s_q, s_k, s_v, s_p, s_ctx, dump_p: bool = False,
+                 p_unsigned: bool = False):
+    """p_unsigned: softmax codes 0..255 with step s_p (= absmax/255) instead of the symmetric -127..127."""
     qkv = np.ascontiguousarray(qkv, np.int8)
     cu = np.ascontiguousarray(cu, np.int32)
     T, H3 = qkv.shape
@@ -183,9 +185,11 @@ def attention_i8(qkv: np.ndarray, cu: np.ndarray, heads: int, s_q, s_k, s_v, s_p
     pd = None
     if dump_p:
         n = int(cu[-1] - cu[-2])
-        pd = np.zeros((heads, n, n), np.int8)
+        pd = np.zeros((heads, n, n), np.uint8)
     lib().orc_attention_i8(_p(qkv), _p(cu), cu.size - 1, H, heads, C.c_float(s_q), C.c_float(s_k), C.c_float(s_v),
-                           C.c_float(s_p), C.c_float(s_ctx), _p(ctx), _p(pd))
+                           C.c_float(s_p), C.c_float(s_ctx), int(bool(p_unsigned)), _p(ctx), _p(pd))
+    if dump_p and not p_unsigned:
+        pd = pd.view(np.int8)
     return (ctx, pd) if dump_p else ctx
 
 

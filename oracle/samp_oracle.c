@@ -44,7 +44,8 @@
 
 #define ORC_API __attribute__((visibility("default")))
 
-enum { ORC_MHA_INT8 = 1, ORC_FFN_INT8 = 2 };
+enum { ORC_MHA_INT8 = 1, ORC_FFN_INT8 = 2,
+       ORC_P_UNSIGNED = 4 };   /* with ORC_MHA_INT8: softmax codes 0..255 instead of the symmetric range */
 
 /* ------------------------------------------------------------------------ */
 /* binary16 <-> binary32 (IEEE 754, round to nearest even)                   */
@@ -231,12 +232,26 @@ static float softmax_row(const float *sc, int n, float *e)
  * columns h*d .. h*d+d-1 of each third.  cu: sequence b owns rows cu[b]..cu[b+1).
  * Only the keys of the same sequence take part (padding is never stored).
  *   score = fl32(acc) * m_sc,        m_sc  = s_q * s_k / sqrt(d)
- *   Pq    = rne(P * (1/s_p))
+ *   Pq    = rne(P * (1/s_p))   clamped to [-127, 127]  (p_unsigned == 0: the
+ *           symmetric code of Appendix B, whose negative half a softmax output
+ *           never uses) or to [0, 255] (p_unsigned != 0: the variant Section 4.2
+ *           points to, spending all 256 codes on [0, 1]; s_p is then absmax/255)
  *   ctx   = rne(fl32(sum_j Pq V) * m_ctx),  m_ctx = s_p * s_v / s_ctx
- * p_dump (optional): int8 [heads][n][n] codes of the LAST sequence.           */
+ * p_dump (optional): [heads][n][n] codes of the LAST sequence, one byte each
+ * (0..127 or 0..255; a softmax code is never negative).                       */
+static inline int32_t pcode(float v, int p_unsigned)
+{
+    float r = nearbyintf(v);
+    if (!(r == r)) r = 0.0f;
+    float hi = p_unsigned ? 255.0f : 127.0f, lo = p_unsigned ? 0.0f : -127.0f;
+    if (r > hi) r = hi;
+    if (r < lo) r = lo;
+    return (int32_t)r;
+}
+
 ORC_API void orc_attention_i8(const int8_t *qkv, const int32_t *cu, int B, int H, int heads,
                               float s_q, float s_k, float s_v, float s_p, float s_ctx,
-                              int8_t *ctx, int8_t *p_dump)
+                              int p_unsigned, int8_t *ctx, uint8_t *p_dump)
 {
     int d = H / heads;
     float m_sc = (float)((double)s_q * (double)s_k / sqrt((double)d));
@@ -258,8 +273,8 @@ ORC_API void orc_attention_i8(const int8_t *qkv, const int32_t *cu, int B, int H
                 float rS = softmax_row(sc, n, e);
                 for (int j = 0; j < n; j++) {
                     float P = e[j] * rS;
-                    pq[j] = qcode(P * inv_sp);
-                    if (p_dump && b == B - 1) p_dump[((size_t)h * n + i) * n + j] = (int8_t)pq[j];
+                    pq[j] = pcode(P * inv_sp, p_unsigned);
+                    if (p_dump && b == B - 1) p_dump[((size_t)h * n + i) * n + j] = (uint8_t)pq[j];
                 }
                 for (int c = 0; c < d; c++) {
                     int32_t O = 0;
@@ -526,6 +541,7 @@ static void forward_sequence(const orc_encoder *E, const uint16_t *hidden, int n
         const orc_layer *Y = &E->L[l];
         const orc_layer_scales *s = &Y->s;
         int mha8 = (Y->mode & ORC_MHA_INT8) != 0, ffn8 = (Y->mode & ORC_FFN_INT8) != 0;
+        int pu = (Y->mode & ORC_P_UNSIGNED) != 0;
         int last = (l == Lc - 1);
         int next8 = !last && (E->L[l + 1].mode & ORC_MHA_INT8);
         int tp = taps && taps->layer == l;
@@ -534,7 +550,7 @@ static void forward_sequence(const orc_encoder *E, const uint16_t *hidden, int n
         if (mha8) {
             gemm_i8_t((const int8_t *)x, Y->qkv_t, acc, n, 3 * H, H);
             orc_epilogue_requant(acc, n, 3 * H, Y->m_qkv, Y->b_qkv_q, (int8_t *)qkv);
-            orc_attention_i8((const int8_t *)qkv, cu, 1, H, heads, s->q, s->k, s->v, s->p, s->ctx, (int8_t *)ctx, NULL);
+            orc_attention_i8((const int8_t *)qkv, cu, 1, H, heads, s->q, s->k, s->v, s->p, s->ctx, pu, (int8_t *)ctx, NULL);
             gemm_i8_t((const int8_t *)ctx, Y->o_t, acc, n, H, H);
             orc_epilogue_requant(acc, n, H, Y->m_o, Y->zero_h, (int8_t *)ao);
         } else {

@@ -388,6 +388,46 @@ def test_int8_attention_closed_forms():
     assert np.array_equal(ctx[n].astype(np.int64), want1.astype(np.int64))
 
 
+def test_int8_attention_unsigned_softmax_codes():
+    """Variant that spends all 256 codes on [0, 1] (Section 4.2 / Appendix B name the idle negative half of the
+    symmetric code as the main accuracy loss): codes are rne(P / s) clamped to [0, 255]; everything else is unchanged."""
+    rng = np.random.default_rng(17)
+    heads, d = 2, 64
+    H = heads * d
+    n = 23
+    cu = np.array([0, 3, 3 + n], np.int32)
+    qkv = rng.integers(-127, 128, (int(cu[-1]), 3 * H), dtype=np.int8)
+    s_q, s_k, s_v, s_ctx = map(np.float32, (0.021, 0.025, 0.02, 0.0067))
+    x = qkv[cu[1]:cu[2]].astype(np.int64)
+    P64 = [_softmax64((x[:, h * d:(h + 1) * d] @ x[:, H + h * d:H + (h + 1) * d].T).astype(np.float64)
+                      * float(s_q) * float(s_k) / math.sqrt(d)) for h in range(heads)]
+    absmax = max(p.max() for p in P64) * 0.8                       # some probabilities clamp
+    s_signed, s_unsigned = np.float32(absmax / 127), np.float32(absmax / 255)
+    ctx, Pu = oracle.attention_i8(qkv, cu, heads, s_q, s_k, s_v, s_unsigned, s_ctx, dump_p=True, p_unsigned=True)
+    _, Ps = oracle.attention_i8(qkv, cu, heads, s_q, s_k, s_v, s_signed, s_ctx, dump_p=True)
+    assert Pu.dtype == np.uint8 and Pu.max() == 255 and Ps.max() == 127
+    m_ctx = np.float32(np.float64(s_unsigned) * np.float64(s_v) / np.float64(s_ctx))
+    err_u, err_s = [], []
+    for h in range(heads):
+        codes = Pu[h].astype(np.float64)
+        assert np.abs(codes - np.clip(P64[h] / float(s_unsigned), 0, 255)).max() <= 0.5 + 1e-3
+        v = x[:, 2 * H + h * d:2 * H + (h + 1) * d]
+        O = Pu[h].astype(np.int64) @ v                                   # exact integer P.V from the dumped codes
+        want = np.clip(np.rint(O.astype(np.float32) * m_ctx), -127, 127).astype(np.int8)
+        assert np.array_equal(ctx[cu[1]:cu[2], h * d:(h + 1) * d], want)
+        inside = P64[h] < absmax * 0.99
+        err_u.append(np.abs(codes * float(s_unsigned) - P64[h])[inside])
+        err_s.append(np.abs(Ps[h].astype(np.float64) * float(s_signed) - P64[h])[inside])
+    # twice as many levels over the same range: half the rounding error
+    ratio = np.concatenate(err_u).mean() / np.concatenate(err_s).mean()
+    assert 0.4 <= ratio <= 0.6
+    # a single-key sequence has probability 1: the top code
+    one = rng.integers(-127, 128, (1, 3 * H), dtype=np.int8)
+    _, P1 = oracle.attention_i8(one, np.array([0, 1], np.int32), heads, s_q, s_k, s_v, np.float32(1 / 255), s_ctx,
+                                dump_p=True, p_unsigned=True)
+    assert P1.shape == (heads, 1, 1) and (P1 == 255).all()
+
+
 def test_attention_sequences_are_independent():
     rng = np.random.default_rng(16)
     heads, d = 2, 64
