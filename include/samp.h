@@ -47,8 +47,12 @@ extern "C" {
 
 typedef struct samp_encoder samp_encoder_t;
 
-/* per-layer precision: bit 0 = MHA block INT8, bit 1 = FFN block INT8 (Section 3.2, Table 1) */
-enum { SAMP_FP16 = 0, SAMP_MHA_INT8 = 1, SAMP_FFN_INT8 = 2, SAMP_FULL_INT8 = 3 };
+/* per-layer precision: bit 0 = MHA block INT8, bit 1 = FFN block INT8 (Section 3.2, Table 1).
+ * SAMP_P_UNSIGNED, valid only together with bit 0, stores the softmax output of that layer as
+ * unsigned codes rne(P / s_p) in [0, 255] instead of the symmetric [-127, 127], whose negative
+ * half a softmax never uses (the loss Section 4.2 and Appendix B describe); the caller then
+ * passes the step s_p = absmax(P) / 255 in samp_layer_scales_t.                                  */
+enum { SAMP_FP16 = 0, SAMP_MHA_INT8 = 1, SAMP_FFN_INT8 = 2, SAMP_FULL_INT8 = 3, SAMP_P_UNSIGNED = 4 };
 
 enum {
     SAMP_OK = 0,
@@ -169,6 +173,11 @@ SAMP_API int samp_allocate_decay_aware(const double *accuracy, const double *lat
 SAMP_API int samp_recommend(const double *accuracy, const double *latency, int32_t n, double max_latency,
                             double min_accuracy, int32_t *settings_out, int32_t capacity, int32_t *count_out);
 
+/* Code-usage statistic of any int8 tensor (Appendix B compares the softmax codes with the codes of
+ * the attention output): ADDS to hist[256] (dev uint64, zeroed by the caller; index = the code as
+ * an unsigned byte) the number of occurrences of each code among codes[0..n).                     */
+SAMP_API int samp_code_histogram(const int8_t *codes, size_t n, uint64_t *hist, void *stream);
+
 /* Tuning aid: force the tile configuration of every GEMM launched afterwards by this process
  * (0: 128x128 tile with 64-byte K stages, 1: 128x128 with 128-byte stages, 2: 64 tokens x 128
  * channels), or -1 (default) to choose by problem shape.  Configurations 1 and 2 need the operand
@@ -200,10 +209,14 @@ SAMP_API int samp_gemm_f16(const uint16_t *A, const uint16_t *W, const float *bi
 /* Softmax attention over packed rows.  qkv: dev [T,3H] (int8 or fp16), columns [0,H) Q, [H,2H) K,
  * [2H,3H) V.  cu_seqlens: dev int32 [B+1], sequence b owns rows cu[b]..cu[b+1); max_len >= every
  * length, <= 512.  INT8 flavour (Section 4.2 / Appendix B: quantised softmax output):
- * score = float(q.k) * (s_q s_k / 8); P = softmax; Pq = rne(P / s_p); ctx = rne(float(Pq.V) * s_p s_v / s_ctx). */
+ * score = float(q.k) * (s_q s_k / 8); P = softmax; Pq = rne(P / s_p) clamped to [-127, 127], or to
+ * [0, 255] if p_unsigned != 0; ctx = rne(float(Pq.V) * s_p s_v / s_ctx).
+ * p_hist: NULL, or dev uint64 [256] to which the kernel ADDS the number of times each code byte
+ * (index = the code as an unsigned byte) occurs among the softmax codes of valid query/key pairs
+ * (the caller zeroes it): the code-usage statistic of Appendix B.                                 */
 SAMP_API int samp_attention_i8(const int8_t *qkv, const int32_t *cu_seqlens, int32_t B, int32_t max_len, int32_t hidden,
-                               int32_t heads, float s_q, float s_k, float s_v, float s_p, float s_ctx, int8_t *ctx,
-                               void *stream);
+                               int32_t heads, float s_q, float s_k, float s_v, float s_p, float s_ctx, int32_t p_unsigned,
+                               int8_t *ctx, uint64_t *p_hist, void *stream);
 SAMP_API int samp_attention_f16(const uint16_t *qkv, const int32_t *cu_seqlens, int32_t B, int32_t max_len, int32_t hidden,
                                 int32_t heads, uint16_t *ctx, void *stream);
 

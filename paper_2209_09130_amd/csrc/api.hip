@@ -57,6 +57,9 @@ size_t staging_bytes(const samp_config_t &c)
     return up(big * 2) + up((size_t)std::max(3 * c.hidden, c.ffn) * sizeof(float));
 }
 
+// bit 0: MHA INT8, bit 1: FFN INT8, bit 2 (only with bit 0): unsigned softmax codes
+bool valid_mode(int m) { return m >= 0 && m <= 7 && (!(m & SAMP_P_UNSIGNED) || (m & SAMP_MHA_INT8)); }
+
 int check_config(const samp_config_t *c)
 {
     if (!c) return fail(SAMP_ERR_ARG, "config is NULL");
@@ -212,7 +215,8 @@ int run(samp_encoder_t *enc, const void *hidden, const int32_t *mask, int B, int
             HIP_TRY(launch_gemm_i8(EPI_REQUANT, (const int8_t *)x, (const int8_t *)Y.w_qkv, w.qkv, Y.m_qkv, Y.bq_qkv, 0.f,
                                    rows, 3 * H, H, st, timing(enc, SAMP_PROF_QKV)));
             HIP_TRY(launch_attention_i8((const int8_t *)w.qkv, cu, B, S, H, heads, Y.m_sc, Y.inv_sp, Y.m_ctx,
-                                        (int8_t *)w.ctx, st, timing(enc, SAMP_PROF_ATTN)));
+                                        (Y.mode & SAMP_P_UNSIGNED) != 0, (int8_t *)w.ctx, nullptr, st,
+                                        timing(enc, SAMP_PROF_ATTN)));
             HIP_TRY(launch_gemm_i8(EPI_REQUANT, (const int8_t *)w.ctx, (const int8_t *)Y.w_o, w.ao, Y.m_o, nullptr, 0.f,
                                    rows, H, H, st, timing(enc, SAMP_PROF_ATTN_OUT)));
         } else {
@@ -271,7 +275,7 @@ size_t samp_encoder_arena_bytes(const samp_config_t *cfg, const uint8_t *modes)
     if (!modes) { fail(SAMP_ERR_ARG, "modes is NULL"); return 0; }
     size_t n = 0;
     for (int l = 0; l < cfg->layers; l++) {
-        if (modes[l] > 3) { fail(SAMP_ERR_ARG, "unknown mode %d for layer %d", modes[l], l); return 0; }
+        if (!valid_mode(modes[l])) { fail(SAMP_ERR_ARG, "unknown mode %d for layer %d", modes[l], l); return 0; }
         n += layer_arena_bytes(*cfg, modes[l]);
     }
     return n + staging_bytes(*cfg);
@@ -286,7 +290,7 @@ int samp_encoder_create(const samp_config_t *cfg, const uint8_t *modes, const sa
     *out = nullptr;
     bool any8 = false;
     for (int l = 0; l < cfg->layers; l++) {
-        if (modes[l] > 3) return fail(SAMP_ERR_ARG, "unknown mode %d for layer %d", modes[l], l);
+        if (!valid_mode(modes[l])) return fail(SAMP_ERR_ARG, "unknown mode %d for layer %d", modes[l], l);
         any8 |= modes[l] != 0;
         const samp_layer_weights_t &w = weights[l];
         if (!w.w_qkv || !w.w_o || !w.w_ffn1 || !w.w_ffn2 || !w.b_qkv || !w.b_o || !w.b_ffn1 || !w.b_ffn2 || !w.ln1_g ||
@@ -600,14 +604,16 @@ static int check_attention(const void *qkv, const int32_t *cu, int B, int max_le
 }
 
 int samp_attention_i8(const int8_t *qkv, const int32_t *cu, int32_t B, int32_t max_len, int32_t hidden, int32_t heads,
-                      float s_q, float s_k, float s_v, float s_p, float s_ctx, int8_t *ctx, void *stream)
+                      float s_q, float s_k, float s_v, float s_p, float s_ctx, int32_t p_unsigned, int8_t *ctx,
+                      uint64_t *p_hist, void *stream)
 {
     if (int rc = check_attention(qkv, cu, B, max_len, hidden, heads, ctx)) return rc;
     if (!(good_scale(s_q) && good_scale(s_k) && good_scale(s_v) && good_scale(s_p) && good_scale(s_ctx)))
         return fail(SAMP_ERR_SCALE, "attention scales must be finite and positive");
     const float m_sc = (float)((double)s_q * (double)s_k / std::sqrt(64.0));
     const float m_ctx = (float)((double)s_p * (double)s_v / (double)s_ctx);
-    HIP_TRY(launch_attention_i8(qkv, cu, B, max_len, hidden, heads, m_sc, 1.0f / s_p, m_ctx, ctx, (hipStream_t)stream, nullptr));
+    HIP_TRY(launch_attention_i8(qkv, cu, B, max_len, hidden, heads, m_sc, 1.0f / s_p, m_ctx, p_unsigned != 0, ctx,
+                                reinterpret_cast<unsigned long long *>(p_hist), (hipStream_t)stream, nullptr));
     return SAMP_OK;
 }
 
@@ -678,6 +684,14 @@ int samp_recommend(const double *accuracy, const double *latency, int32_t n, dou
     if (capacity < 1) return fail(SAMP_ERR_ARG, "capacity must be >= 1");
     if (std::isinf(max_latency) || std::isinf(min_accuracy)) return fail(SAMP_ERR_ARG, "thresholds must be finite or NaN (unset)");
     *count_out = recommend_settings(accuracy, latency, n, max_latency, min_accuracy, settings_out, capacity);
+    return SAMP_OK;
+}
+
+int samp_code_histogram(const int8_t *codes, size_t n, uint64_t *hist, void *stream)
+{
+    if (!codes || !hist) return fail(SAMP_ERR_ARG, "NULL pointer");
+    if (n < 1) return fail(SAMP_ERR_SHAPE, "n must be >= 1");
+    HIP_TRY(launch_code_histogram(codes, n, reinterpret_cast<unsigned long long *>(hist), (hipStream_t)stream));
     return SAMP_OK;
 }
 

@@ -56,11 +56,18 @@ __device__ __forceinline__ SeqInfo seq_info(const int *cu, int b, int max_len)
     return {b * max_len, max_len};
 }
 
-template <int NT>
+// PU: the softmax codes are unsigned, rne(P / s_p) in [0, 255] (the variant that spends all 256 codes
+//     on [0, 1]).  The matrix core multiplies signed bytes, so it is fed code - 128 (a flip of the top
+//     bit) and the missing 128 * sum_k V[k] is added back from a second product of the same V tile with
+//     a row of ones; both are exact in int32.
+// HIST: also counts every softmax code of a valid (query, key) pair into p_hist[256] (a diagnostic:
+//     which of the 256 integers the softmax output uses, as Appendix B tabulates).
+template <int NT, bool PU, bool HIST>
 __global__ __launch_bounds__(256) void attention_i8_kernel(const int8_t *__restrict__ qkv, const int *__restrict__ cu,
                                                            int max_len, int H, float m_sc, float inv_sp, float m_ctx,
-                                                           int8_t *__restrict__ ctx)
+                                                           int8_t *__restrict__ ctx, unsigned long long *__restrict__ p_hist)
 {
+    __shared__ unsigned hist[HIST ? 256 : 1];
     __shared__ __attribute__((aligned(16))) int8_t vt[4][NT][64 * VT_STRIDE_I8];
     __shared__ __attribute__((aligned(16))) int so[4][QB][64];
     __shared__ float smax[4][QB];
@@ -73,6 +80,7 @@ __global__ __launch_bounds__(256) void attention_i8_kernel(const int8_t *__restr
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, g = lane >> 5;
     const size_t ld = (size_t)3 * H;
     const int8_t *base = qkv + (size_t)sq.t0 * ld + head * 64;
+    if (HIST) hist[tid] = 0;                                      // ordered before its use by the barriers below
 
     // Q strip: second MFMA operand, lane (query r, half g) holds 16 consecutive bytes of the head dim
     const int qrow = min(q0 + r, n - 1);
@@ -143,21 +151,29 @@ __global__ __launch_bounds__(256) void attention_i8_kernel(const int8_t *__restr
     const float S = (float)(((ssum[0][r] + ssum[1][r]) + ssum[2][r]) + ssum[3][r]);
     const float rS = __fdiv_rn(1.0f, S);
 
-    v16i o[2];
+    v16i o[2], o1[PU ? 2 : 1];
 #pragma unroll
     for (int cb = 0; cb < 2; cb++)
 #pragma unroll
-        for (int e = 0; e < 16; e++) o[cb][e] = 0;
+        for (int e = 0; e < 16; e++) { o[cb][e] = 0; if (PU) o1[cb][e] = 0; }
+    const float lo = PU ? 0.0f : -127.0f, hi = PU ? 255.0f : 127.0f;
+    const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
 #pragma unroll
     for (int i = 0; i < NT; i++) {
-        if ((w + 4 * i) * 32 < n) {
+        const int j0 = (w + 4 * i) * 32;
+        if (j0 < n) {
             v4i pf;
 #pragma unroll
             for (int q = 0; q < 4; q++) {
-                int c[4];
+                float f[4];
 #pragma unroll
-                for (int t = 0; t < 4; t++) c[t] = qcode((sc[i][4 * q + t] * rS) * inv_sp);
-                pf[q] = pack4(c[0], c[1], c[2], c[3]);
+                for (int t = 0; t < 4; t++) {
+                    // clamp, then round half to even in the adder: the code is the low byte of f
+                    f[t] = __builtin_amdgcn_fmed3f((sc[i][4 * q + t] * rS) * inv_sp, lo, hi) + SAMP_RNE_MAGIC;
+                    if (HIST && q0 + r < n && j0 + 8 * q + 4 * g + t < n) atomicAdd(&hist[__float_as_uint(f[t]) & 0xffu], 1u);
+                }
+                pf[q] = pack_codes(f[0], f[1], f[2], f[3]);
+                if (PU) pf[q] ^= (int)0x80808080u;                 // code - 128 as a signed byte
             }
 #pragma unroll
             for (int cb = 0; cb < 2; cb++) {
@@ -166,8 +182,15 @@ __global__ __launch_bounds__(256) void attention_i8_kernel(const int8_t *__restr
                 for (int q = 0; q < 4; q++)
                     vf[q] = *reinterpret_cast<const int *>(&vt[w][i][(cb * 32 + r) * VT_STRIDE_I8 + 8 * q + 4 * g]);
                 o[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(pf, vf, o[cb], 0, 0, 0);
+                if (PU) o1[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ones, vf, o1[cb], 0, 0, 0);
             }
         }
+    }
+    if (PU) {
+#pragma unroll
+        for (int cb = 0; cb < 2; cb++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) o[cb][e] += o1[cb][e] * 128;
     }
     // partial context of this wave: lane holds channel cb*32 + r and queries 8q + 4g + t
 #pragma unroll
@@ -187,6 +210,7 @@ __global__ __launch_bounds__(256) void attention_i8_kernel(const int8_t *__restr
         v2i pk = {pack4(codes[0], codes[1], codes[2], codes[3]), pack4(codes[4], codes[5], codes[6], codes[7])};
         *reinterpret_cast<v2i *>(ctx + (size_t)(sq.t0 + q0 + query) * H + head * 64 + c0) = pk;
     }
+    if (HIST && hist[tid]) atomicAdd(&p_hist[tid], (unsigned long long)hist[tid]);   // after the barrier above
 }
 
 // FP16 flavour: fp16 q, k, v; binary32 scores, fast exp; P rounded to fp16 before P.V; binary32
@@ -313,16 +337,31 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const __half *__rest
 
 }  // namespace
 
-hipError_t launch_attention_i8(const int8_t *qkv, const int *cu, int B, int max_len, int H, int heads, float m_sc,
-                               float inv_sp, float m_ctx, int8_t *ctx, hipStream_t st, const Timing *tm)
+template <bool PU, bool HIST>
+static void launch_attention_i8_variant(const int8_t *qkv, const int *cu, int B, int max_len, int H, int heads, float m_sc,
+                                        float inv_sp, float m_ctx, int8_t *ctx, unsigned long long *p_hist, hipStream_t st,
+                                        const Timing *tm)
 {
     dim3 grid((max_len + QB - 1) / QB, heads, B), block(256);
     if (max_len <= 128)
-        launch_kernel(attention_i8_kernel<1>, grid, block, 0, st, tm, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx);
+        launch_kernel(attention_i8_kernel<1, PU, HIST>, grid, block, 0, st, tm, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx, p_hist);
     else if (max_len <= 256)
-        launch_kernel(attention_i8_kernel<2>, grid, block, 0, st, tm, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx);
+        launch_kernel(attention_i8_kernel<2, PU, HIST>, grid, block, 0, st, tm, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx, p_hist);
     else
-        launch_kernel(attention_i8_kernel<4>, grid, block, 0, st, tm, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx);
+        launch_kernel(attention_i8_kernel<4, PU, HIST>, grid, block, 0, st, tm, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx, p_hist);
+}
+
+hipError_t launch_attention_i8(const int8_t *qkv, const int *cu, int B, int max_len, int H, int heads, float m_sc,
+                               float inv_sp, float m_ctx, bool p_unsigned, int8_t *ctx, unsigned long long *p_hist,
+                               hipStream_t st, const Timing *tm)
+{
+    if (p_unsigned) {
+        if (p_hist) launch_attention_i8_variant<true, true>(qkv, cu, B, max_len, H, heads, m_sc, inv_sp, m_ctx, ctx, p_hist, st, tm);
+        else launch_attention_i8_variant<true, false>(qkv, cu, B, max_len, H, heads, m_sc, inv_sp, m_ctx, ctx, p_hist, st, tm);
+    } else {
+        if (p_hist) launch_attention_i8_variant<false, true>(qkv, cu, B, max_len, H, heads, m_sc, inv_sp, m_ctx, ctx, p_hist, st, tm);
+        else launch_attention_i8_variant<false, false>(qkv, cu, B, max_len, H, heads, m_sc, inv_sp, m_ctx, ctx, p_hist, st, tm);
+    }
     return hipGetLastError();
 }
 

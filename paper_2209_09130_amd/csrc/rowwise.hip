@@ -4,6 +4,7 @@
 // All of them move each byte once with coalesced 4..16-byte accesses; reductions stay inside a wave.
 #include "samp_common.h"
 #include <hip/hip_ext.h>
+#include <algorithm>
 
 namespace samp {
 namespace {
@@ -294,6 +295,27 @@ __global__ __launch_bounds__(256) void gelu_quant_kernel(const float *__restrict
     }
 }
 
+// counts of each byte value: per-block counters in LDS, merged with one global atomic per bin
+__global__ __launch_bounds__(256) void code_histogram_kernel(const int8_t *__restrict__ codes, size_t n,
+                                                             unsigned long long *__restrict__ hist)
+{
+    __shared__ unsigned h[256];
+    h[threadIdx.x] = 0;
+    __syncthreads();
+    const size_t nvec = n / 16;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (size_t)gridDim.x * 256) {
+        const v4i v = reinterpret_cast<const v4i *>(codes)[i];
+#pragma unroll
+        for (int k = 0; k < 4; k++)
+#pragma unroll
+            for (int b = 0; b < 4; b++) atomicAdd(&h[((unsigned)v[k] >> (8 * b)) & 0xffu], 1u);
+    }
+    if (blockIdx.x == 0)
+        for (size_t i = nvec * 16 + threadIdx.x; i < n; i += 256) atomicAdd(&h[(unsigned char)codes[i]], 1u);
+    __syncthreads();
+    if (h[threadIdx.x]) atomicAdd(&hist[threadIdx.x], (unsigned long long)h[threadIdx.x]);
+}
+
 __global__ void fill_f32_kernel(float *p, int n, float v)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -371,6 +393,13 @@ hipError_t launch_gelu_quant(const float *y, size_t n, float inv_s, int8_t *code
     size_t blocks = (n + 255) / 256;
     if (blocks > 16384) blocks = 16384;
     hipLaunchKernelGGL(gelu_quant_kernel, dim3((unsigned)blocks), dim3(256), 0, st, y, n, inv_s, codes, fast);
+    return hipGetLastError();
+}
+
+hipError_t launch_code_histogram(const int8_t *codes, size_t n, unsigned long long *hist, hipStream_t st)
+{
+    const size_t blocks = std::min<size_t>((n / 16 + 255) / 256 + 1, 2048);
+    hipLaunchKernelGGL(code_histogram_kernel, dim3((unsigned)blocks), dim3(256), 0, st, codes, n, hist);
     return hipGetLastError();
 }
 

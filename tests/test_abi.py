@@ -49,7 +49,9 @@ def test_invalid_arguments_become_error_codes_on_the_host(L):
     assert b"head size" in L.samp_last_error()
     bad_seq = _Config(2, 768, 12, 3072, 8, 1024, 1e-12)
     assert L.samp_encoder_arena_bytes(C.byref(bad_seq), modes) == 0
-    assert L.samp_encoder_arena_bytes(C.byref(ok), (C.c_uint8 * 2)(7, 0)) == 0
+    assert L.samp_encoder_arena_bytes(C.byref(ok), (C.c_uint8 * 2)(8, 0)) == 0
+    assert L.samp_encoder_arena_bytes(C.byref(ok), (C.c_uint8 * 2)(6, 0)) == 0       # unsigned softmax codes need an INT8 MHA
+    assert L.samp_encoder_arena_bytes(C.byref(ok), (C.c_uint8 * 2)(7, 5)) > 0
     assert L.samp_encoder_arena_bytes(None, modes) == 0
     # step entry points reject NULL pointers and unsupported shapes before touching the device
     assert L.samp_gemm_i8_i32(None, None, None, 1, 128, 64, None) == -1

@@ -21,7 +21,7 @@ import pytest
 
 import oracle
 import samp_workloads as W
-from samp_workloads import FP16, MHA_INT8, FFN_INT8, FULL_INT8
+from samp_workloads import FP16, MHA_INT8, FFN_INT8, FULL_INT8, P_UNSIGNED
 
 pytestmark = pytest.mark.gpu
 
@@ -193,6 +193,51 @@ def test_c2_bert_base_12_layers_batch_32_end_to_end(P, mode):
     d = compare(got[pick], want, lens[pick], True, f"C2 {W.MODE_NAMES[mode]}")
     if mode == FULL_INT8:
         assert (d == 0).all()
+
+
+def unsigned_p_scales(sc):
+    """The calibrated softmax step is absmax/127; the unsigned code covers the same range with 255 levels."""
+    sc = sc.copy()
+    sc[:, 4] = (sc[:, 4].astype(np.float32) * np.float32(127.0 / 255.0)).astype(np.float32)
+    return sc
+
+
+@pytest.mark.parametrize("varlen", [False, True])
+def test_small_encoder_with_unsigned_softmax_codes_is_bit_identical(P, varlen):
+    w = small((FULL_INT8 | P_UNSIGNED, MHA_INT8 | P_UNSIGNED, FULL_INT8 | P_UNSIGNED, FULL_INT8), varlen=varlen)
+    wts = W.make_weights(w)
+    hid, lens, mask = W.make_hidden(w)
+    sc = unsigned_p_scales(oracle.calibrate(*args(w), wts, W.make_calibration_batch(w)))
+    want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid, lens)
+    got = run_gpu(P, w, wts, sc, hid, mask if varlen else None)
+    compare(got, want, lens, False, f"small unsigned-P varlen={varlen}")     # layer 1 has an FP16 FFN
+    w = small((FULL_INT8 | P_UNSIGNED,) * 3, varlen=varlen)
+    want = oracle.Encoder(*args(w), w.modes, wts[:3], sc[:3]).forward(hid, lens)
+    got = run_gpu(P, w, wts[:3], sc[:3], hid, mask if varlen else None)
+    assert (compare(got, want, lens, True, "small all unsigned-P") == 0).all()
+
+
+def test_c2_fully_quant_with_unsigned_softmax_codes(P):
+    """The variant at the benchmark shape: bit-identical to the oracle.  With random weights attention is nearly
+    uniform and the softmax rounding is a small part of the total error, so the distance to the unquantised reference
+    only has to be no worse than with the symmetric code (the halving of the softmax rounding error itself is pinned
+    at the step level)."""
+    base = W.config("C2")
+    wts = W.make_weights(base)
+    hid, lens, _ = W.make_hidden(base)
+    sc = oracle.calibrate(*args(base), wts, W.make_calibration_batch(base))
+    pick = [3, 30]
+    ref, _ = oracle.reference_forward(*args(base), wts, hid[pick], lens[pick])
+    dist = {}
+    for name, flag, scales in (("symmetric", 0, sc), ("unsigned", P_UNSIGNED, unsigned_p_scales(sc))):
+        w = base.with_modes(FULL_INT8 | flag)
+        got = run_gpu(P, w, wts, scales, hid, None)
+        want = oracle.Encoder(*args(w), w.modes, wts, scales).forward(hid[pick], lens[pick])
+        assert (compare(got[pick], want, lens[pick], True, f"C2 FULL_INT8 {name} softmax codes") == 0).all()
+        dist[name] = float(np.abs(got[pick].astype(np.float64) - ref).mean())
+    print(f"[parity] C2 mean |out - unquantised reference|: symmetric {dist['symmetric']:.4g}  unsigned {dist['unsigned']:.4g}",
+          flush=True)
+    assert dist["unsigned"] <= 1.02 * dist["symmetric"]
 
 
 @pytest.mark.parametrize("mode", [FFN_INT8, MHA_INT8])

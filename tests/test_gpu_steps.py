@@ -215,6 +215,52 @@ def test_int8_attention_peaked_softmax_bit_exact(P):
     assert np.array_equal(got, want)
 
 
+@pytest.mark.parametrize("lens,heads", [([128], 2), ([1, 5, 32, 33, 64, 17], 3), ([300, 512, 129], 1)])
+def test_int8_attention_unsigned_softmax_codes_bit_exact(P, lens, heads):
+    """Codes 0..255 for the softmax output: the kernel feeds code - 128 to the signed matrix core and adds
+    128 * sum(V) back; the context must equal the oracle's, which multiplies the unsigned codes directly."""
+    rng = np.random.default_rng(sum(lens) + 3)
+    H = heads * 64
+    cu = _cu(lens)
+    qkv = np.clip(np.rint(rng.standard_normal((int(cu[-1]), 3 * H)) * 30), -127, 127).astype(np.int8)
+    for sc in ((0.0209, 0.0249, 0.021, 0.00015, 0.0021), (0.05, 0.05, 0.021, 0.002, 0.006)):
+        want = oracle.attention_i8(qkv, cu, heads, *sc, p_unsigned=True)
+        got = host(P.attention_i8(dev(qkv), dev(cu), max(lens), heads, *sc, p_unsigned=True))
+        assert np.array_equal(got, want)
+        assert np.abs(want).max() > 20
+
+
+def test_softmax_code_usage_histogram(P):
+    """The statistic of Appendix B (how many of the 256 integers a tensor's codes use) on synthetic data: the
+    kernel's count of the softmax codes equals the count of the oracle's dumped codes, and samp_code_histogram of the
+    context equals numpy's bincount.  Symmetric softmax codes never use the negative half (on this input 67.6 % of
+    the integers stay unused; the paper reports 67.58 % on its data), unsigned codes reach into the upper half."""
+    rng = np.random.default_rng(31)
+    heads, lens = 2, [7, 150]
+    H = heads * 64
+    cu = _cu(lens)
+    qkv = np.clip(np.rint(rng.standard_normal((int(cu[-1]), 3 * H)) * 30), -127, 127).astype(np.int8)
+    used = {}
+    for p_unsigned in (False, True):
+        sc = (0.03, 0.03, 0.021, 0.3 / (255 if p_unsigned else 127), 0.004)
+        ctx, hist = P.attention_i8(dev(qkv), dev(cu), max(lens), heads, *sc, p_unsigned=p_unsigned, want_hist=True)
+        want_hist = np.zeros(256, np.int64)
+        for b in range(len(lens)):                           # the oracle dumps the codes of the last sequence it is given
+            sl = slice(cu[b], cu[b + 1])
+            _, Pq = oracle.attention_i8(qkv[sl], np.array([0, lens[b]], np.int32), heads, *sc, dump_p=True,
+                                        p_unsigned=p_unsigned)
+            want_hist += np.bincount(Pq.view(np.uint8).ravel(), minlength=256)
+        assert np.array_equal(host(hist), want_hist)
+        assert want_hist.sum() == heads * sum(n * n for n in lens)
+        used[p_unsigned] = want_hist > 0
+        ctx_hist = host(P.code_histogram(ctx))
+        assert np.array_equal(ctx_hist, np.bincount(host(ctx).view(np.uint8).ravel(), minlength=256))
+    assert not used[False][128:].any() and 0.6 < 1 - used[False].mean() < 0.75
+    assert used[True][128:].any() and used[True].sum() > used[False].sum()
+    odd = dev(qkv.ravel()[:12345])                              # a length that is not a multiple of 16
+    assert np.array_equal(host(P.code_histogram(odd)), np.bincount(qkv.ravel()[:12345].view(np.uint8), minlength=256))
+
+
 @pytest.mark.parametrize("lens,heads", [([128], 2), ([1, 5, 32, 33, 64, 17], 3), ([300, 512], 1)])
 def test_fp16_attention_within_tolerance(P, lens, heads):
     rng = np.random.default_rng(sum(lens) + 1)
