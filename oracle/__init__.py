@@ -231,6 +231,30 @@ def add_ln(inp: np.ndarray, s_in: float, bias: np.ndarray, res: np.ndarray, s_re
     return out
 
 
+class _Embedding(C.Structure):
+    _fields_ = [("tok", C.c_void_p), ("seg", C.c_void_p), ("pos", C.c_void_p), ("gamma", C.c_void_p), ("beta", C.c_void_p),
+                ("vocab", C.c_int32), ("segments", C.c_int32), ("positions", C.c_int32), ("eps", C.c_float)]
+
+
+def _embedding(emb: Dict[str, np.ndarray]):
+    """emb: tok [V,H], seg [G,H], pos [P,H] fp16; gamma, beta [H] fp32; eps."""
+    keep = [_f16(emb["tok"]), _f16(emb["seg"]), _f16(emb["pos"]), _f32(emb["gamma"]), _f32(emb["beta"])]
+    e = _Embedding(*[a.ctypes.data for a in keep], keep[0].shape[0], keep[1].shape[0], keep[2].shape[0], float(emb["eps"]))
+    return e, keep
+
+
+def embed_ln(emb: Dict[str, np.ndarray], token_ids: np.ndarray, segment_ids: Optional[np.ndarray], out_i8: bool,
+             s_out: float = 1.0) -> np.ndarray:
+    """Embedding kernel for ONE sequence: LayerNorm(tok[id] + seg[sid] + pos[s]) as fp16 or int8 codes."""
+    e, keep = _embedding(emb)
+    ids = np.ascontiguousarray(token_ids, np.int32)
+    seg = None if segment_ids is None else np.ascontiguousarray(segment_ids, np.int32)
+    H = keep[0].shape[1]
+    out = np.empty((ids.size, H), np.int8 if out_i8 else np.float16)
+    lib().orc_embed_ln(C.byref(e), _p(ids), _p(seg), ids.size, H, _p(out), int(out_i8), C.c_float(s_out))
+    return out
+
+
 # ---------------------------------------------------------------- encoder
 def _weights_array(weights: Sequence[Dict[str, np.ndarray]]):
     keep = []
@@ -304,6 +328,20 @@ class Encoder:
         if rc != 0:
             raise ValueError("oracle: sequence length outside [1, S]")
         return (out, tapped) if tap_layer is not None else out
+
+    def forward_ids(self, emb: Dict[str, np.ndarray], token_ids: np.ndarray, segment_ids: Optional[np.ndarray],
+                    lens: np.ndarray, nthreads: int = 0) -> np.ndarray:
+        """The encoder with the Embedding kernel in front (ids int32 [B,S])."""
+        e, keep = _embedding(emb)
+        ids = np.ascontiguousarray(token_ids, np.int32)
+        seg = None if segment_ids is None else np.ascontiguousarray(segment_ids, np.int32)
+        B, S = ids.shape
+        lens = np.ascontiguousarray(lens, np.int32)
+        out = np.empty((B, S, self.hidden), np.float16)
+        rc = lib().orc_encoder_forward_ids(self._h, C.byref(e), _p(ids), _p(seg), _p(lens), B, S, _p(out), nthreads)
+        if rc != 0:
+            raise ValueError("oracle: sequence length outside [1, S]")
+        return out
 
     def close(self):
         if self._h:

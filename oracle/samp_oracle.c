@@ -370,6 +370,24 @@ ORC_API void orc_gemm_f16(const uint16_t *A, const uint16_t *W, const float *bia
 /*   t = fmaf(in_q, s_in, bias);  z = fmaf(res_q, s_res, t)                   */
 /* fp16 operands: t = in + bias; z = t + res (binary32 adds).                 */
 /* ------------------------------------------------------------------------ */
+/* LayerNorm of one row z[H] and its output conversion, as described above */
+static void ln_row(const float *z, int H, const float *gamma, const float *beta, float eps,
+                   void *out, size_t o, int out_i8, float inv_s)
+{
+    double mu = 0.0, var = 0.0;
+    for (int c = 0; c < H; c++) mu += (double)z[c];
+    mu /= (double)H;
+    for (int c = 0; c < H; c++) { double dlt = (double)z[c] - mu; var += dlt * dlt; }
+    var /= (double)H;
+    float mu32 = (float)mu;
+    float rstd32 = (float)(1.0 / sqrt(var + (double)eps));
+    for (int c = 0; c < H; c++) {
+        float y = fmaf((z[c] - mu32) * rstd32, gamma[c], beta[c]);
+        if (out_i8) ((int8_t *)out)[o + c] = qcode(y * inv_s);
+        else ((uint16_t *)out)[o + c] = f2h(y);
+    }
+}
+
 ORC_API void orc_add_ln(const void *in, int in_i8, float s_in, const float *bias,
                         const void *res, int res_i8, float s_res,
                         const float *gamma, const float *beta, float eps,
@@ -385,18 +403,44 @@ ORC_API void orc_add_ln(const void *in, int in_i8, float s_in, const float *bias
             z[c] = res_i8 ? fmaf((float)((const int8_t *)res)[o + c], s_res, a)
                           : a + h2f(((const uint16_t *)res)[o + c]);
         }
-        double mu = 0.0, var = 0.0;
-        for (int c = 0; c < H; c++) mu += (double)z[c];
-        mu /= (double)H;
-        for (int c = 0; c < H; c++) { double dlt = (double)z[c] - mu; var += dlt * dlt; }
-        var /= (double)H;
-        float mu32 = (float)mu;
-        float rstd32 = (float)(1.0 / sqrt(var + (double)eps));
+        ln_row(z, H, gamma, beta, eps, out, o, out_i8, inv_s);
+    }
+    free(z);
+}
+
+/* ------------------------------------------------------------------------ */
+/* Embedding kernel (Section 3.1, "Embedding": the token, segment and        */
+/* position embeddings of BERT are summed in ONE kernel; Section 3.2: for a   */
+/* quantised first block the module hands INT8 to the encoder directly).      */
+/* BERT's embedding ends with a LayerNorm, which belongs to the same kernel.  */
+/*   z[c] = (tok[id][c] + seg[sid][c]) + pos[s][c]    binary32 adds of fp16   */
+/*   out  = LayerNorm(z) as in the fused step above: fp16, or rne(y / s_out)  */
+/* The token at position s of a sequence uses pos[s].  segment_ids == NULL    */
+/* means segment 0.  Ids outside their table are clamped into it.             */
+/* ------------------------------------------------------------------------ */
+typedef struct {
+    const uint16_t *tok, *seg, *pos;    /* fp16 tables [vocab][H], [segments][H], [positions][H] */
+    const float *gamma, *beta;
+    int32_t vocab, segments, positions;
+    float eps;
+} orc_embedding;
+
+static int clampi(int v, int hi) { return v < 0 ? 0 : (v > hi ? hi : v); }
+
+ORC_API void orc_embed_ln(const orc_embedding *E, const int32_t *token_ids, const int32_t *segment_ids,
+                          int n, int H, void *out, int out_i8, float s_out)
+{
+    float *z = (float *)malloc(sizeof(float) * H);
+    float inv_s = out_i8 ? 1.0f / s_out : 0.0f;
+    for (int s = 0; s < n; s++) {
+        const uint16_t *t = E->tok + (size_t)clampi(token_ids[s], E->vocab - 1) * H;
+        const uint16_t *g = E->seg + (size_t)clampi(segment_ids ? segment_ids[s] : 0, E->segments - 1) * H;
+        const uint16_t *p = E->pos + (size_t)clampi(s, E->positions - 1) * H;
         for (int c = 0; c < H; c++) {
-            float y = fmaf((z[c] - mu32) * rstd32, gamma[c], beta[c]);
-            if (out_i8) ((int8_t *)out)[o + c] = qcode(y * inv_s);
-            else ((uint16_t *)out)[o + c] = f2h(y);
+            float a = h2f(t[c]) + h2f(g[c]);
+            z[c] = a + h2f(p[c]);
         }
+        ln_row(z, H, E->gamma, E->beta, E->eps, out, (size_t)s * H, out_i8, inv_s);
     }
     free(z);
 }
@@ -522,7 +566,9 @@ static void tap(void *dst, const void *src, size_t bytes) { if (dst) memcpy(dst,
  * follows Section 3.2: QKV GEMM, attention, attention-output GEMM, fused
  * bias+residual+LayerNorm(+quant), FFN1 GEMM + bias + GELU (+quant), FFN2 GEMM,
  * fused bias+residual+LayerNorm(+quant unless the consumer is floating point). */
-static void forward_sequence(const orc_encoder *E, const uint16_t *hidden, int n, uint16_t *out,
+typedef struct { const orc_embedding *emb; const int32_t *token_ids, *segment_ids; } orc_ids;
+
+static void forward_sequence(const orc_encoder *E, const uint16_t *hidden, const orc_ids *ids, int n, uint16_t *out,
                              const orc_taps *taps)
 {
     const int H = E->cfg.hidden, F = E->cfg.ffn, heads = E->cfg.heads, Lc = E->cfg.layers;
@@ -534,7 +580,9 @@ static void forward_sequence(const orc_encoder *E, const uint16_t *hidden, int n
     int32_t cu[2] = { 0, n };
 
     /* entry: the producer of a tensor quantises it with its consumer's step */
-    if (E->L[0].mode & ORC_MHA_INT8) orc_quantize_f16(hidden, nH, E->L[0].s.x, (int8_t *)x);
+    if (ids)                           /* the Embedding kernel is that producer */
+        orc_embed_ln(ids->emb, ids->token_ids, ids->segment_ids, n, H, x, (E->L[0].mode & ORC_MHA_INT8) != 0, E->L[0].s.x);
+    else if (E->L[0].mode & ORC_MHA_INT8) orc_quantize_f16(hidden, nH, E->L[0].s.x, (int8_t *)x);
     else memcpy(x, hidden, nH * 2);
 
     for (int l = 0; l < Lc; l++) {
@@ -598,8 +646,28 @@ ORC_API int orc_encoder_forward(const orc_encoder *E, const uint16_t *hidden, co
 #endif
     #pragma omp parallel for schedule(dynamic, 1)
     for (int b = 0; b < B; b++)
-        forward_sequence(E, hidden + (size_t)b * S * H, lens[b], out + (size_t)b * S * H,
+        forward_sequence(E, hidden + (size_t)b * S * H, NULL, lens[b], out + (size_t)b * S * H,
                          (taps && b == 0) ? taps : NULL);
+    return 0;
+}
+
+/* The same with the Embedding kernel in front: token_ids, segment_ids int32 [B,S] (segment_ids may be
+ * NULL); the first lens[b] ids of row b are used.                                                  */
+ORC_API int orc_encoder_forward_ids(const orc_encoder *E, const orc_embedding *emb, const int32_t *token_ids,
+                                    const int32_t *segment_ids, const int32_t *lens, int B, int S, uint16_t *out,
+                                    int nthreads)
+{
+    const int H = E->cfg.hidden;
+    for (int b = 0; b < B; b++) if (lens[b] < 1 || lens[b] > S) return -1;
+    memset(out, 0, (size_t)B * S * H * 2);
+#ifdef _OPENMP
+    if (nthreads > 0) omp_set_num_threads(nthreads);
+#endif
+    #pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; b++) {
+        orc_ids ids = { emb, token_ids + (size_t)b * S, segment_ids ? segment_ids + (size_t)b * S : NULL };
+        forward_sequence(E, NULL, &ids, lens[b], out + (size_t)b * S * H, NULL);
+    }
     return 0;
 }
 

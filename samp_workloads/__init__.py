@@ -161,3 +161,29 @@ def make_hidden(w: Workload, batch: Optional[int] = None):
 def make_calibration_batch(w: Workload) -> np.ndarray:
     """Full-length calibration batch (8 x 128 by default), same channel recipe."""
     return _draw_hidden(w, w.calib_seed, w.calib_batch, w.calib_seq)
+
+
+def make_embedding(w: Workload, vocab: int = 21128, segments: int = 2, seed: int = 300, plain: bool = False):
+    """Embedding tables of a BERT-style model (token, segment, position; fp16) and the LayerNorm vectors that end the
+    embedding.  N(0, 0.02) like the other weights; vocab defaults to the size of the Chinese BERT-base vocabulary."""
+    rng = np.random.default_rng(seed)
+    H = w.hidden
+    emb = {
+        "tok": (rng.standard_normal((vocab, H)) * 0.02).astype(np.float16),
+        "seg": (rng.standard_normal((segments, H)) * 0.02).astype(np.float16),
+        "pos": (rng.standard_normal((max(w.seq, 8), H)) * 0.02).astype(np.float16),
+        "gamma": np.ones(H, np.float32) if plain else (1.0 + 0.1 * rng.standard_normal(H)).astype(np.float32),
+        "beta": np.zeros(H, np.float32) if plain else (0.1 * rng.standard_normal(H)).astype(np.float32),
+        "eps": w.ln_eps,
+    }
+    return emb
+
+
+def make_ids(w: Workload, vocab: int = 21128, segments: int = 2, seed: int = 301):
+    """Token and segment ids [B,S] int32 for the workload's batch: uniform tokens, segment 0 then 1 split at a random
+    point of each sequence; ids in padded positions are random too (they must not matter)."""
+    rng = np.random.default_rng(seed)
+    ids = rng.integers(0, vocab, (w.batch, w.seq)).astype(np.int32)
+    split = rng.integers(0, w.seq + 1, w.batch)
+    seg = (np.arange(w.seq)[None, :] >= split[:, None]).astype(np.int32) % segments
+    return ids, seg

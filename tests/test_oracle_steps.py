@@ -441,3 +441,79 @@ def test_attention_sequences_are_independent():
     qf = rng.standard_normal((30, 3 * H)).astype(np.float16)
     bothf = oracle.attention_f16(qf, np.array([0, 11, 30], np.int32), heads)
     assert np.array_equal(bothf[:11], oracle.attention_f16(qf[:11], np.array([0, 11], np.int32), heads))
+
+
+# ------------------------------------------------------------------ embedding kernel
+def _emb(rng, V=50, G=2, Pn=16, H=128):
+    return {"tok": (rng.standard_normal((V, H)) * 0.5).astype(np.float16), "seg": (rng.standard_normal((G, H)) * 0.5).astype(np.float16),
+            "pos": (rng.standard_normal((Pn, H)) * 0.5).astype(np.float16),
+            "gamma": (1 + 0.2 * rng.standard_normal(H)).astype(np.float32), "beta": (0.3 * rng.standard_normal(H)).astype(np.float32),
+            "eps": 1e-12}
+
+
+def test_embedding_kernel_against_torch_embedding_and_layer_norm():
+    """Section 3.1: token + segment + position embeddings, then BERT's LayerNorm; checked against the library
+    routines in float64 (fp16 output: half an ulp; int8 output: half a step)."""
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(41)
+    emb = _emb(rng)
+    n = 13
+    ids = rng.integers(0, 50, n).astype(np.int32)
+    seg = rng.integers(0, 2, n).astype(np.int32)
+    t64 = lambda a: torch.from_numpy(np.asarray(a, np.float64))
+    z = (torch.nn.functional.embedding(torch.from_numpy(ids.astype(np.int64)), t64(emb["tok"]))
+         + torch.nn.functional.embedding(torch.from_numpy(seg.astype(np.int64)), t64(emb["seg"])) + t64(emb["pos"])[:n])
+    want = torch.nn.functional.layer_norm(z, (128,), t64(emb["gamma"]), t64(emb["beta"]), 1e-12).numpy()
+    got = oracle.embed_ln(emb, ids, seg, out_i8=False).astype(np.float64)
+    assert np.abs(got - want).max() <= np.abs(want).max() * 2.0 ** -11 + 1e-6
+    s_out = np.float32(np.abs(want).max() / 127)
+    codes = oracle.embed_ln(emb, ids, seg, out_i8=True, s_out=s_out).astype(np.float64)
+    assert np.abs(codes - want / float(s_out)).max() <= 0.5 + 1e-3 and np.abs(codes).max() == 127
+    # no segment ids = segment 0
+    assert np.array_equal(oracle.embed_ln(emb, ids, None, False), oracle.embed_ln(emb, ids, np.zeros(n, np.int32), False))
+
+
+def test_embedding_kernel_closed_forms_and_id_clamping():
+    rng = np.random.default_rng(42)
+    emb = _emb(rng)
+    # a constant row has zero variance: with eps > 0 the output is beta exactly
+    flat = dict(emb, tok=np.full((50, 128), 0.25, np.float16), seg=np.full((2, 128), -0.5, np.float16),
+                pos=np.full((16, 128), 1.0, np.float16), eps=1e-5)
+    got = oracle.embed_ln(flat, np.array([3, 4], np.int32), None, False)
+    assert np.array_equal(got, np.tile(emb["beta"].astype(np.float16), (2, 1)))
+    # the position is the index inside the sequence: the same token at two positions differs by the position rows
+    same = oracle.embed_ln(dict(emb, gamma=np.ones(128, np.float32), beta=np.zeros(128, np.float32)),
+                           np.array([7, 7], np.int32), None, False)
+    assert not np.array_equal(same[0], same[1])
+    # ids outside the tables are clamped into them
+    a = oracle.embed_ln(emb, np.array([-5, 999], np.int32), np.array([9, -1], np.int32), False)
+    b = oracle.embed_ln(emb, np.array([0, 49], np.int32), np.array([1, 0], np.int32), False)
+    assert np.array_equal(a, b)
+
+
+def test_encoder_with_embedding_entry_equals_embedding_then_encoder_for_fp16_entry():
+    """With an FP16 first block the Embedding kernel's fp16 output IS the encoder input; with an INT8 first block the
+    kernel quantises its binary32 LayerNorm value directly (Section 3.2: INT8 between Embedding and Encoder)."""
+    import samp_workloads as W
+    w = W.Workload("emb", 2, 128, 2, 256, 3, 12, (W.FFN_INT8, W.FULL_INT8), varlen=True, min_len=1, plain_params=False,
+                   calib_batch=2, calib_seq=12)
+    wts = W.make_weights(w)
+    _, lens, _ = W.make_hidden(w)
+    emb = W.make_embedding(w, vocab=64)
+    ids, seg = W.make_ids(w, vocab=64)
+    hid = np.zeros((w.batch, w.seq, w.hidden), np.float16)
+    for b in range(w.batch):
+        hid[b, :lens[b]] = oracle.embed_ln(emb, ids[b, :lens[b]], seg[b, :lens[b]], False)
+    cfg = (w.layers, w.hidden, w.heads, w.ffn, w.ln_eps)
+    sc = oracle.calibrate(*cfg, wts, hid[:2])
+    enc = oracle.Encoder(*cfg, w.modes, wts, sc)
+    assert np.array_equal(enc.forward_ids(emb, ids, seg, lens), enc.forward(hid, lens))
+    enc.close()
+    enc8 = oracle.Encoder(*cfg, (W.FULL_INT8, W.FULL_INT8), wts, sc)
+    out_ids = enc8.forward_ids(emb, ids, seg, lens)
+    x0 = oracle.embed_ln(emb, ids[0, :lens[0]], seg[0, :lens[0]], True, sc[0, 0])
+    _, taps = enc8.forward(hid[:1], lens[:1], tap_layer=0)
+    # same codes except where the fp16 rounding of the hand-over moved a value across a rounding boundary
+    assert (x0 != taps["x"]).mean() < 0.02 and np.abs(x0.astype(int) - taps["x"].astype(int)).max() <= 1
+    assert not out_ids[0, lens[0]:].any()
+    enc8.close()
