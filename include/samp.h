@@ -116,6 +116,27 @@ SAMP_API size_t samp_encoder_workspace_bytes(const samp_encoder_t *enc, int32_t 
 SAMP_API int samp_encoder_forward(samp_encoder_t *enc, const void *hidden, const int32_t *mask, int32_t B, int32_t S,
                                   void *out, void *workspace, size_t workspace_bytes, void *stream);
 
+/* Embedding module in front of the encoder (Section 3.1: the token, segment and position embeddings
+ * are summed in ONE kernel; BERT's embedding ends with a LayerNorm, which is part of it; Section 3.2:
+ * when layer 0's attention block is INT8 the kernel hands int8 to the encoder directly, quantising
+ * its binary32 LayerNorm value with layer 0's input step).  z = (tok[id] + seg[sid]) + pos[s] in
+ * binary32, s = position inside the sequence.  All pointers are device memory, 16-byte aligned,
+ * owned by the caller: tables fp16 row-major [rows, hidden], gamma / beta float [hidden].  Ids
+ * outside their table are clamped into it.  Padding bytes of the struct must be zero (memset it). */
+typedef struct {
+    const void *token_table, *segment_table, *position_table;
+    const float *gamma, *beta;
+    int32_t vocab, segments, positions;   /* rows of the three tables; positions >= S */
+    float ln_eps;
+} samp_embedding_t;
+
+/* samp_encoder_forward starting from ids: token_ids, segment_ids dev int32 [B,S] (segment_ids may be
+ * NULL = segment 0); ids at padded positions are ignored.  Everything else as samp_encoder_forward.
+ * The embedding's pointers and sizes become part of the recorded graph of this argument set.      */
+SAMP_API int samp_encoder_forward_ids(samp_encoder_t *enc, const samp_embedding_t *emb, const int32_t *token_ids,
+                                      const int32_t *segment_ids, const int32_t *mask, int32_t B, int32_t S, void *out,
+                                      void *workspace, size_t workspace_bytes, void *stream);
+
 /* Sequences are independent (all scales are static, Appendix B), so a forward may cut a small batch
  * into up to 4 groups of sequences that run concurrently on streams owned by the encoder, forked
  * from and joined back into the caller's stream; results do not depend on the split.  groups = 0
@@ -234,6 +255,11 @@ SAMP_API int samp_gelu_quant(const float *y, int64_t n, float s_out, int8_t *cod
 
 /* Per-output-channel weight quantisation: W dev fp16 [N,K] -> Wq dev int8 [N,K], s_w dev float [N]. */
 SAMP_API int samp_quantize_weight(const uint16_t *W, int32_t N, int32_t K, int8_t *Wq, float *s_w, void *stream);
+
+/* The Embedding kernel on its own (see samp_embedding_t): out dev [B*S, H], fp16 (out_i8 == 0) or
+ * int8 codes with step s_out, row b*S+s = LayerNorm(tok + seg + pos[s]).  H % 16 == 0, H <= 2048.  */
+SAMP_API int samp_embed_ln(const samp_embedding_t *emb, const int32_t *token_ids, const int32_t *segment_ids, int32_t B,
+                           int32_t S, int32_t H, void *out, int32_t out_i8, float s_out, void *stream);
 
 /* Padding removal on entry (variable-length batches): packs the valid rows of hidden [B,S,H] (fp16)
  * into packed [T,H] as fp16 (s_x <= 0) or int8 codes with step s_x; writes cu_seqlens [B+1] and

@@ -82,6 +82,39 @@ def _f(v) -> C.c_float:
     return C.c_float(float(v))
 
 
+class _EmbeddingStruct(C.Structure):
+    _fields_ = [("token_table", C.c_void_p), ("segment_table", C.c_void_p), ("position_table", C.c_void_p),
+                ("gamma", C.c_void_p), ("beta", C.c_void_p), ("vocab", C.c_int32), ("segments", C.c_int32),
+                ("positions", C.c_int32), ("ln_eps", C.c_float)]
+
+
+class Embedding:
+    """Device copies of the embedding tables and the samp_embedding_t that points at them."""
+
+    def __init__(self, tok: np.ndarray, seg: np.ndarray, pos: np.ndarray, gamma: np.ndarray, beta: np.ndarray, eps: float):
+        assert tok.dtype == seg.dtype == pos.dtype == np.float16
+        self.tok, self.seg, self.pos = (torch.from_numpy(np.ascontiguousarray(a)).cuda() for a in (tok, seg, pos))
+        self.gamma, self.beta = (torch.from_numpy(np.ascontiguousarray(a, np.float32)).cuda() for a in (gamma, beta))
+        self.hidden = tok.shape[1]
+        self.struct = _EmbeddingStruct()            # ctypes zero-fills, padding included
+        self.struct.token_table, self.struct.segment_table, self.struct.position_table = (
+            self.tok.data_ptr(), self.seg.data_ptr(), self.pos.data_ptr())
+        self.struct.gamma, self.struct.beta = self.gamma.data_ptr(), self.beta.data_ptr()
+        self.struct.vocab, self.struct.segments, self.struct.positions = tok.shape[0], seg.shape[0], pos.shape[0]
+        self.struct.ln_eps = float(eps)
+
+
+def embed_ln(emb: Embedding, token_ids: torch.Tensor, segment_ids: Optional[torch.Tensor], out_i8: bool,
+             s_out: float = 1.0) -> torch.Tensor:
+    """samp_embed_ln: [B*S, H] fp16 or int8 codes."""
+    assert token_ids.dtype == torch.int32 and token_ids.dim() == 2
+    B, S = token_ids.shape
+    out = torch.zeros((B * S, emb.hidden), dtype=torch.int8 if out_i8 else torch.float16, device=token_ids.device)
+    _check(lib().samp_embed_ln(C.byref(emb.struct), _dp(token_ids), _dp(segment_ids), B, S, emb.hidden, _dp(out),
+                               int(bool(out_i8)), _f(s_out), _stream()))
+    return out
+
+
 class Encoder:
     """samp_encoder_create / forward / calibrate / destroy."""
 
@@ -139,6 +172,18 @@ class Encoder:
             assert mask.dtype == torch.int32 and tuple(mask.shape) == (B, S)
         _check(lib().samp_encoder_forward(self._h, _dp(hidden), _dp(mask), B, S, _dp(out), _dp(ws),
                                           C.c_size_t(ws.numel()), _stream()))
+        return out
+
+    def forward_ids(self, emb: "Embedding", token_ids: torch.Tensor, segment_ids: Optional[torch.Tensor] = None,
+                    mask: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """samp_encoder_forward_ids: the Embedding kernel feeds layer 0 directly."""
+        assert token_ids.dtype == torch.int32 and token_ids.dim() == 2
+        B, S = token_ids.shape
+        ws = self._workspace(B, S)
+        if out is None:
+            out = torch.empty((B, S, emb.hidden), dtype=torch.float16, device=token_ids.device)
+        _check(lib().samp_encoder_forward_ids(self._h, C.byref(emb.struct), _dp(token_ids), _dp(segment_ids), _dp(mask),
+                                              B, S, _dp(out), _dp(ws), C.c_size_t(ws.numel()), _stream()))
         return out
 
     def calibrate(self, hidden: torch.Tensor, mask: Optional[torch.Tensor] = None) -> np.ndarray:

@@ -104,7 +104,7 @@ struct samp_encoder {
     bool streams_ready = false;
     // whole-forward HIP graphs, one per distinct argument set (the forward is launch-bound: a few
     // hundred kernels of 5..30 microseconds); captured on an internal stream, replayed on the caller's
-    struct Graph { const void *hidden, *mask, *out, *ws; int B, S, G; int seen; hipGraphExec_t exec; };
+    struct Graph { const void *hidden, *mask, *out, *ws; int B, S, G; int seen; hipGraphExec_t exec; const void *seg; samp_embedding_t emb; };
     std::vector<Graph> graphs;
     bool graphs_enabled = true;
     hipStream_t cap = nullptr;
@@ -159,21 +159,23 @@ Workspace carve(const samp_config_t &c, int B, int S, void *base)
     return w;
 }
 
+// input of a forward that starts from ids: the Embedding kernel produces layer 0's input
+struct Ids { samp_embedding_t emb; const int32_t *token_ids, *segment_ids; };
+
 int check_forward_args(const samp_encoder_t *enc, const void *hidden, int B, int S, const void *workspace, size_t ws_bytes)
 {
-    if (!enc || !hidden || !workspace) return fail(SAMP_ERR_ARG, "encoder, hidden or workspace is NULL");
+    if (!enc || !hidden || !workspace) return fail(SAMP_ERR_ARG, "encoder, input or workspace is NULL");
     if (B < 1 || S < 1) return fail(SAMP_ERR_SHAPE, "B and S must be >= 1");
     if (B > enc->cfg.max_batch || S > enc->cfg.max_seq)
         return fail(SAMP_ERR_SHAPE, "B=%d S=%d exceed max_batch=%d max_seq=%d", B, S, enc->cfg.max_batch, enc->cfg.max_seq);
     if (!aligned(workspace, ALIGN)) return fail(SAMP_ERR_SPACE, "workspace must be 256-byte aligned");
     const size_t need = samp_encoder_workspace_bytes(enc, B, S);
     if (ws_bytes < need) return fail(SAMP_ERR_SPACE, "workspace has %zu bytes, %zu needed", ws_bytes, need);
-    if (!aligned(hidden, 16)) return fail(SAMP_ERR_ARG, "hidden must be 16-byte aligned");
     return SAMP_OK;
 }
 
 // The kernel sequence.  calib: FP16-only run that also records each tensor's absmax.
-int run(samp_encoder_t *enc, const void *hidden, const int32_t *mask, int B, int S, void *out, void *workspace,
+int run(samp_encoder_t *enc, const void *hidden, const Ids *ids, const int32_t *mask, int B, int S, void *out, void *workspace,
         hipStream_t st, bool calib)
 {
     const samp_config_t &c = enc->cfg;
@@ -189,7 +191,19 @@ int run(samp_encoder_t *enc, const void *hidden, const int32_t *mask, int B, int
     if (calib) HIP_TRY(launch_fill_f32(w.absmax, Lc * 10, 0.0f, st));
 
     // entry: padding removal and, if layer 0's attention block is INT8, quantisation by its producer
-    if (packed) {
+    if (ids) {                                      // the Embedding kernel is layer 0's producer
+        if (packed) {
+            HIP_TRY(launch_seq_offsets(mask, B, S, w.cu, st));
+            cu = w.cu; row_map = w.row_map; rows.dev_rows = w.cu + B;
+        }
+        const samp_embedding_t &e = ids->emb;
+        EmbedArgs ea{ids->token_ids, ids->segment_ids, (const __half *)e.token_table, (const __half *)e.segment_table,
+                     (const __half *)e.position_table, e.vocab, e.segments, e.positions, e.gamma, e.beta, e.ln_eps,
+                     packed ? w.cu : nullptr, B, S, H, w.x, first8, first8 ? enc->L[0].s.x : 1.0f,
+                     packed ? w.row_map : nullptr, packed ? (__half *)out : nullptr};
+        HIP_TRY(launch_embed_ln(ea, st, timing(enc, SAMP_PROF_ENTRY)));
+        x = w.x;
+    } else if (packed) {
         HIP_TRY(launch_seq_offsets(mask, B, S, w.cu, st));
         HIP_TRY(launch_pack_rows((const __half *)hidden, w.cu, B, S, H, first8 ? enc->L[0].s.x : 0.0f, w.x, w.row_map,
                                  (__half *)out, st, timing(enc, SAMP_PROF_ENTRY)));
@@ -404,11 +418,11 @@ int samp_encoder_set_groups(samp_encoder_t *enc, int32_t groups)
     return SAMP_OK;
 }
 
-static int forward_eager(samp_encoder_t *enc, const void *hidden, const int32_t *mask, int32_t B, int32_t S, void *out,
-                         void *workspace, hipStream_t st)
+static int forward_eager(samp_encoder_t *enc, const void *hidden, const Ids *ids, const int32_t *mask, int32_t B, int32_t S,
+                         void *out, void *workspace, hipStream_t st)
 {
     const int G = choose_groups(enc, B, S);
-    if (G == 1) return run(enc, hidden, mask, B, S, out, workspace, st, false);
+    if (G == 1) return run(enc, hidden, ids, mask, B, S, out, workspace, st, false);
     if (!enc->streams_ready) {
         for (int i = 0; i < MAX_GROUPS - 1; i++) {
             HIP_TRY(hipStreamCreateWithFlags(&enc->side[i], hipStreamNonBlocking));
@@ -430,7 +444,10 @@ static int forward_eager(samp_encoder_t *enc, const void *hidden, const int32_t 
         if (nb <= 0) break;
         hipStream_t gs = (g == 0 || serial) ? st : enc->side[g - 1];
         if (g > 0 && !serial) HIP_TRY(hipStreamWaitEvent(gs, enc->fork, 0));
-        const int rc = run(enc, (const __half *)hidden + b0 * seq_elems, mask ? mask + (size_t)b0 * S : nullptr, nb, S,
+        Ids part;
+        if (ids) part = Ids{ids->emb, ids->token_ids + (size_t)b0 * S, ids->segment_ids ? ids->segment_ids + (size_t)b0 * S : nullptr};
+        const int rc = run(enc, ids ? nullptr : (const __half *)hidden + b0 * seq_elems, ids ? &part : nullptr,
+                           mask ? mask + (size_t)b0 * S : nullptr, nb, S,
                            (__half *)out + b0 * seq_elems, (char *)workspace + g * piece, gs, false);
         if (rc != SAMP_OK) return rc;
         if (g > 0 && !serial) {
@@ -441,28 +458,86 @@ static int forward_eager(samp_encoder_t *enc, const void *hidden, const int32_t 
     return SAMP_OK;
 }
 
+// forward from a hidden state (ids == nullptr) or from ids (hidden == nullptr), with the graph cache
+static int forward_common(samp_encoder_t *enc, const void *hidden, const Ids *ids, const int32_t *mask, int32_t B, int32_t S,
+                          void *out, void *workspace, hipStream_t st);
+
 int samp_encoder_forward(samp_encoder_t *enc, const void *hidden, const int32_t *mask, int32_t B, int32_t S, void *out,
                          void *workspace, size_t workspace_bytes, void *stream)
 {
     if (int rc = check_forward_args(enc, hidden, B, S, workspace, workspace_bytes)) return rc;
+    if (!aligned(hidden, 16)) return fail(SAMP_ERR_ARG, "hidden must be 16-byte aligned");
     if (!out) return fail(SAMP_ERR_ARG, "out is NULL");
     if (out == hidden) return fail(SAMP_ERR_ARG, "out must not alias hidden");
     if (!aligned(out, 16)) return fail(SAMP_ERR_ARG, "out must be 16-byte aligned");
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    if (!enc->graphs_enabled || enc->prof_which != SAMP_PROF_OFF) return forward_eager(enc, hidden, mask, B, S, out, workspace, st);
+    return forward_common(enc, hidden, nullptr, mask, B, S, out, workspace, static_cast<hipStream_t>(stream));
+}
+
+static int check_embedding(const samp_embedding_t *e, int H, int S)
+{
+    if (!e) return fail(SAMP_ERR_ARG, "embedding is NULL");
+    if (!e->token_table || !e->segment_table || !e->position_table || !e->gamma || !e->beta)
+        return fail(SAMP_ERR_ARG, "an embedding table or LayerNorm vector is NULL");
+    if (!aligned(e->token_table, 16) || !aligned(e->segment_table, 16) || !aligned(e->position_table, 16) ||
+        !aligned(e->gamma, 16) || !aligned(e->beta, 16))
+        return fail(SAMP_ERR_ARG, "embedding tables and LayerNorm vectors must be 16-byte aligned");
+    if (e->vocab < 1 || e->segments < 1) return fail(SAMP_ERR_SHAPE, "vocab and segments must be >= 1");
+    if (e->positions < S) return fail(SAMP_ERR_SHAPE, "position table has %d rows, S=%d needed", e->positions, S);
+    if (!(e->ln_eps >= 0.0f) || !std::isfinite(e->ln_eps)) return fail(SAMP_ERR_ARG, "ln_eps must be finite and >= 0");
+    if (H < 16 || H % 16 || H > 2048) return fail(SAMP_ERR_SHAPE, "H %% 16 == 0 and H <= 2048 required");
+    return SAMP_OK;
+}
+
+int samp_encoder_forward_ids(samp_encoder_t *enc, const samp_embedding_t *emb, const int32_t *token_ids,
+                             const int32_t *segment_ids, const int32_t *mask, int32_t B, int32_t S, void *out,
+                             void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (int rc = check_forward_args(enc, token_ids, B, S, workspace, workspace_bytes)) return rc;
+    if (int rc = check_embedding(emb, enc->cfg.hidden, S)) return rc;
+    if (!out) return fail(SAMP_ERR_ARG, "out is NULL");
+    if (!aligned(out, 16)) return fail(SAMP_ERR_ARG, "out must be 16-byte aligned");
+    const Ids ids{*emb, token_ids, segment_ids};
+    return forward_common(enc, nullptr, &ids, mask, B, S, out, workspace, static_cast<hipStream_t>(stream));
+}
+
+int samp_embed_ln(const samp_embedding_t *emb, const int32_t *token_ids, const int32_t *segment_ids, int32_t B, int32_t S,
+                  int32_t H, void *out, int32_t out_i8, float s_out, void *stream)
+{
+    if (!token_ids || !out) return fail(SAMP_ERR_ARG, "NULL pointer");
+    if (B < 1 || S < 1) return fail(SAMP_ERR_SHAPE, "B and S must be >= 1");
+    if (int rc = check_embedding(emb, H, S)) return rc;
+    if (out_i8 && !good_scale(s_out)) return fail(SAMP_ERR_SCALE, "the output step is not finite and positive");
+    if (!aligned(out, 16)) return fail(SAMP_ERR_ARG, "out must be 16-byte aligned");
+    EmbedArgs ea{token_ids, segment_ids, (const __half *)emb->token_table, (const __half *)emb->segment_table,
+                 (const __half *)emb->position_table, emb->vocab, emb->segments, emb->positions, emb->gamma, emb->beta,
+                 emb->ln_eps, nullptr, B, S, H, out, out_i8 != 0, out_i8 ? s_out : 1.0f, nullptr, nullptr};
+    HIP_TRY(launch_embed_ln(ea, (hipStream_t)stream, nullptr));
+    return SAMP_OK;
+}
+
+static int forward_common(samp_encoder_t *enc, const void *hidden, const Ids *ids, const int32_t *mask, int32_t B, int32_t S,
+                          void *out, void *workspace, hipStream_t st)
+{
+    const void *key = ids ? (const void *)ids->token_ids : hidden;
+    const void *key_seg = ids ? (const void *)ids->segment_ids : nullptr;
+    samp_embedding_t key_emb;
+    std::memset(&key_emb, 0, sizeof(key_emb));
+    if (ids) key_emb = ids->emb;
+    if (!enc->graphs_enabled || enc->prof_which != SAMP_PROF_OFF) return forward_eager(enc, hidden, ids, mask, B, S, out, workspace, st);
 
     const int G = choose_groups(enc, B, S);
     samp_encoder::Graph *g = nullptr;
     for (auto &e : enc->graphs)
-        if (e.hidden == hidden && e.mask == mask && e.out == out && e.ws == workspace && e.B == B && e.S == S && e.G == G) g = &e;
+        if (e.hidden == key && e.seg == key_seg && std::memcmp(&e.emb, &key_emb, sizeof(key_emb)) == 0 && e.mask == mask && e.out == out && e.ws == workspace &&
+            e.B == B && e.S == S && e.G == G) g = &e;
     if (g && g->exec) { HIP_TRY(hipGraphLaunch(g->exec, st)); return SAMP_OK; }
     if (!g) {                                       // first sight of these arguments: run eagerly (one-off set-up happens here)
         if (enc->graphs.size() >= 8) {
             if (enc->graphs.front().exec) (void)hipGraphExecDestroy(enc->graphs.front().exec);
             enc->graphs.erase(enc->graphs.begin());
         }
-        enc->graphs.push_back({hidden, mask, out, workspace, B, S, G, 1, nullptr});
-        return forward_eager(enc, hidden, mask, B, S, out, workspace, st);
+        enc->graphs.push_back({key, mask, out, workspace, B, S, G, 1, nullptr, key_seg, key_emb});
+        return forward_eager(enc, hidden, ids, mask, B, S, out, workspace, st);
     }
     // second sight: record the same launches into a graph on an internal stream, then replay it
     if (!enc->cap) HIP_TRY(hipStreamCreateWithFlags(&enc->cap, hipStreamNonBlocking));
@@ -470,7 +545,7 @@ int samp_encoder_forward(samp_encoder_t *enc, const void *hidden, const int32_t 
     hipError_t e = hipStreamBeginCapture(enc->cap, hipStreamCaptureModeRelaxed);
     int rc = SAMP_OK;
     if (e == hipSuccess) {
-        rc = forward_eager(enc, hidden, mask, B, S, out, workspace, enc->cap);
+        rc = forward_eager(enc, hidden, ids, mask, B, S, out, workspace, enc->cap);
         e = hipStreamEndCapture(enc->cap, &graph);
     }
     if (e == hipSuccess && rc == SAMP_OK) e = hipGraphInstantiate(&g->exec, graph, nullptr, nullptr, 0);
@@ -479,7 +554,7 @@ int samp_encoder_forward(samp_encoder_t *enc, const void *hidden, const int32_t 
         (void)hipGetLastError();
         g->exec = nullptr;
         enc->graphs_enabled = false;
-        return forward_eager(enc, hidden, mask, B, S, out, workspace, st);
+        return forward_eager(enc, hidden, ids, mask, B, S, out, workspace, st);
     }
     HIP_TRY(hipGraphLaunch(g->exec, st));
     return SAMP_OK;
@@ -499,7 +574,7 @@ int samp_encoder_calibrate(samp_encoder_t *enc, const void *hidden, const int32_
     if (!scales_out) return fail(SAMP_ERR_ARG, "scales_out is NULL");
     if (!enc->all_fp16) return fail(SAMP_ERR_ARG, "calibration needs an encoder whose layers are all SAMP_FP16");
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (int rc = run(enc, hidden, mask, B, S, nullptr, workspace, st, true)) return rc;
+    if (int rc = run(enc, hidden, nullptr, mask, B, S, nullptr, workspace, st, true)) return rc;
     const int n = enc->cfg.layers * 10;
     std::vector<float> am(n);
     Workspace w = carve(enc->cfg, B, S, workspace);

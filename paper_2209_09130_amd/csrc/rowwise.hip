@@ -59,6 +59,67 @@ template <bool I8> __device__ __forceinline__ void load16(const void *p, size_t 
     }
 }
 
+// Second half of a LayerNorm row held by 16 lanes (z: this lane's channels, sum: its partial sum):
+// binary64 mean and variance, binary32 normalisation, output as int8 codes or fp16 at element
+// offset obase, optional running absmax of the fp16 output.
+template <int NJ, bool OUT_I8>
+__device__ __forceinline__ void ln_finish(const float (&z)[NJ][16], double sum, int H, int sub, const float *gamma,
+                                          const float *beta, float eps, float s_out, void *out, size_t obase, float *absmax_out)
+{
+    const double mu = row16_sum(sum) / (double)H;
+    double sq = 0.0;
+#pragma unroll
+    for (int j = 0; j < NJ; j++) {
+        if (j * 256 + sub * 16 < H) {
+#pragma unroll
+            for (int e = 0; e < 16; e++) { const double d = (double)z[j][e] - mu; sq += d * d; }
+        }
+    }
+    const double var = row16_sum(sq) / (double)H;
+    const float mu32 = (float)mu;
+    const float rstd32 = (float)(1.0 / sqrt(var + (double)eps));
+    const float inv_s = OUT_I8 ? 1.0f / s_out : 0.0f;
+    float amax = 0.0f;
+#pragma unroll
+    for (int j = 0; j < NJ; j++) {
+        const int c = j * 256 + sub * 16;
+        if (c < H) {
+            float y[16];
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                const v4f gg = *reinterpret_cast<const v4f *>(gamma + c + 4 * q);
+                const v4f be = *reinterpret_cast<const v4f *>(beta + c + 4 * q);
+#pragma unroll
+                for (int t = 0; t < 4; t++)
+                    y[4 * q + t] = __builtin_fmaf((z[j][4 * q + t] - mu32) * rstd32, gg[t], be[t]);
+            }
+            if (OUT_I8) {
+                v4i o;
+#pragma unroll
+                for (int q = 0; q < 4; q++)
+                    o[q] = pack_codes(code_bits(y[4 * q] * inv_s), code_bits(y[4 * q + 1] * inv_s), code_bits(y[4 * q + 2] * inv_s),
+                                      code_bits(y[4 * q + 3] * inv_s));
+                *reinterpret_cast<v4i *>((int8_t *)out + obase + c) = o;
+            } else {
+                v8h h0, h1;
+#pragma unroll
+                for (int e = 0; e < 8; e++) { h0[e] = to_half(y[e]); h1[e] = to_half(y[8 + e]); }
+                *reinterpret_cast<v8h *>((__half *)out + obase + c) = h0;
+                *reinterpret_cast<v8h *>((__half *)out + obase + c + 8) = h1;
+                if (absmax_out) {
+#pragma unroll
+                    for (int e = 0; e < 8; e++)
+                        amax = __builtin_fmaxf(amax, __builtin_fmaxf(__builtin_fabsf((float)h0[e]), __builtin_fabsf((float)h1[e])));
+                }
+            }
+        }
+    }
+    if (!OUT_I8 && absmax_out) {
+        amax = row16_max(amax);
+        if (sub == 0) atomicMax(reinterpret_cast<int *>(absmax_out), __float_as_int(amax));   // values >= 0
+    }
+}
+
 template <int NJ, bool IN_I8, bool RES_I8, bool OUT_I8>
 __global__ __launch_bounds__(256) void add_ln_kernel(AddLnArgs a)
 {
@@ -93,58 +154,8 @@ __global__ __launch_bounds__(256) void add_ln_kernel(AddLnArgs a)
             for (int e = 0; e < 16; e++) z[j][e] = 0.0f;
         }
     }
-    const double mu = row16_sum(sum) / (double)H;
-    double sq = 0.0;
-#pragma unroll
-    for (int j = 0; j < NJ; j++) {
-        if (j * 256 + sub * 16 < H) {
-#pragma unroll
-            for (int e = 0; e < 16; e++) { const double d = (double)z[j][e] - mu; sq += d * d; }
-        }
-    }
-    const double var = row16_sum(sq) / (double)H;
-    const float mu32 = (float)mu;
-    const float rstd32 = (float)(1.0 / sqrt(var + (double)a.eps));
-    const float inv_s = OUT_I8 ? 1.0f / a.s_out : 0.0f;
-    const size_t obase = (size_t)(a.row_map ? a.row_map[row] : row) * H;
-    float amax = 0.0f;
-#pragma unroll
-    for (int j = 0; j < NJ; j++) {
-        const int c = j * 256 + sub * 16;
-        if (c < H) {
-            float y[16];
-#pragma unroll
-            for (int q = 0; q < 4; q++) {
-                const v4f gg = *reinterpret_cast<const v4f *>(a.gamma + c + 4 * q);
-                const v4f be = *reinterpret_cast<const v4f *>(a.beta + c + 4 * q);
-#pragma unroll
-                for (int t = 0; t < 4; t++)
-                    y[4 * q + t] = __builtin_fmaf((z[j][4 * q + t] - mu32) * rstd32, gg[t], be[t]);
-            }
-            if (OUT_I8) {
-                v4i o;
-#pragma unroll
-                for (int q = 0; q < 4; q++)
-                    o[q] = pack4(qcode(y[4 * q] * inv_s), qcode(y[4 * q + 1] * inv_s), qcode(y[4 * q + 2] * inv_s), qcode(y[4 * q + 3] * inv_s));
-                *reinterpret_cast<v4i *>((int8_t *)a.out + obase + c) = o;
-            } else {
-                v8h h0, h1;
-#pragma unroll
-                for (int e = 0; e < 8; e++) { h0[e] = to_half(y[e]); h1[e] = to_half(y[8 + e]); }
-                *reinterpret_cast<v8h *>((__half *)a.out + obase + c) = h0;
-                *reinterpret_cast<v8h *>((__half *)a.out + obase + c + 8) = h1;
-                if (a.absmax_out) {
-#pragma unroll
-                    for (int e = 0; e < 8; e++)
-                        amax = __builtin_fmaxf(amax, __builtin_fmaxf(__builtin_fabsf((float)h0[e]), __builtin_fabsf((float)h1[e])));
-                }
-            }
-        }
-    }
-    if (!OUT_I8 && a.absmax_out) {
-        amax = row16_max(amax);
-        if (sub == 0) atomicMax(reinterpret_cast<int *>(a.absmax_out), __float_as_int(amax));   // values >= 0
-    }
+    ln_finish<NJ, OUT_I8>(z, sum, H, sub, a.gamma, a.beta, a.eps, a.s_out, a.out,
+                          (size_t)(a.row_map ? a.row_map[row] : row) * H, a.absmax_out);
 }
 
 template <int NJ>
@@ -161,6 +172,68 @@ hipError_t launch_add_ln_nj(const AddLnArgs &a, hipStream_t st, const Timing *tm
     SAMP_LN_CASE(false, true, true) SAMP_LN_CASE(false, true, false)
 #undef SAMP_LN_CASE
     return hipErrorInvalidValue;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Embedding kernel (Section 3.1: the token, segment and position embeddings are summed in one kernel;
+// Section 3.2: a quantised first block receives INT8 from it directly).  BERT's embedding ends with
+// a LayerNorm, done here too.  16 lanes per (b, s) position; valid positions write packed row
+// cu[b] + s (and remember where they came from), padded ones zero their row of the final output.
+//   z = (tok[id] + seg[sid]) + pos[s]  in binary32;  out = LayerNorm(z) as fp16 or rne(y / s_out).
+// Ids outside their table are clamped into it, so no id can make the kernel read out of bounds.
+// ---------------------------------------------------------------------------------------------
+template <int NJ, bool OUT_I8>
+__global__ __launch_bounds__(256) void embed_ln_kernel(EmbedArgs a)
+{
+    const int rowid = blockIdx.x * 16 + (threadIdx.x >> 4);
+    if (rowid >= a.B * a.S) return;
+    const int sub = threadIdx.x & 15, H = a.H;
+    const int b = rowid / a.S, s = rowid - b * a.S;
+    int t = rowid;
+    if (a.cu) {
+        const int t0 = a.cu[b], n = a.cu[b + 1] - t0;
+        if (s >= n) {
+            if (a.out_zero_pad)
+                for (int c = sub * 8; c < H; c += 128) *reinterpret_cast<v4i *>(a.out_zero_pad + (size_t)rowid * H + c) = v4i{0, 0, 0, 0};
+            return;
+        }
+        t = t0 + s;
+        if (sub == 0 && a.row_map) a.row_map[t] = rowid;
+    }
+    const int id = min(max(a.token_ids[rowid], 0), a.vocab - 1);
+    const int sid = a.segment_ids ? min(max(a.segment_ids[rowid], 0), a.segments - 1) : 0;
+    const int pid = min(s, a.positions - 1);
+    float z[NJ][16];
+    double sum = 0.0;
+#pragma unroll
+    for (int j = 0; j < NJ; j++) {
+        const int c = j * 256 + sub * 16;
+        if (c < H) {
+            float x[16], g[16], p[16];
+            load16<false>(a.tok, (size_t)id * H + c, x);
+            load16<false>(a.seg, (size_t)sid * H + c, g);
+            load16<false>(a.pos, (size_t)pid * H + c, p);
+#pragma unroll
+            for (int e = 0; e < 16; e++) {
+                const float u = x[e] + g[e];
+                z[j][e] = u + p[e];
+                sum += (double)z[j][e];
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 16; e++) z[j][e] = 0.0f;
+        }
+    }
+    ln_finish<NJ, OUT_I8>(z, sum, H, sub, a.gamma, a.beta, a.eps, a.s_out, a.out, (size_t)t * H, nullptr);
+}
+
+template <int NJ>
+hipError_t launch_embed_ln_nj(const EmbedArgs &a, hipStream_t st, const Timing *tm)
+{
+    dim3 grid((a.B * a.S + 15) / 16), block(256);
+    if (a.out_i8) launch_kernel(embed_ln_kernel<NJ, true>, grid, block, 0, st, tm, a);
+    else launch_kernel(embed_ln_kernel<NJ, false>, grid, block, 0, st, tm, a);
+    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -351,6 +424,21 @@ hipError_t launch_fold(const float *, float s_in, const float *s_w, const float 
 {
     hipLaunchKernelGGL(fold_kernel, dim3((N + 255) / 256), dim3(256), 0, st, s_in, s_w, bias, s_out, N, m, b);
     return hipGetLastError();
+}
+
+hipError_t launch_embed_ln(const EmbedArgs &a, hipStream_t st, const Timing *tm)
+{
+    switch ((a.H + 255) / 256) {
+    case 1: return launch_embed_ln_nj<1>(a, st, tm);
+    case 2: return launch_embed_ln_nj<2>(a, st, tm);
+    case 3: return launch_embed_ln_nj<3>(a, st, tm);
+    case 4: return launch_embed_ln_nj<4>(a, st, tm);
+    case 5: return launch_embed_ln_nj<5>(a, st, tm);
+    case 6: return launch_embed_ln_nj<6>(a, st, tm);
+    case 7: return launch_embed_ln_nj<7>(a, st, tm);
+    case 8: return launch_embed_ln_nj<8>(a, st, tm);
+    }
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_seq_offsets(const int *mask, int B, int S, int *cu, hipStream_t st)

@@ -173,6 +173,18 @@ struct AddLnArgs {
 };
 hipError_t launch_add_ln(const AddLnArgs &a, hipStream_t st, const Timing *tm);
 
+struct EmbedArgs {
+    const int *token_ids, *segment_ids;                    // [B*S]; segment_ids may be null (segment 0)
+    const __half *tok, *seg, *pos; int vocab, segments, positions;
+    const float *gamma, *beta; float eps;
+    const int *cu;                                         // null: every sequence has S rows and row b*S+s is written
+    int B, S, H;
+    void *out; bool out_i8; float s_out;
+    int *row_map;                                          // with cu: output row of packed row t
+    __half *out_zero_pad;                                  // with cu: [B*S, H] whose padded rows are zeroed
+};
+hipError_t launch_embed_ln(const EmbedArgs &a, hipStream_t st, const Timing *tm);
+
 hipError_t launch_quantize_weight(const __half *W, int N, int K, int8_t *Wq, float *s_w, hipStream_t st);
 hipError_t launch_fold(const float *s_in_dev_or_null, float s_in, const float *s_w, const float *bias, float s_out, int N,
                        float *m, float *b, hipStream_t st);

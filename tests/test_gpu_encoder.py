@@ -240,6 +240,41 @@ def test_c2_fully_quant_with_unsigned_softmax_codes(P):
     assert dist["unsigned"] <= 1.02 * dist["symmetric"]
 
 
+@pytest.mark.parametrize("varlen", [False, True])
+@pytest.mark.parametrize("modes", [(FULL_INT8,) * 3, (FP16, FULL_INT8, FP16)])
+def test_encoder_from_ids_through_the_embedding_kernel(P, modes, varlen):
+    """samp_encoder_forward_ids: the Embedding kernel writes layer 0's input (int8 for an INT8 first block, fp16
+    otherwise) into the packed workspace; eager, graph replays and both batch-group settings agree with the oracle."""
+    import torch
+    w = small(modes, batch=6, seq=40, varlen=varlen)
+    wts = W.make_weights(w)
+    _, lens, mask = W.make_hidden(w)
+    emb = W.make_embedding(w, vocab=500)
+    ids, seg = W.make_ids(w, vocab=500)
+    hid = np.zeros((w.batch, w.seq, w.hidden), np.float16)
+    for b in range(w.batch):
+        hid[b, :lens[b]] = oracle.embed_ln(emb, ids[b, :lens[b]], seg[b, :lens[b]], False)
+    sc = oracle.calibrate(*args(w), wts, hid[:4])
+    want = oracle.Encoder(*args(w), w.modes, wts, sc).forward_ids(emb, ids, seg, lens)
+    E = P.Embedding(emb["tok"], emb["seg"], emb["pos"], emb["gamma"], emb["beta"], emb["eps"])
+    enc = P.Encoder(*args(w), w.modes, wts, sc, max_batch=w.batch, max_seq=w.seq)
+    t_ids, t_seg = torch.from_numpy(ids).cuda(), torch.from_numpy(seg).cuda()
+    t_mask = torch.from_numpy(mask).cuda() if varlen else None
+    outs = []
+    for groups in (1, 2):
+        enc.set_groups(groups)
+        for _ in range(3):                                   # eager, capture, replay
+            res = torch.full((w.batch, w.seq, w.hidden), 7.0, dtype=torch.float16, device="cuda")
+            outs.append(enc.forward_ids(E, t_ids, t_seg, t_mask, res).cpu().numpy())
+            torch.cuda.synchronize()
+    enc.close()
+    for o in outs[1:]:
+        assert np.array_equal(o, outs[0])
+    d = compare(outs[0], want, lens, modes[0] == FULL_INT8, f"from ids {modes} varlen={varlen}")
+    if all(m == FULL_INT8 for m in modes):
+        assert (d == 0).all()
+
+
 @pytest.mark.parametrize("mode", [FFN_INT8, MHA_INT8])
 def test_c2_mixed_precision_modes_layer_by_layer_and_end_to_end(P, mode):
     w = W.config("C2").with_modes(mode)

@@ -318,3 +318,26 @@ def test_padding_removal_packs_valid_rows(P, quant):
     want = oracle.quantize_f16(rows, s_x) if quant else rows
     assert np.array_equal(packed[:T], want)
     assert np.array_equal(row_map[:T], np.concatenate([b * S + np.arange(lens[b]) for b in range(B)]))
+
+
+# ------------------------------------------------------------------ embedding kernel
+@pytest.mark.parametrize("H", [128, 768, 1024])
+def test_embedding_kernel_bit_exact(P, H):
+    rng = np.random.default_rng(H + 50)
+    V, B, S = 97, 3, 21
+    emb = {"tok": (rng.standard_normal((V, H)) * 0.5).astype(np.float16), "seg": (rng.standard_normal((2, H)) * 0.5).astype(np.float16),
+           "pos": (rng.standard_normal((S + 3, H)) * 0.5).astype(np.float16),
+           "gamma": (1 + 0.2 * rng.standard_normal(H)).astype(np.float32), "beta": (0.3 * rng.standard_normal(H)).astype(np.float32),
+           "eps": 1e-12}
+    ids = rng.integers(-3, V + 3, (B, S)).astype(np.int32)          # a few ids outside the table: clamped on both sides
+    seg = rng.integers(0, 2, (B, S)).astype(np.int32)
+    E = P.Embedding(emb["tok"], emb["seg"], emb["pos"], emb["gamma"], emb["beta"], emb["eps"])
+    for out_i8, s_out in ((False, 1.0), (True, 0.031)):
+        want = np.concatenate([oracle.embed_ln(emb, ids[b], seg[b], out_i8, s_out) for b in range(B)])
+        got = host(P.embed_ln(E, dev(ids), dev(seg), out_i8, s_out))
+        assert np.array_equal(got, want)
+    want = np.concatenate([oracle.embed_ln(emb, ids[b], None, False) for b in range(B)])
+    assert np.array_equal(host(P.embed_ln(E, dev(ids), None, False)), want)
+    short = P.Embedding(emb["tok"], emb["seg"], emb["pos"][:S - 1], emb["gamma"], emb["beta"], emb["eps"])
+    with pytest.raises(P.SampError):
+        P.embed_ln(short, dev(ids), None, False)                    # position table shorter than the sequences
