@@ -380,3 +380,13 @@ def calibrate(layers, hidden_size, heads, ffn, ln_eps, weights, calib_hidden, nt
     sc = np.empty_like(am)
     lib().orc_scales_from_absmax(_p(am), am.size, _p(sc))
     return sc
+
+
+# ---------------------------------------------------------------- downstream target
+def classify(hidden: np.ndarray, w_pool: np.ndarray, b_pool: np.ndarray, w_cls: np.ndarray, b_cls: np.ndarray) -> np.ndarray:
+    """Classification target on the first token (Section 3.1, "Downstream Target"; the paper's tasks are BERT text
+    classification): pooled = tanh(W_p h[:, 0] + b_p), logits = W_c pooled + b_c, all in binary64.
+    hidden fp16 [B,S,H]; w_pool fp16 [H,H], w_cls fp16 [C,H] (rows = outputs); biases fp32.  Returns float64 [B,C]."""
+    h = np.asarray(hidden[:, 0, :], np.float64)
+    pooled = np.tanh(h @ np.asarray(w_pool, np.float64).T + np.asarray(b_pool, np.float64))
+    return pooled @ np.asarray(w_cls, np.float64).T + np.asarray(b_cls, np.float64)

@@ -517,3 +517,29 @@ def test_encoder_with_embedding_entry_equals_embedding_then_encoder_for_fp16_ent
     assert (x0 != taps["x"]).mean() < 0.02 and np.abs(x0.astype(int) - taps["x"].astype(int)).max() <= 1
     assert not out_ids[0, lens[0]:].any()
     enc8.close()
+
+
+# ------------------------------------------------------------------ classification target
+def test_classification_target_against_torch_linear_layers_and_closed_forms():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(51)
+    B, S, H, Cn = 4, 6, 128, 5
+    hid = rng.standard_normal((B, S, H)).astype(np.float16)
+    wp = (rng.standard_normal((H, H)) * 0.1).astype(np.float16)
+    bp = (rng.standard_normal(H) * 0.1).astype(np.float32)
+    wc = (rng.standard_normal((Cn, H)) * 0.1).astype(np.float16)
+    bc = (rng.standard_normal(Cn) * 0.1).astype(np.float32)
+    got = oracle.classify(hid, wp, bp, wc, bc)
+    t = lambda a: torch.from_numpy(np.asarray(a, np.float64))
+    pooled = torch.tanh(torch.nn.functional.linear(t(hid[:, 0]), t(wp), t(bp)))
+    want = torch.nn.functional.linear(pooled, t(wc), t(bc)).numpy()
+    assert np.abs(got - want).max() < 1e-12
+    # only the first token matters
+    other = hid.copy(); other[:, 1:] = 0
+    assert np.array_equal(oracle.classify(other, wp, bp, wc, bc), got)
+    # zero pooler weights: pooled = tanh(b_p), logits = W_c tanh(b_p) + b_c for every sequence
+    z = oracle.classify(hid, np.zeros_like(wp), bp, wc, bc)
+    assert np.allclose(z, np.tanh(bp.astype(np.float64)) @ wc.astype(np.float64).T + bc, atol=1e-14)
+    # a large pre-activation saturates tanh: identity-like pooler with a big bias gives logits = sum of W_c rows + b_c
+    sat = oracle.classify(hid, np.zeros_like(wp), np.full(H, 50.0, np.float32), wc, bc)
+    assert np.allclose(sat, wc.astype(np.float64).sum(axis=1) + bc, atol=1e-12)
