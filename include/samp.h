@@ -194,6 +194,15 @@ SAMP_API int samp_allocate_decay_aware(const double *accuracy, const double *lat
 SAMP_API int samp_recommend(const double *accuracy, const double *latency, int32_t n, double max_latency,
                             double min_accuracy, int32_t *settings_out, int32_t capacity, int32_t *count_out);
 
+/* Downstream target (Section 3.1, "Downstream Target"): text classification on the first token of
+ * every sequence of the encoder output.  logits[b, c] = W_c . tanh(W_p . hidden[b, 0, :] + b_p) + b_c
+ * with binary32 accumulation.  hidden dev fp16 [B,S,H]; w_pool dev fp16 [H,H], w_cls dev fp16
+ * [classes,H] (row = output channel, 16-byte aligned); b_pool, b_cls dev float; logits dev float
+ * [B, classes].  H % 8 == 0, H <= 4096.                                                           */
+SAMP_API int samp_classify(const uint16_t *hidden, int32_t B, int32_t S, int32_t H, const uint16_t *w_pool,
+                           const float *b_pool, const uint16_t *w_cls, const float *b_cls, int32_t classes,
+                           float *logits, void *stream);
+
 /* Code-usage statistic of any int8 tensor (Appendix B compares the softmax codes with the codes of
  * the attention output): ADDS to hist[256] (dev uint64, zeroed by the caller; index = the code as
  * an unsigned byte) the number of occurrences of each code among codes[0..n).                     */

@@ -265,6 +265,15 @@ def attention_i8(qkv, cu, max_len: int, heads: int, s_q, s_k, s_v, s_p, s_ctx, p
     return (ctx, hist) if want_hist else ctx
 
 
+def classify(hidden: torch.Tensor, w_pool, b_pool, w_cls, b_cls) -> torch.Tensor:
+    """samp_classify: float32 logits [B, classes] from the first token of each sequence."""
+    B, S, H = hidden.shape
+    Cn = w_cls.shape[0]
+    logits = torch.zeros((B, Cn), dtype=torch.float32, device=hidden.device)
+    _check(lib().samp_classify(_dp(hidden), B, S, H, _dp(w_pool), _dp(b_pool), _dp(w_cls), _dp(b_cls), Cn, _dp(logits), _stream()))
+    return logits
+
+
 def code_histogram(codes: torch.Tensor) -> torch.Tensor:
     """int64 [256] counts of an int8 tensor's byte values (index = the code as an unsigned byte)."""
     assert codes.dtype == torch.int8

@@ -762,6 +762,19 @@ int samp_recommend(const double *accuracy, const double *latency, int32_t n, dou
     return SAMP_OK;
 }
 
+int samp_classify(const uint16_t *hidden, int32_t B, int32_t S, int32_t H, const uint16_t *w_pool, const float *b_pool,
+                  const uint16_t *w_cls, const float *b_cls, int32_t classes, float *logits, void *stream)
+{
+    if (!hidden || !w_pool || !b_pool || !w_cls || !b_cls || !logits) return fail(SAMP_ERR_ARG, "NULL pointer");
+    if (B < 1 || S < 1 || classes < 1) return fail(SAMP_ERR_SHAPE, "B, S and classes must be >= 1");
+    if (H < 8 || H % 8 || H > 4096) return fail(SAMP_ERR_SHAPE, "H %% 8 == 0 and H <= 4096 required");
+    if (!aligned(hidden, 16) || !aligned(w_pool, 16) || !aligned(w_cls, 16))
+        return fail(SAMP_ERR_ARG, "hidden and the weight matrices must be 16-byte aligned");
+    HIP_TRY(launch_classify((const __half *)hidden, B, S, H, (const __half *)w_pool, b_pool, (const __half *)w_cls, b_cls,
+                            classes, logits, (hipStream_t)stream));
+    return SAMP_OK;
+}
+
 int samp_code_histogram(const int8_t *codes, size_t n, uint64_t *hist, void *stream)
 {
     if (!codes || !hist) return fail(SAMP_ERR_ARG, "NULL pointer");

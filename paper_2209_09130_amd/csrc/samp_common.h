@@ -196,6 +196,9 @@ hipError_t launch_absmax_f16(const __half *x, Rows rows, int cols, int ld, float
 hipError_t launch_fill_f32(float *p, int n, float v, hipStream_t st);
 hipError_t launch_gelu_quant(const float *y, size_t n, float inv_s, int8_t *codes, float *fast, hipStream_t st);
 
+hipError_t launch_classify(const __half *hidden, int B, int S, int H, const __half *w_pool, const float *b_pool,
+                           const __half *w_cls, const float *b_cls, int C, float *logits, hipStream_t st);
+
 // host-side recommendation logic (allocator.hip)
 int allocate_decay_aware(const double *A, const double *L, int n);
 int recommend_settings(const double *A, const double *L, int n, double max_latency, double min_accuracy, int *out, int cap);

@@ -341,3 +341,19 @@ def test_embedding_kernel_bit_exact(P, H):
     short = P.Embedding(emb["tok"], emb["seg"], emb["pos"][:S - 1], emb["gamma"], emb["beta"], emb["eps"])
     with pytest.raises(P.SampError):
         P.embed_ln(short, dev(ids), None, False)                    # position table shorter than the sequences
+
+
+# ------------------------------------------------------------------ classification target
+@pytest.mark.parametrize("B,S,H,Cn", [(5, 7, 128, 3), (32, 128, 768, 15), (2, 1, 1024, 119)])
+def test_classification_target_within_accumulation_tolerance(P, B, S, H, Cn):
+    rng = np.random.default_rng(B + H + Cn)
+    hid = rng.standard_normal((B, S, H)).astype(np.float16)
+    wp = (rng.standard_normal((H, H)) * 0.05).astype(np.float16)
+    bp = (rng.standard_normal(H) * 0.1).astype(np.float32)
+    wc = (rng.standard_normal((Cn, H)) * 0.05).astype(np.float16)
+    bc = (rng.standard_normal(Cn) * 0.1).astype(np.float32)
+    want = oracle.classify(hid, wp, bp, wc, bc)
+    got = host(P.classify(dev(hid), dev(wp), dev(bp), dev(wc), dev(bc))).astype(np.float64)
+    # binary32 accumulation over H terms and a binary32 tanh against binary64: a few 1e-6 relative
+    assert np.abs(got - want).max() <= 2e-5 * max(1.0, np.abs(want).max())
+    assert np.array_equal(got.argmax(axis=1), want.argmax(axis=1))
