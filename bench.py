@@ -74,8 +74,8 @@ def main() -> int:
     ap.add_argument("--only-mode", default=None, help="time a single precision mode (FULL_INT8, FP16, ...)")
     a = ap.parse_args()
     if a.gpus != 1:
-        print("bench.py: this build runs on one GPU only (sequences are independent; see DESIGN.md for how the "
-              "path shards). Use --gpus 1.", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (sequences are independent, so more GPUs would each take a "
+              "share of the batch; nothing here does that). Use --gpus 1.", file=sys.stderr)
         return 2
 
     import numpy as np

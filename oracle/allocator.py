@@ -9,7 +9,7 @@ Two procedures of the paper, written in its notation:
   the result Lq is the index of the recommended setting.
 * recommend(A, L, max_latency, min_accuracy): the threshold rules of Appendix A.
 
-Readings where the paper is silent (the same readings are taken by the library; the design doc lists them):
+Readings where the paper is silent (the library takes the same readings):
 * L is a latency (time per inference).  Table 2 prints speedups; its rows are turned into latencies as 1/speedup.
 * L[i] == L_rec makes the decay rate a division by zero: the rate is taken as -inf if the accuracy rose (accepted,
   like any negative rate), +inf if it fell (never accepted), and the setting is skipped if both are unchanged.
