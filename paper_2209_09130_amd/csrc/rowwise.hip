@@ -17,6 +17,8 @@ namespace {
 //   mean / variance in binary64 (two passes over registers), rounded once to binary32
 //   y = fmaf((z - mu) * rstd, gamma, beta);  out = rne(y / s_out) or fp16(y)
 // ---------------------------------------------------------------------------------------------
+constexpr int LN_ROWS = 8;               // token rows per block of the LayerNorm step (16 lanes each): small blocks slot in beside the other group's kernels
+
 template <int CTRL> __device__ __forceinline__ int dpp_mov(int v)
 { return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true); }
 
@@ -121,10 +123,10 @@ __device__ __forceinline__ void ln_finish(const float (&z)[NJ][16], double sum, 
 }
 
 template <int NJ, bool IN_I8, bool RES_I8, bool OUT_I8>
-__global__ __launch_bounds__(256) void add_ln_kernel(AddLnArgs a)
+__global__ __launch_bounds__(16 * LN_ROWS) void add_ln_kernel(AddLnArgs a)
 {
     const int M = a.rows.dev_rows ? *a.rows.dev_rows : a.rows.host_rows;
-    const int row = blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int row = blockIdx.x * LN_ROWS + (threadIdx.x >> 4);
     if (row >= M) return;                               // whole 16-lane rows leave together
     const int sub = threadIdx.x & 15, H = a.H;
     const size_t base = (size_t)row * H;
@@ -161,7 +163,7 @@ __global__ __launch_bounds__(256) void add_ln_kernel(AddLnArgs a)
 template <int NJ>
 hipError_t launch_add_ln_nj(const AddLnArgs &a, hipStream_t st, const Timing *tm)
 {
-    dim3 grid((a.rows.host_rows + 15) / 16), block(256);
+    dim3 grid((a.rows.host_rows + LN_ROWS - 1) / LN_ROWS), block(16 * LN_ROWS);
 #define SAMP_LN_CASE(I, R, O)                                                                              \
     if (a.in_i8 == I && a.res_i8 == R && a.out_i8 == O) {                                                  \
         launch_kernel(add_ln_kernel<NJ, I, R, O>, grid, block, 0, st, tm, a);                           \
