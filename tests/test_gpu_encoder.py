@@ -338,6 +338,22 @@ def test_c5_long_sequences(P):
     assert (d == 0).all()
 
 
+@pytest.mark.parametrize("name,pick", [("C4", [0, 31]), ("C5", [0, 127])])
+def test_c4_and_c5_at_full_depth_on_sampled_sequences(P, name, pick):
+    """The two large configurations exactly as bench.py runs them (all layers, full batch, Fully-Quant, no mask):
+    the oracle computes the first and the last sequence of the batch (sequences are independent) and the GPU output
+    for them must be bit-identical."""
+    w = W.config(name)
+    assert all(m == FULL_INT8 for m in w.modes)
+    wts = W.make_weights(w)
+    hid, lens, _ = W.make_hidden(w)
+    sc = oracle.calibrate(*args(w), wts, W.make_calibration_batch(w))
+    got = run_gpu(P, w, wts, sc, hid, None)
+    want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid[pick], lens[pick])
+    d = compare(got[pick], want, lens[pick], True, f"{name} full depth FULL_INT8")
+    assert (d == 0).all()
+
+
 def test_gpu_calibration_matches_the_oracle_calibration(P):
     import torch
     w = W.config("C1").with_modes(FP16)
