@@ -354,6 +354,38 @@ def test_c4_and_c5_at_full_depth_on_sampled_sequences(P, name, pick):
     assert (d == 0).all()
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_random_small_configurations(P, seed):
+    """Seeded random shapes and per-layer modes (hidden 128..384, ffn 128..640, 1..3 layers, batch 1..7, length 1..70,
+    with and without padding, unsigned softmax codes on some INT8 attention blocks)."""
+    rng = np.random.default_rng(1000 + seed)
+    heads = 2 * int(rng.integers(1, 4))                    # hidden = 128, 256 or 384
+    layers = int(rng.integers(1, 4))
+    modes = []
+    for _ in range(layers):
+        m = int(rng.integers(0, 4))
+        if m & 1 and rng.random() < 0.4:
+            m |= P_UNSIGNED
+        modes.append(m)
+    seq = int(rng.integers(1, 71))
+    w = W.Workload(f"rand{seed}", layers, heads * 64, heads, int(rng.integers(1, 6)) * 128, int(rng.integers(1, 8)), seq,
+                   tuple(modes), varlen=bool(rng.integers(0, 2)), min_len=1, plain_params=False, calib_batch=3,
+                   calib_seq=max(seq, 8), weight_seed=int(rng.integers(1, 10_000)), hidden_seed=int(rng.integers(1, 10_000)),
+                   len_seed=int(rng.integers(1, 10_000)))
+    wts = W.make_weights(w)
+    hid, lens, mask = W.make_hidden(w)
+    sc = oracle.calibrate(*args(w), wts, W.make_calibration_batch(w))
+    for l, m in enumerate(modes):
+        if m & P_UNSIGNED:
+            sc[l, 4] = np.float32(sc[l, 4] * np.float32(127.0 / 255.0))
+    want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid, lens)
+    got = run_gpu(P, w, wts, sc, hid, mask if w.varlen else None)
+    exact = all((m & 3) == FULL_INT8 for m in modes)
+    d = compare(got, want, lens, exact or all(m == FP16 for m in modes), f"random {seed}: H{w.hidden} F{w.ffn} B{w.batch} S{seq} {modes}")
+    if exact:
+        assert (d == 0).all()
+
+
 def test_gpu_calibration_matches_the_oracle_calibration(P):
     import torch
     w = W.config("C1").with_modes(FP16)
