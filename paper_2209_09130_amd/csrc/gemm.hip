@@ -348,7 +348,11 @@ hipError_t launch_cfg(const void *A, const void *W, void *out, const Epi &epi, R
 // so small problems want many small tiles (more CUs pulling), large ones the larger tile (less traffic):
 //   0: 128 x 128 tile, 64-byte stages, 4-deep ring  (any K that is a multiple of 64 bytes)
 //   1: 128 x 128 tile, 128-byte stages (whole cache lines per row), 2-deep ring, 2 blocks per CU
-//   2: 64 tokens x 128 channels, otherwise as 1: up to about two and a half 128 x 128 tiles per CU
+//   2: 64 tokens x 128 channels, otherwise as 1: up to about two and a half 128 x 128 tiles per CU; rows of
+//      3072 bytes or more (FFN2) get a 3-deep ring (72 KB, still two blocks per CU) when there is at most one
+//      block per CU: -4 % on the BERT-base forward (with more blocks than CUs it measured slower); a 4-deep ring is faster for the kernel alone but crowds out the other group's kernels
+constexpr int LONG_K_BYTES = 3072;
+
 template <class T, class Epi>
 hipError_t launch(const void *A, const void *W, void *out, const Epi &epi, Rows rows, int N, int K, hipStream_t st,
                   const Timing *tm)
@@ -361,7 +365,10 @@ hipError_t launch(const void *A, const void *W, void *out, const Epi &epi, Rows 
     }
     switch (cfg) {
     case 1: return launch_cfg<T, Epi, 2, 2, 128, 2, 2>(A, W, out, epi, rows, N, K, st, tm);
-    case 2: return launch_cfg<T, Epi, 1, 2, 128, 2, 2>(A, W, out, epi, rows, N, K, st, tm);
+    case 2:
+        if (K * T::ELEM >= LONG_K_BYTES && (long)(N / 128) * ((rows.host_rows + 63) / 64) <= 256)
+            return launch_cfg<T, Epi, 1, 2, 128, 3, 2>(A, W, out, epi, rows, N, K, st, tm);
+        return launch_cfg<T, Epi, 1, 2, 128, 2, 2>(A, W, out, epi, rows, N, K, st, tm);
     default: return launch_cfg<T, Epi, 2, 2, 64, 4, 2>(A, W, out, epi, rows, N, K, st, tm);
     }
 }

@@ -110,6 +110,25 @@ def test_every_gemm_tile_configuration_gives_the_same_results(P, config):
         P.set_gemm_config(3)
 
 
+def test_long_rows_with_few_tiles_take_the_deeper_ring(P):
+    """Operand rows of 3072 bytes with at most one block per CU run through a 3-deep stage ring (FFN2 at small
+    batch): INT8 requantising GEMM bit-exact, FP16 GEMM within one ulp, ragged last row tile."""
+    rng = np.random.default_rng(91)
+    M, N, K = 300, 256, 3072
+    A = rng.integers(-127, 128, (M, K), dtype=np.int8)
+    W = rng.integers(-127, 128, (N, K), dtype=np.int8)
+    s_w, bias = _tables(rng, N)
+    m, b = oracle.fold_requant(0.037, s_w, bias, 0.042)
+    want = oracle.epilogue_requant(oracle.gemm_i8_i32(A, W), m, b)
+    assert np.array_equal(host(P.gemm_i8_requant(dev(A), dev(W), dev(m), dev(b))), want)
+    assert np.array_equal(host(P.gemm_i8_i32(dev(A), dev(W))), oracle.gemm_i8_i32(A, W))
+    Ah = (rng.standard_normal((M, K // 2)) * 0.5).astype(np.float16)
+    Wh = (rng.standard_normal((N, K // 2)) * 0.05).astype(np.float16)
+    wantf = oracle.gemm_f16(Ah, Wh, bias, False).astype(np.float64)
+    gotf = host(P.gemm_f16(dev(Ah), dev(Wh), dev(bias), False)).astype(np.float64)
+    assert (np.abs(gotf - wantf) <= np.maximum(np.abs(wantf), 2.0 ** -14) * 2.0 ** -10 + 1e-6).all()
+
+
 def test_int8_gemm_gelu_quant_epilogue_bit_exact(P):
     rng = np.random.default_rng(21)
     M, N, K = 260, 384, 768
