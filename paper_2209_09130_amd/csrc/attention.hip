@@ -28,10 +28,14 @@ constexpr int VT_STRIDE_F16 = 72;      // bytes per V^T row (32 keys + pad), fp1
 // of degree 11 in r (truncation below 2^-47), scaled by 2^k.  Its error is far below a binary32
 // ulp, so rounding the result to binary32 gives the correctly rounded exponential (up to ties
 // narrower than 2^-45), which is what the quantiser's decision is defined on.
+// The caller clamps x to [-746, 0] (in binary32; -inf of a masked key becomes a value whose
+// exponential rounds to 0).  k = rint(x / ln2) comes out of one fma with 1.5 * 2^52: the sum's low
+// dword is k as an integer, the sum minus the constant is k as a double.
 __device__ __forceinline__ double exp_nonpos(double x)
 {
-    x = __builtin_fmax(x, -746.0);                       // also maps -inf (masked keys) to an underflowing value
-    const double k = __builtin_rint(x * 1.44269504088896338700e+00);
+    const double shifted = __builtin_fma(x, 1.44269504088896338700e+00, 6755399441055744.0);
+    const int ki = (int)(unsigned)__double_as_longlong(shifted);
+    const double k = shifted - 6755399441055744.0;
     double r = __builtin_fma(k, -6.93147180369123816490e-01, x);
     r = __builtin_fma(k, -1.90821492927058770002e-10, r);
     double p = 2.50521083854417187751e-08;               // 1/11!
@@ -46,7 +50,7 @@ __device__ __forceinline__ double exp_nonpos(double x)
     p = __builtin_fma(p, r, 5.00000000000000000000e-01);
     p = __builtin_fma(p, r, 1.0);
     p = __builtin_fma(p, r, 1.0);
-    return __builtin_ldexp(p, (int)k);
+    return __builtin_ldexp(p, ki);
 }
 
 struct SeqInfo { int t0, n; };
@@ -120,11 +124,19 @@ __global__ __launch_bounds__(256) void attention_i8_kernel(const int8_t *__restr
                 dst[2 * (VT_STRIDE_I8 / 4)] = __builtin_amdgcn_perm(t23h, t01h, 0x05040100u);
                 dst[3 * (VT_STRIDE_I8 / 4)] = __builtin_amdgcn_perm(t23h, t01h, 0x07060302u);
             }
+            if (j0 + 32 <= n) {                                  // wave-uniform: a full tile needs no masking
 #pragma unroll
-            for (int e = 0; e < 16; e++) {
-                const int key = j0 + 8 * (e >> 2) + 4 * g + (e & 3);
-                sc[i][e] = key < n ? (float)acc[e] * m_sc : -INFINITY;
-                mx = __builtin_fmaxf(mx, sc[i][e]);
+                for (int e = 0; e < 16; e++) {
+                    sc[i][e] = (float)acc[e] * m_sc;
+                    mx = __builtin_fmaxf(mx, sc[i][e]);
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; e++) {
+                    const int key = j0 + 8 * (e >> 2) + 4 * g + (e & 3);
+                    sc[i][e] = key < n ? (float)acc[e] * m_sc : -INFINITY;
+                    mx = __builtin_fmaxf(mx, sc[i][e]);
+                }
             }
         } else {
 #pragma unroll
@@ -141,7 +153,7 @@ __global__ __launch_bounds__(256) void attention_i8_kernel(const int8_t *__restr
     for (int i = 0; i < NT; i++)
 #pragma unroll
         for (int e = 0; e < 16; e++) {
-            const float ev = (float)exp_nonpos((double)(sc[i][e] - mx));   // 0 for masked keys (score -inf)
+            const float ev = (float)exp_nonpos((double)__builtin_fmaxf(sc[i][e] - mx, -746.0f));   // 0 for masked keys (score -inf)
             sc[i][e] = ev;
             part += (double)ev;
         }
