@@ -20,6 +20,8 @@
 // Work-groups are renumbered so that each XCD (own L2) owns a contiguous range of tiles.
 #include "samp_common.h"
 
+#include <type_traits>
+
 namespace samp {
 namespace {
 
@@ -364,7 +366,11 @@ hipError_t launch(const void *A, const void *W, void *out, const Epi &epi, Rows 
         cfg = tiles <= 640 ? 2 : 1;
     }
     switch (cfg) {
-    case 1: return launch_cfg<T, Epi, 2, 2, 128, 2, 2>(A, W, out, epi, rows, N, K, st, tm);
+    case 1:
+        // the GELU epilogue is as much vector work as the main loop is matrix work: 64-byte stages leave room
+        // for three resident blocks per CU, whose epilogues and main loops overlap (-3 % on the large forwards)
+        if constexpr (std::is_same<Epi, EpiGeluQuant>::value) return launch_cfg<T, Epi, 2, 2, 64, 3, 3>(A, W, out, epi, rows, N, K, st, tm);
+        else return launch_cfg<T, Epi, 2, 2, 128, 2, 2>(A, W, out, epi, rows, N, K, st, tm);
     case 2:
         if (K * T::ELEM >= LONG_K_BYTES && (long)(N / 128) * ((rows.host_rows + 63) / 64) <= 256)
             return launch_cfg<T, Epi, 1, 2, 128, 3, 2>(A, W, out, epi, rows, N, K, st, tm);
