@@ -82,7 +82,7 @@ __global__ __launch_bounds__(256) void attention_i8_kernel(const int8_t *__restr
     if (q0 >= sq.n) return;
     const int n = sq.n, head = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, g = lane >> 5;
-    const size_t ld = (size_t)3 * H;
+    const unsigned ld = 3u * (unsigned)H;                          // row offsets inside a sequence fit 32 bits
     const int8_t *base = qkv + (size_t)sq.t0 * ld + head * 64;
     if (HIST) hist[tid] = 0;                                      // ordered before its use by the barriers below
 
@@ -90,7 +90,7 @@ __global__ __launch_bounds__(256) void attention_i8_kernel(const int8_t *__restr
     const int qrow = min(q0 + r, n - 1);
     v4i qf[2];
 #pragma unroll
-    for (int ks = 0; ks < 2; ks++) qf[ks] = *reinterpret_cast<const v4i *>(base + (size_t)qrow * ld + ks * 32 + g * 16);
+    for (int ks = 0; ks < 2; ks++) qf[ks] = *reinterpret_cast<const v4i *>(base + (unsigned)qrow * ld + ks * 32 + g * 16);
 
     float sc[NT][16];
     float mx = -INFINITY;
@@ -99,7 +99,7 @@ __global__ __launch_bounds__(256) void attention_i8_kernel(const int8_t *__restr
         const int j0 = (w + 4 * i) * 32;
         if (j0 < n) {                                           // wave-uniform
             const int krow = min(j0 + r, n - 1);
-            const int8_t *kp = base + (size_t)krow * ld + H;
+            const int8_t *kp = base + (unsigned)krow * ld + H;
             v16i acc;
 #pragma unroll
             for (int e = 0; e < 16; e++) acc[e] = 0;
@@ -115,7 +115,7 @@ __global__ __launch_bounds__(256) void attention_i8_kernel(const int8_t *__restr
                 unsigned d[4];
 #pragma unroll
                 for (int t = 0; t < 4; t++)
-                    d[t] = *reinterpret_cast<const unsigned *>(vp + (size_t)min(j0 + 4 * kq + t, n - 1) * ld + 4 * cq);
+                    d[t] = *reinterpret_cast<const unsigned *>(vp + (unsigned)min(j0 + 4 * kq + t, n - 1) * ld + 4 * cq);
                 const unsigned t01l = __builtin_amdgcn_perm(d[1], d[0], 0x05010400u), t23l = __builtin_amdgcn_perm(d[3], d[2], 0x05010400u);
                 const unsigned t01h = __builtin_amdgcn_perm(d[1], d[0], 0x07030602u), t23h = __builtin_amdgcn_perm(d[3], d[2], 0x07030602u);
                 unsigned *dst = reinterpret_cast<unsigned *>(&vt[w][i][(4 * cq) * VT_STRIDE_I8 + 4 * kq]);
@@ -242,13 +242,13 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const __half *__rest
     if (q0 >= sq.n) return;
     const int n = sq.n, head = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, g = lane >> 5;
-    const size_t ld = (size_t)3 * H;
+    const unsigned ld = 3u * (unsigned)H;
     const __half *base = qkv + (size_t)sq.t0 * ld + head * 64;
 
     const int qrow = min(q0 + r, n - 1);
     v8h qf[4];
 #pragma unroll
-    for (int ks = 0; ks < 4; ks++) qf[ks] = *reinterpret_cast<const v8h *>(base + (size_t)qrow * ld + ks * 16 + g * 8);
+    for (int ks = 0; ks < 4; ks++) qf[ks] = *reinterpret_cast<const v8h *>(base + (unsigned)qrow * ld + ks * 16 + g * 8);
 
     float sc[NT][16];
     float mx = -INFINITY;
@@ -257,7 +257,7 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const __half *__rest
         const int j0 = (w + 4 * i) * 32;
         if (j0 < n) {
             const int krow = min(j0 + r, n - 1);
-            const __half *kp = base + (size_t)krow * ld + H;
+            const __half *kp = base + (unsigned)krow * ld + H;
             v16f acc;
 #pragma unroll
             for (int e = 0; e < 16; e++) acc[e] = 0.0f;
@@ -269,7 +269,7 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const __half *__rest
 #pragma unroll
             for (int u = 0; u < 4; u++) {
                 const int idx = lane + 64 * u, key = idx >> 3, c0 = (idx & 7) * 8;
-                const v8h v = *reinterpret_cast<const v8h *>(vp + (size_t)min(j0 + key, n - 1) * ld + c0);
+                const v8h v = *reinterpret_cast<const v8h *>(vp + (unsigned)min(j0 + key, n - 1) * ld + c0);
 #pragma unroll
                 for (int e = 0; e < 8; e++)
                     *reinterpret_cast<_Float16 *>(&vt[w][i][(c0 + e) * VT_STRIDE_F16 + key * 2]) = v[e];
