@@ -77,10 +77,15 @@ __global__ __launch_bounds__(256) void attention_i8_kernel(const int8_t *__restr
     __shared__ float smax[4][QB];
     __shared__ double ssum[4][QB];
 
-    const SeqInfo sq = seq_info(cu, blockIdx.z, max_len);
-    const int q0 = blockIdx.x * QB;
+    // work item = (sequence, head, query block), sequences outermost: XCD x works on the x-th eighth of the
+    // sequences, whose tokens it also owns in the kernels before and after this one
+    const int nqb = (max_len + QB - 1) / QB, heads = H >> 6;
+    const int item = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int seq = item / (nqb * heads), head = (item / nqb) % heads;
+    const SeqInfo sq = seq_info(cu, seq, max_len);
+    const int q0 = (item % nqb) * QB;
     if (q0 >= sq.n) return;
-    const int n = sq.n, head = blockIdx.y;
+    const int n = sq.n;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, g = lane >> 5;
     const unsigned ld = 3u * (unsigned)H;                          // row offsets inside a sequence fit 32 bits
     const int8_t *base = qkv + (size_t)sq.t0 * ld + head * 64;
@@ -237,10 +242,15 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const __half *__rest
     __shared__ float smax[4][QB];
     __shared__ float ssum[4][QB];
 
-    const SeqInfo sq = seq_info(cu, blockIdx.z, max_len);
-    const int q0 = blockIdx.x * QB;
+    // work item = (sequence, head, query block), sequences outermost: XCD x works on the x-th eighth of the
+    // sequences, whose tokens it also owns in the kernels before and after this one
+    const int nqb = (max_len + QB - 1) / QB, heads = H >> 6;
+    const int item = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int seq = item / (nqb * heads), head = (item / nqb) % heads;
+    const SeqInfo sq = seq_info(cu, seq, max_len);
+    const int q0 = (item % nqb) * QB;
     if (q0 >= sq.n) return;
-    const int n = sq.n, head = blockIdx.y;
+    const int n = sq.n;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, g = lane >> 5;
     const unsigned ld = 3u * (unsigned)H;
     const __half *base = qkv + (size_t)sq.t0 * ld + head * 64;
@@ -354,7 +364,7 @@ static void launch_attention_i8_variant(const int8_t *qkv, const int *cu, int B,
                                         float inv_sp, float m_ctx, int8_t *ctx, unsigned long long *p_hist, hipStream_t st,
                                         const Timing *tm)
 {
-    dim3 grid((max_len + QB - 1) / QB, heads, B), block(256);
+    dim3 grid((unsigned)((max_len + QB - 1) / QB) * heads * B), block(256);
     if (max_len <= 128)
         launch_kernel(attention_i8_kernel<1, PU, HIST>, grid, block, 0, st, tm, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx, p_hist);
     else if (max_len <= 256)
@@ -380,7 +390,7 @@ hipError_t launch_attention_i8(const int8_t *qkv, const int *cu, int B, int max_
 hipError_t launch_attention_f16(const __half *qkv, const int *cu, int B, int max_len, int H, int heads, float scale,
                                 __half *ctx, float *p_absmax, hipStream_t st, const Timing *tm)
 {
-    dim3 grid((max_len + QB - 1) / QB, heads, B), block(256);
+    dim3 grid((unsigned)((max_len + QB - 1) / QB) * heads * B), block(256);
     if (max_len <= 128)
         launch_kernel(attention_f16_kernel<1>, grid, block, 0, st, tm, qkv, cu, max_len, H, scale, ctx, p_absmax);
     else if (max_len <= 256)

@@ -195,16 +195,13 @@ void gemm_nt_kernel(const char *__restrict__ A, const char *__restrict__ W, char
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     float *tab = reinterpret_cast<float *>(lds + RING_BYTES);
 
-    // XCD-aware renumbering: hardware hands consecutive work-groups to the 8 XCDs in turn; give
-    // each XCD a contiguous range of tiles (same token rows, all channel tiles) for L2 reuse.
-    int tile = blockIdx.x;
-    {
-        const int per = tiles_total >> 3, body = per << 3;
-        if (tile < body) tile = (tile & 7) * per + (tile >> 3);
-    }
+    // each XCD owns a contiguous range of the tiles of the rows that exist (tile order: token rows, then
+    // channel tiles), i.e. the same eighth of the token rows as in every other kernel of the path
     const int M = dev_rows ? *dev_rows : host_rows;
+    const int tiles = ((M + BM - 1) / BM) * tiles_n;
+    if ((int)blockIdx.x >= tiles) return;
+    const int tile = xcd_contiguous(blockIdx.x, tiles);
     const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
-    if (m0 >= M) return;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = (wave >> 1) * 32 * TM, wn = (wave & 1) * 32 * TN;       // wave tile origin inside the block tile

@@ -126,7 +126,9 @@ template <int NJ, bool IN_I8, bool RES_I8, bool OUT_I8>
 __global__ __launch_bounds__(16 * LN_ROWS) void add_ln_kernel(AddLnArgs a)
 {
     const int M = a.rows.dev_rows ? *a.rows.dev_rows : a.rows.host_rows;
-    const int row = blockIdx.x * LN_ROWS + (threadIdx.x >> 4);
+    const int nblk = (M + LN_ROWS - 1) / LN_ROWS;
+    if ((int)blockIdx.x >= nblk) return;
+    const int row = xcd_contiguous(blockIdx.x, nblk) * LN_ROWS + (threadIdx.x >> 4);   // XCD x: x-th eighth of the rows
     if (row >= M) return;                               // whole 16-lane rows leave together
     const int sub = threadIdx.x & 15, H = a.H;
     const size_t base = (size_t)row * H;
@@ -301,7 +303,10 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *__rest
                                                             int8_t *__restrict__ out)
 {
     const float inv_s = 1.0f / s_x;
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (size_t)gridDim.x * 256) {
+    // one contiguous chunk per block, chunks numbered so that XCD x quantises the x-th eighth of the tensor
+    const size_t chunk = (n8 + gridDim.x - 1) / gridDim.x;
+    const size_t first = (size_t)xcd_contiguous(blockIdx.x, gridDim.x) * chunk, last = first + chunk < n8 ? first + chunk : n8;
+    for (size_t i = first + threadIdx.x; i < last; i += 256) {
         const v8h v = *reinterpret_cast<const v8h *>(x + i * 8);
         v2i o;
         o.x = pack4(qcode((float)v[0] * inv_s), qcode((float)v[1] * inv_s), qcode((float)v[2] * inv_s), qcode((float)v[3] * inv_s));
