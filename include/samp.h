@@ -28,6 +28,11 @@
  *     samp_last_error() then describes the failure.  No exception or abort
  *     crosses this boundary.  Arguments are checked on the host before any
  *     kernel is launched.
+ *   - Threads: an encoder handle is used by one thread at a time (a forward
+ *     updates its graph cache and event pool); different handles, and the step
+ *     entry points, may be used from different threads.  samp_last_error() is
+ *     per thread.  An encoder owns a few HIP streams and events for its batch
+ *     groups and graph capture; samp_encoder_destroy releases them.
  *   - Quantiser (Appendix B: multiply by a scale, round, symmetric 8-bit range):
  *     code = clamp(round_half_even(x * (1/s)), -127, 127), where the step s is
  *     absmax/127 from a min-max calibration (Table 2 caption) and 1/s is formed

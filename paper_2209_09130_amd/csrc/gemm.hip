@@ -20,6 +20,7 @@
 // Work-groups are renumbered so that each XCD (own L2) owns a contiguous range of tiles.
 #include "samp_common.h"
 
+#include <atomic>
 #include <type_traits>
 
 namespace samp {
@@ -181,7 +182,7 @@ __device__ __forceinline__ void wait_vm_and_barrier()
 template <class T, class Epi, int TM, int TN, int BKB, int NSTAGE, int WAVES_PER_EU>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WAVES_PER_EU, 8)))
 void gemm_nt_kernel(const char *__restrict__ A, const char *__restrict__ W, char *__restrict__ out, Epi epi, int host_rows,
-                    const int *__restrict__ dev_rows, int N, int Kbytes, int tiles_n, int tiles_total)
+                    const int *__restrict__ dev_rows, int N, int Kbytes, int tiles_n)
 {
     constexpr int NT = 256, NWAVES = 4;
     constexpr int BM = 64 * TM, BN = 64 * TN;
@@ -329,16 +330,17 @@ hipError_t launch_cfg(const void *A, const void *W, void *out, const Epi &epi, R
     if (N % BN) return hipErrorInvalidValue;
     if ((K * T::ELEM) % BKB) return hipErrorInvalidValue;
     auto kern = gemm_nt_kernel<T, Epi, TM, TN, BKB, NSTAGE, WPE>;
-    static bool attr_set = false;                                 // > 64 KiB of dynamic LDS must be enabled once
-    if (!attr_set) {
+    // > 64 KiB of dynamic LDS must be enabled once per kernel; setting it twice from two threads is harmless
+    static std::atomic<bool> attr_set{false};
+    if (!attr_set.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     const int tiles_n = N / BN, tiles_m = (rows.host_rows + BM - 1) / BM, total = tiles_n * tiles_m;
     launch_kernel(kern, dim3(total), dim3(256), LDS, st, tm,
                           (const char *)A, (const char *)W, (char *)out, epi, rows.host_rows, rows.dev_rows, N, K * T::ELEM,
-                          tiles_n, total);
+                          tiles_n);
     return hipGetLastError();
 }
 
@@ -356,7 +358,7 @@ template <class T, class Epi>
 hipError_t launch(const void *A, const void *W, void *out, const Epi &epi, Rows rows, int N, int K, hipStream_t st,
                   const Timing *tm)
 {
-    int cfg = gemm_config_override;
+    int cfg = gemm_config_override.load(std::memory_order_relaxed);
     if ((K * T::ELEM) % 128) cfg = 0;
     else if (cfg < 0) {
         const long tiles = (long)(N / 128) * ((rows.host_rows + 127) / 128);
@@ -378,7 +380,7 @@ hipError_t launch(const void *A, const void *W, void *out, const Epi &epi, Rows 
 
 }  // namespace
 
-int gemm_config_override = -1;                    // tuning aid: force one tile configuration (see launch())
+std::atomic<int> gemm_config_override{-1};                    // tuning aid: force one tile configuration (see launch())
 
 hipError_t launch_gemm_i8(GemmEpilogue epi, const int8_t *A, const int8_t *W, void *out, const float *m, const float *b,
                           float inv_s_out, Rows rows, int N, int K, hipStream_t st, const Timing *tm)

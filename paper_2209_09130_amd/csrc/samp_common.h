@@ -5,6 +5,8 @@
 #include <hip/hip_ext.h>
 #include <stdint.h>
 
+#include <atomic>
+
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v16i __attribute__((ext_vector_type(16)));
@@ -160,7 +162,7 @@ inline void launch_kernel(K kern, dim3 grid, dim3 block, size_t lds, hipStream_t
 struct Rows { int host_rows; const int *dev_rows; };
 
 enum GemmEpilogue { EPI_RAW_I32, EPI_REQUANT, EPI_GELU_QUANT };
-extern int gemm_config_override;                           // < 0: choose the tile configuration by shape
+extern std::atomic<int> gemm_config_override;                           // < 0: choose the tile configuration by shape
 
 hipError_t launch_gemm_i8(GemmEpilogue epi, const int8_t *A, const int8_t *W, void *out, const float *m, const float *b,
                           float inv_s_out, Rows rows, int N, int K, hipStream_t st, const Timing *tm);
