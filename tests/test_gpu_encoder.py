@@ -400,6 +400,25 @@ def test_gpu_calibration_matches_the_oracle_calibration(P):
     assert got[0, 0] == want[0, 0]                       # the input's absmax is exact
 
 
+def test_gpu_calibration_with_padding_ignores_padded_rows(P):
+    """Calibration on a right-padded batch whose pad rows hold large garbage: the steps must be those of the valid
+    tokens only (the oracle's unquantised forward with the same lengths)."""
+    import torch
+    w = W.Workload("calpad", 2, 256, 4, 512, 6, 50, (FP16, FP16), varlen=True, min_len=3, plain_params=False)
+    wts = W.make_weights(w)
+    hid, lens, mask = W.make_hidden(w)
+    for b in range(w.batch):
+        hid[b, lens[b]:] *= np.float16(50.0)              # pad rows louder than any token
+    _, am = oracle.reference_forward(*args(w), wts, hid, lens, want_out=False, want_absmax=True)
+    want = am / np.float32(127)
+    enc = P.Encoder(*args(w), w.modes, wts, None, max_batch=w.batch, max_seq=w.seq)
+    got = enc.calibrate(torch.from_numpy(hid).cuda(), torch.from_numpy(mask).cuda())
+    enc.close()
+    assert np.abs(got / want - 1).max() < 1e-2
+    valid_max = max(np.abs(hid[b, :lens[b]].astype(np.float32)).max() for b in range(w.batch))
+    assert got[0, 0] == np.float32(valid_max) / np.float32(127)
+
+
 @pytest.mark.parametrize("varlen", [False, True])
 def test_batch_groups_and_graph_replay_do_not_change_results(P, varlen):
     """The forward may split the batch over concurrent streams and replay a recorded graph; neither
