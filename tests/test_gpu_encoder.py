@@ -400,6 +400,63 @@ def test_gpu_calibration_matches_the_oracle_calibration(P):
     assert got[0, 0] == want[0, 0]                       # the input's absmax is exact
 
 
+def test_one_encoder_many_shapes_and_graph_cache_eviction(P):
+    """The same encoder serves batches of different shapes in turn; every (buffers, B, S) gets its own recorded graph
+    and the cache holds eight of them, so eleven shapes used three times each also exercise eviction and re-capture."""
+    import torch
+    w = small((FULL_INT8, FULL_INT8), batch=8, seq=64, varlen=True)
+    wts = W.make_weights(w)
+    sc = oracle.calibrate(*args(w), wts, W.make_calibration_batch(w))
+    enc = P.Encoder(*args(w), w.modes, wts, sc, max_batch=8, max_seq=64)
+    orc = oracle.Encoder(*args(w), w.modes, wts, sc)
+    rng = np.random.default_rng(77)
+    cases = []
+    for i in range(11):
+        B, S = int(rng.integers(1, 9)), int(rng.integers(1, 65))
+        hid = rng.standard_normal((B, S, w.hidden)).astype(np.float16)
+        lens = rng.integers(1, S + 1, B).astype(np.int32)
+        mask = (np.arange(S)[None, :] < lens[:, None]).astype(np.int32)
+        cases.append((torch.from_numpy(hid).cuda(), torch.from_numpy(mask).cuda(), torch.empty((B, S, w.hidden), dtype=torch.float16, device="cuda"),
+                      orc.forward(hid, lens)))
+    for rnd in range(3):
+        for h, m, out, want in cases:
+            out.fill_(3.0)
+            enc.forward(h, m, out)
+            torch.cuda.synchronize()
+            assert np.array_equal(out.cpu().numpy(), want), rnd
+    enc.close()
+    orc.close()
+
+
+def test_ids_to_logits_pipeline(P):
+    """Embedding kernel -> encoder -> classification target, all through the library, against the oracle's chain."""
+    import torch
+    w = small((FULL_INT8, FULL_INT8, FULL_INT8), batch=5, seq=33, varlen=True)
+    wts = W.make_weights(w)
+    _, lens, mask = W.make_hidden(w)
+    emb = W.make_embedding(w, vocab=300)
+    ids, seg = W.make_ids(w, vocab=300)
+    hid = np.zeros((w.batch, w.seq, w.hidden), np.float16)
+    for b in range(w.batch):
+        hid[b, :lens[b]] = oracle.embed_ln(emb, ids[b, :lens[b]], seg[b, :lens[b]], False)
+    sc = oracle.calibrate(*args(w), wts, hid[:4])
+    rng = np.random.default_rng(5)
+    wp = (rng.standard_normal((w.hidden, w.hidden)) * 0.05).astype(np.float16)
+    bp = (rng.standard_normal(w.hidden) * 0.1).astype(np.float32)
+    wc = (rng.standard_normal((7, w.hidden)) * 0.05).astype(np.float16)
+    bc = (rng.standard_normal(7) * 0.1).astype(np.float32)
+    enc_out = oracle.Encoder(*args(w), w.modes, wts, sc).forward_ids(emb, ids, seg, lens)
+    want = oracle.classify(enc_out, wp, bp, wc, bc)
+    E = P.Embedding(emb["tok"], emb["seg"], emb["pos"], emb["gamma"], emb["beta"], emb["eps"])
+    enc = P.Encoder(*args(w), w.modes, wts, sc, max_batch=w.batch, max_seq=w.seq)
+    dev = lambda a: torch.from_numpy(a).cuda()
+    out = enc.forward_ids(E, dev(ids), dev(seg), dev(mask))
+    logits = P.classify(out, dev(wp), dev(bp), dev(wc), dev(bc)).cpu().numpy().astype(np.float64)
+    enc.close()
+    assert np.array_equal(out.cpu().numpy(), enc_out)              # Fully-Quant from ids: bit-identical
+    assert np.abs(logits - want).max() <= 2e-5 * max(1.0, np.abs(want).max())
+
+
 def test_gpu_calibration_with_padding_ignores_padded_rows(P):
     """Calibration on a right-padded batch whose pad rows hold large garbage: the steps must be those of the valid
     tokens only (the oracle's unquantised forward with the same lengths)."""
