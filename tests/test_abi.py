@@ -65,3 +65,24 @@ def test_invalid_arguments_become_error_codes_on_the_host(L):
     out = C.c_void_p()
     assert L.samp_encoder_create(C.byref(ok), modes, None, None, None, C.c_size_t(0), None, C.byref(out)) == -1
     assert L.samp_encoder_forward(None, None, None, 1, 1, None, None, C.c_size_t(0), None) == -1
+
+
+def test_later_entry_points_reject_bad_arguments_on_the_host(L):
+    """The embedding, target, histogram and tuning entry points check their arguments before any launch."""
+    from paper_2209_09130_amd.binding import _EmbeddingStruct
+    buf = (C.c_char * 256)()
+    emb = _EmbeddingStruct()                                   # all pointers NULL
+    assert L.samp_embed_ln(C.byref(emb), buf, None, 1, 4, 128, buf, 0, C.c_float(1), None) == -1
+    assert b"NULL" in L.samp_last_error()
+    assert L.samp_embed_ln(None, buf, None, 1, 4, 128, buf, 0, C.c_float(1), None) == -1
+    assert L.samp_embed_ln(C.byref(emb), None, None, 1, 4, 128, buf, 0, C.c_float(1), None) == -1
+    assert L.samp_encoder_forward_ids(None, C.byref(emb), buf, None, None, 1, 4, buf, buf, C.c_size_t(256), None) == -1
+    assert L.samp_classify(None, 1, 4, 128, buf, buf, buf, buf, 3, buf, None) == -1
+    assert L.samp_classify(buf, 1, 4, 100, buf, buf, buf, buf, 3, buf, None) == -2          # H % 8
+    assert L.samp_classify(buf, 1, 4, 128, buf, buf, buf, buf, 0, buf, None) == -2          # no classes
+    assert L.samp_code_histogram(None, C.c_size_t(16), buf, None) == -1
+    assert L.samp_code_histogram(buf, C.c_size_t(0), buf, None) == -2
+    assert L.samp_set_gemm_config(9) == -1
+    assert L.samp_set_gemm_config(-1) == 0
+    assert L.samp_attention_i8(None, None, 1, 16, 128, 2, C.c_float(1), C.c_float(1), C.c_float(1), C.c_float(1), C.c_float(1),
+                               0, None, None, None) == -1
