@@ -215,7 +215,7 @@ SAMP_API int samp_code_histogram(const int8_t *codes, size_t n, uint64_t *hist, 
 
 /* Tuning aid: force the tile configuration of every GEMM launched afterwards by this process
  * (0: 128x128 tile with 64-byte K stages, 1: 128x128 with 128-byte stages, 2: 64 tokens x 128
- * channels), or -1 (default) to choose by problem shape.  Configurations 1 and 2 need the operand
+ * channels), or -1 (default) to choose by problem shape (which may also take 64 x 96 tiles).  Configurations 1 and 2 need the operand
  * rows to be multiples of 128 bytes and fall back to 0 otherwise.  Results do not depend on it
  * for INT8; FP16 sums are formed in the same order in all three.                                   */
 SAMP_API int samp_set_gemm_config(int32_t config);

@@ -179,19 +179,21 @@ __device__ __forceinline__ void wait_vm_and_barrier()
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-template <class T, class Epi, int TM, int TN, int BKB, int NSTAGE, int WAVES_PER_EU>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WAVES_PER_EU, 8)))
+// A block is WGM x WGN waves, each computing 32 TM tokens x 32 TN channels.
+template <class T, class Epi, int TM, int TN, int BKB, int NSTAGE, int WAVES_PER_EU, int WGM = 2, int WGN = 2>
+__global__ __launch_bounds__(64 * WGM * WGN) __attribute__((amdgpu_waves_per_eu(WAVES_PER_EU, 8)))
 void gemm_nt_kernel(const char *__restrict__ A, const char *__restrict__ W, char *__restrict__ out, Epi epi, int host_rows,
                     const int *__restrict__ dev_rows, int N, int Kbytes, int tiles_n)
 {
-    constexpr int NT = 256, NWAVES = 4;
-    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int NWAVES = WGM * WGN, NT = 64 * NWAVES;
+    constexpr int BM = 32 * WGM * TM, BN = 32 * WGN * TN;
     constexpr int A_BYTES = BM * BKB, W_BYTES = BN * BKB, STAGE_BYTES = A_BYTES + W_BYTES;
     constexpr int CH = BKB / 16, RPI = 64 / CH;                  // chunks per row; rows per direct-load instruction
     static_assert(BKB == 64 || BKB == 128, "stage depth");
-    static_assert((BM / RPI) % NWAVES == 0 && (BN / RPI) % NWAVES == 0, "tile rows must split evenly over the waves");
-    constexpr int NA = BM / RPI / NWAVES, NW = BN / RPI / NWAVES; // direct-load instructions per wave per stage
-    constexpr int NLD = NA + NW;
+    static_assert(BM % RPI == 0 && BN % RPI == 0, "operand tiles must be whole 1 KiB pieces");
+    // a stage is (BM + BN) / RPI pieces of 1 KiB (the token tile first, then the channel tile), dealt to the
+    // waves in turn; when they do not divide evenly the first NPIECE % NWAVES waves issue one load more
+    constexpr int NPIECE = (BM + BN) / RPI, NLD = (NPIECE + NWAVES - 1) / NWAVES, NLD_FEWER = NPIECE / NWAVES;
     constexpr int RING_BYTES = NSTAGE * STAGE_BYTES;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     float *tab = reinterpret_cast<float *>(lds + RING_BYTES);
@@ -205,33 +207,38 @@ void gemm_nt_kernel(const char *__restrict__ A, const char *__restrict__ W, char
     const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = (wave >> 1) * 32 * TM, wn = (wave & 1) * 32 * TN;       // wave tile origin inside the block tile
+    const int wm = (wave / WGN) * 32 * TM, wn = (wave % WGN) * 32 * TN;    // wave tile origin inside the block tile
     const int r = lane & 31, g = lane >> 5;
 
     // direct loads: instruction j of this wave fills RPI consecutive rows (1 KiB) of an operand tile;
     // lane i supplies row (i / CH), LDS chunk (i % CH), i.e. global chunk (i % CH) ^ swz(row).
-    const char *a_src[NA], *w_src[NW];
+    const char *src[NLD];
+    const bool fewer = NLD_FEWER != NLD && wave >= NPIECE % NWAVES;   // this wave has no last piece
 #pragma unroll
-    for (int j = 0; j < NA; j++) {
-        const int row = RPI * (wave + NWAVES * j) + lane / CH;
-        int am = m0 + row; if (am > M - 1) am = M - 1;            // rows past the end re-read the last row
-        a_src[j] = A + (size_t)am * Kbytes + (((lane % CH) ^ swz<BKB>(row)) << 4);
-    }
-#pragma unroll
-    for (int j = 0; j < NW; j++) {
-        const int row = RPI * (wave + NWAVES * j) + lane / CH;
-        w_src[j] = W + (size_t)(n0 + row) * Kbytes + (((lane % CH) ^ swz<BKB>(row)) << 4);
+    for (int j = 0; j < NLD; j++) {
+        const int piece = min(wave + NWAVES * j, NPIECE - 1);
+        const int srow = RPI * piece + lane / CH;                // row inside the stage
+        if (srow < BM) {
+            int am = m0 + srow; if (am > M - 1) am = M - 1;      // rows past the end re-read the last row
+            src[j] = A + (size_t)am * Kbytes + (((lane % CH) ^ swz<BKB>(srow)) << 4);
+        } else {
+            const int row = srow - BM;
+            src[j] = W + (size_t)(n0 + row) * Kbytes + (((lane % CH) ^ swz<BKB>(row)) << 4);
+        }
     }
     auto issue = [&](int kt) {
         char *st = lds + (kt % NSTAGE) * STAGE_BYTES;
 #pragma unroll
-        for (int j = 0; j < NA; j++)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(a_src[j] + (size_t)kt * BKB),
-                                             (__attribute__((address_space(3))) void *)(st + (wave + NWAVES * j) * 1024), 16, 0, 0);
-#pragma unroll
-        for (int j = 0; j < NW; j++)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(w_src[j] + (size_t)kt * BKB),
-                                             (__attribute__((address_space(3))) void *)(st + A_BYTES + (wave + NWAVES * j) * 1024), 16, 0, 0);
+        for (int j = 0; j < NLD; j++)
+            if (j < NLD_FEWER || !fewer)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[j] + (size_t)kt * BKB),
+                                                 (__attribute__((address_space(3))) void *)(st + (wave + NWAVES * j) * 1024), 16, 0, 0);
+    };
+    // stage kt has landed when at most the loads of the (NSTAGE - 2) later stages are outstanding
+    auto wait_stage = [&](bool later_stages_in_flight) {
+        if (!later_stages_in_flight) wait_vm_and_barrier<0>();
+        else if (fewer) wait_vm_and_barrier<(NSTAGE - 2) * NLD_FEWER>();
+        else wait_vm_and_barrier<(NSTAGE - 2) * NLD>();
     };
 
     const int KT = Kbytes / BKB;
@@ -250,8 +257,7 @@ void gemm_nt_kernel(const char *__restrict__ A, const char *__restrict__ W, char
 
     for (int kt = 0; kt < KT; kt++) {
         // stage kt must have landed: all but the loads of the (up to NSTAGE-2) later stages
-        if (kt + NSTAGE - 2 < KT) wait_vm_and_barrier<(NSTAGE - 2) * NLD>();
-        else wait_vm_and_barrier<0>();
+        wait_stage(kt + NSTAGE - 2 < KT);
         if (kt + NSTAGE - 1 < KT) issue(kt + NSTAGE - 1);        // refills the buffer consumed at kt-1
         const char *cur = lds + (kt % NSTAGE) * STAGE_BYTES;
 #pragma unroll
@@ -308,11 +314,11 @@ void gemm_nt_kernel(const char *__restrict__ A, const char *__restrict__ W, char
             }
         __syncthreads();
         constexpr int CHUNKS = BN * OB / 16;                      // 16-byte chunks per output row
-        constexpr int ROWS_PER_PASS = NT / CHUNKS;
-        const int orow = tid / CHUNKS, ochunk = tid % CHUNKS;
+        static_assert((BM * CHUNKS) % NT == 0, "output chunks must split evenly over the threads");
 #pragma unroll
-        for (int p = 0; p < BM / ROWS_PER_PASS; p++) {
-            const int lrow = p * ROWS_PER_PASS + orow;
+        for (int p = 0; p < BM * CHUNKS / NT; p++) {
+            const int idx = p * NT + tid;
+            const int lrow = idx / CHUNKS, ochunk = idx % CHUNKS;
             if (m0 + lrow < M) {
                 const v4i v = *reinterpret_cast<const v4i *>(lds + lrow * STRIDE + ochunk * 16);
                 *reinterpret_cast<v4i *>(out + ((size_t)(m0 + lrow) * N + n0) * OB + ochunk * 16) = v;
@@ -321,15 +327,15 @@ void gemm_nt_kernel(const char *__restrict__ A, const char *__restrict__ W, char
     }
 }
 
-template <class T, class Epi, int TM, int TN, int BKB, int NSTAGE, int WPE>
+template <class T, class Epi, int TM, int TN, int BKB, int NSTAGE, int WPE, int WGM = 2, int WGN = 2>
 hipError_t launch_cfg(const void *A, const void *W, void *out, const Epi &epi, Rows rows, int N, int K, hipStream_t st,
                       const Timing *tm)
 {
-    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int BM = 32 * WGM * TM, BN = 32 * WGN * TN;
     constexpr size_t LDS = (size_t)NSTAGE * (BM + BN) * BKB + (size_t)Epi::NTAB * BN * sizeof(float);
     if (N % BN) return hipErrorInvalidValue;
     if ((K * T::ELEM) % BKB) return hipErrorInvalidValue;
-    auto kern = gemm_nt_kernel<T, Epi, TM, TN, BKB, NSTAGE, WPE>;
+    auto kern = gemm_nt_kernel<T, Epi, TM, TN, BKB, NSTAGE, WPE, WGM, WGN>;
     // > 64 KiB of dynamic LDS must be enabled once per kernel; setting it twice from two threads is harmless
     static std::atomic<bool> attr_set{false};
     if (!attr_set.load(std::memory_order_acquire)) {
@@ -338,7 +344,7 @@ hipError_t launch_cfg(const void *A, const void *W, void *out, const Epi &epi, R
         attr_set.store(true, std::memory_order_release);
     }
     const int tiles_n = N / BN, tiles_m = (rows.host_rows + BM - 1) / BM, total = tiles_n * tiles_m;
-    launch_kernel(kern, dim3(total), dim3(256), LDS, st, tm,
+    launch_kernel(kern, dim3(total), dim3(64 * WGM * WGN), LDS, st, tm,
                           (const char *)A, (const char *)W, (char *)out, epi, rows.host_rows, rows.dev_rows, N, K * T::ELEM,
                           tiles_n);
     return hipGetLastError();
@@ -370,10 +376,18 @@ hipError_t launch(const void *A, const void *W, void *out, const Epi &epi, Rows 
         // for three resident blocks per CU, whose epilogues and main loops overlap (-3 % on the large forwards)
         if constexpr (std::is_same<Epi, EpiGeluQuant>::value) return launch_cfg<T, Epi, 2, 2, 64, 3, 3>(A, W, out, epi, rows, N, K, st, tm);
         else return launch_cfg<T, Epi, 2, 2, 128, 2, 2>(A, W, out, epi, rows, N, K, st, tm);
-    case 2:
-        if (K * T::ELEM >= LONG_K_BYTES && (long)(N / 128) * ((rows.host_rows + 63) / 64) <= 256)
-            return launch_cfg<T, Epi, 1, 2, 128, 3, 2>(A, W, out, epi, rows, N, K, st, tm);
+    case 2: {
+        const long row_tiles = (rows.host_rows + 63) / 64;
+        const bool long_k = K * T::ELEM >= LONG_K_BYTES;
+        // 64 x 96 tiles (six waves of 32 x 32) when they put the problem on more CUs without exceeding one block
+        // per CU: the rate at which one CU pulls operands is what bounds these small problems
+        if (gemm_config_override.load(std::memory_order_relaxed) < 0 && N % 96 == 0 && (N / 96) * row_tiles <= 256) {
+            if (long_k) return launch_cfg<T, Epi, 1, 1, 128, 3, 2, 2, 3>(A, W, out, epi, rows, N, K, st, tm);
+            return launch_cfg<T, Epi, 1, 1, 128, 2, 2, 2, 3>(A, W, out, epi, rows, N, K, st, tm);
+        }
+        if (long_k && (N / 128) * row_tiles <= 256) return launch_cfg<T, Epi, 1, 2, 128, 3, 2>(A, W, out, epi, rows, N, K, st, tm);
         return launch_cfg<T, Epi, 1, 2, 128, 2, 2>(A, W, out, epi, rows, N, K, st, tm);
+    }
     default: return launch_cfg<T, Epi, 2, 2, 64, 4, 2>(A, W, out, epi, rows, N, K, st, tm);
     }
 }

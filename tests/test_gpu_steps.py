@@ -79,10 +79,11 @@ def test_int8_gemm_requant_epilogue_bit_exact(P, M, N, K, with_bias):
     assert np.abs(want).max() == 127 and (np.abs(want) < 127).mean() > 0.5      # clamp and interior both hit
 
 
-@pytest.mark.parametrize("config", [0, 1, 2])
+@pytest.mark.parametrize("config", [-1, 0, 1, 2])
 def test_every_gemm_tile_configuration_gives_the_same_results(P, config):
     """The library picks a tile configuration by problem size; force each one in turn on a problem that
-    spans several tiles and a ragged last row tile, for all three INT8 epilogues and the FP16 GEMM."""
+    spans several tiles and a ragged last row tile, for all three INT8 epilogues and the FP16 GEMM.
+    Left to itself (-1) it takes 64 x 96 tiles of six waves here (384 channels, few tiles)."""
     rng = np.random.default_rng(77)
     M, N, K = 333, 384, 768
     A = rng.integers(-127, 128, (M, K), dtype=np.int8)
@@ -110,11 +111,13 @@ def test_every_gemm_tile_configuration_gives_the_same_results(P, config):
         P.set_gemm_config(3)
 
 
-def test_long_rows_with_few_tiles_take_the_deeper_ring(P):
+@pytest.mark.parametrize("N", [256, 384])
+def test_long_rows_with_few_tiles_take_the_deeper_ring(P, N):
     """Operand rows of 3072 bytes with at most one block per CU run through a 3-deep stage ring (FFN2 at small
-    batch): INT8 requantising GEMM bit-exact, FP16 GEMM within one ulp, ragged last row tile."""
-    rng = np.random.default_rng(91)
-    M, N, K = 300, 256, 3072
+    batch), in 64 x 128 tiles or, where the channel count allows it, 64 x 96 tiles whose six waves do not split the
+    stage loads evenly: INT8 requantising GEMM bit-exact, FP16 GEMM within one ulp, ragged last row tile."""
+    rng = np.random.default_rng(91 + N)
+    M, K = 300, 3072
     A = rng.integers(-127, 128, (M, K), dtype=np.int8)
     W = rng.integers(-127, 128, (N, K), dtype=np.int8)
     s_w, bias = _tables(rng, N)
