@@ -69,7 +69,10 @@ enum {
 };
 
 /* Supported shapes: head size hidden/heads == 64; hidden % 128 == 0; ffn % 128 == 0;
- * hidden <= 2048; 1 <= max_seq <= 512; max_batch >= 1.                                           */
+ * hidden <= 2048; 1 <= max_seq <= SAMP_MAX_SEQ; max_batch >= 1.  Up to 512 tokens a sequence's
+ * attention scores stay in registers; longer sequences take a three-sweep attention kernel that
+ * recomputes them (same results, about half the rate per token pair).                            */
+#define SAMP_MAX_SEQ 4096
 typedef struct {
     int32_t layers, hidden, heads, ffn, max_batch, max_seq;
     float ln_eps;
@@ -243,7 +246,7 @@ SAMP_API int samp_gemm_f16(const uint16_t *A, const uint16_t *W, const float *bi
 
 /* Softmax attention over packed rows.  qkv: dev [T,3H] (int8 or fp16), columns [0,H) Q, [H,2H) K,
  * [2H,3H) V.  cu_seqlens: dev int32 [B+1], sequence b owns rows cu[b]..cu[b+1); max_len >= every
- * length, <= 512.  INT8 flavour (Section 4.2 / Appendix B: quantised softmax output):
+ * length, <= SAMP_MAX_SEQ.  INT8 flavour (Section 4.2 / Appendix B: quantised softmax output):
  * score = float(q.k) * (s_q s_k / 8); P = softmax; Pq = rne(P / s_p) clamped to [-127, 127], or to
  * [0, 255] if p_unsigned != 0; ctx = rne(float(Pq.V) * s_p s_v / s_ctx).
  * p_hist: NULL, or dev uint64 [256] to which the kernel ADDS the number of times each code byte

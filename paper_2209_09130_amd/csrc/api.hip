@@ -67,7 +67,7 @@ int check_config(const samp_config_t *c)
     if (c->hidden != c->heads * 64) return fail(SAMP_ERR_SHAPE, "head size hidden/heads must be 64 (hidden=%d heads=%d)", c->hidden, c->heads);
     if (c->hidden % 128 || c->hidden > 2048) return fail(SAMP_ERR_SHAPE, "hidden must be a multiple of 128, at most 2048");
     if (c->ffn < 128 || c->ffn % 128) return fail(SAMP_ERR_SHAPE, "ffn must be a positive multiple of 128");
-    if (c->max_seq < 1 || c->max_seq > 512) return fail(SAMP_ERR_SHAPE, "max_seq must be in [1, 512]");
+    if (c->max_seq < 1 || c->max_seq > SAMP_MAX_SEQ) return fail(SAMP_ERR_SHAPE, "max_seq must be in [1, %d]", SAMP_MAX_SEQ);
     if (!(c->ln_eps >= 0.0f) || !std::isfinite(c->ln_eps)) return fail(SAMP_ERR_ARG, "ln_eps must be finite and >= 0");
     return SAMP_OK;
 }
@@ -672,7 +672,7 @@ int samp_gemm_f16(const uint16_t *A, const uint16_t *W, const float *bias, int32
 static int check_attention(const void *qkv, const int32_t *cu, int B, int max_len, int hidden, int heads, const void *ctx)
 {
     if (!qkv || !cu || !ctx) return fail(SAMP_ERR_ARG, "NULL pointer");
-    if (B < 1 || max_len < 1 || max_len > 512) return fail(SAMP_ERR_SHAPE, "B >= 1 and 1 <= max_len <= 512 required");
+    if (B < 1 || max_len < 1 || max_len > SAMP_MAX_SEQ) return fail(SAMP_ERR_SHAPE, "B >= 1 and 1 <= max_len <= %d required", SAMP_MAX_SEQ);
     if (heads < 1 || hidden != heads * 64) return fail(SAMP_ERR_SHAPE, "head size must be 64");
     if (!aligned(qkv, 16) || !aligned(ctx, 16)) return fail(SAMP_ERR_ARG, "tensors must be 16-byte aligned");
     return SAMP_OK;

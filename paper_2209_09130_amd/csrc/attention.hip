@@ -5,7 +5,8 @@
 //     score = float(q.k) * m_sc;  P = softmax(score);  Pq = rne(P / s_p);  ctx = rne(float(Pq.V) * m_ctx)
 // Because the step of P is static, P must be fully normalised before it is rounded: a block keeps
 // a whole strip of scores on chip (32 queries x all keys of the sequence, <= 512), so the scores
-// never touch memory and no running rescale is needed.
+// never touch memory and no running rescale is needed.  Longer sequences take the three-sweep
+// kernels further down, which recompute the scores instead of keeping them.
 //
 // One block = (sequence, head, 32 queries), 4 waves; wave w owns key tiles w, w+4, ... (32 keys
 // each).  S^T = K.Q^T is computed so that in the 32x32 MFMA result a lane holds ONE query and 16
@@ -21,6 +22,7 @@ namespace samp {
 namespace {
 
 constexpr int QB = 32;                 // queries per block
+constexpr int ONE_PASS_MAX_LEN = 512;  // longest sequence whose score strip stays in registers
 constexpr int VT_STRIDE_I8 = 36;       // bytes per V^T row (32 keys + pad), int8
 constexpr int VT_STRIDE_F16 = 72;      // bytes per V^T row (32 keys + pad), fp16
 
@@ -357,6 +359,280 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const __half *__rest
     }
 }
 
+
+// ---- sequences longer than 512 keys: the same arithmetic as above, tile by tile ---------------------
+// A strip of 32 x n scores no longer fits the registers, so the kernels below sweep the key tiles three
+// times: row maxima, row sums, then codes and P.V.  The integer products q.k are recomputed in each
+// sweep (two MFMAs per 32 x 32 tile; exact, so all sweeps see the same scores), the exponentials in the
+// last two.  A wave still owns key tiles w, w+4, ... and visits them in ascending order, so every
+// binary32 / binary64 operation happens in the same order as in the one-pass kernels.
+
+// scores of key tile j0 for the lane's query: sc[e] belongs to key j0 + 8 (e >> 2) + 4 g + (e & 3)
+__device__ __forceinline__ void score_tile_i8(const int8_t *base, unsigned ld, int H, int j0, int n, int r, int g,
+                                              const v4i (&qf)[2], float m_sc, float (&sc)[16])
+{
+    const int8_t *kp = base + (unsigned)min(j0 + r, n - 1) * ld + H;
+    v16i acc;
+#pragma unroll
+    for (int e = 0; e < 16; e++) acc[e] = 0;
+#pragma unroll
+    for (int ks = 0; ks < 2; ks++)
+        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(*reinterpret_cast<const v4i *>(kp + ks * 32 + g * 16), qf[ks], acc, 0, 0, 0);
+#pragma unroll
+    for (int e = 0; e < 16; e++) {
+        const int key = j0 + 8 * (e >> 2) + 4 * g + (e & 3);
+        sc[e] = key < n ? (float)acc[e] * m_sc : -INFINITY;
+    }
+}
+
+template <bool PU, bool HIST>
+__global__ __launch_bounds__(256) void attention_i8_long_kernel(const int8_t *__restrict__ qkv, const int *__restrict__ cu,
+                                                                int max_len, int H, float m_sc, float inv_sp, float m_ctx,
+                                                                int8_t *__restrict__ ctx, unsigned long long *__restrict__ p_hist)
+{
+    __shared__ unsigned hist[HIST ? 256 : 1];
+    __shared__ __attribute__((aligned(16))) int8_t vt[4][64 * VT_STRIDE_I8];
+    __shared__ __attribute__((aligned(16))) int so[4][QB][64];
+    __shared__ float smax[4][QB];
+    __shared__ double ssum[4][QB];
+
+    const int nqb = (max_len + QB - 1) / QB, heads = H >> 6;
+    const int item = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int seq = item / (nqb * heads), head = (item / nqb) % heads;
+    const SeqInfo sq = seq_info(cu, seq, max_len);
+    const int q0 = (item % nqb) * QB;
+    if (q0 >= sq.n) return;
+    const int n = sq.n;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, g = lane >> 5;
+    const unsigned ld = 3u * (unsigned)H;
+    const int8_t *base = qkv + (size_t)sq.t0 * ld + head * 64;
+    if (HIST) hist[tid] = 0;
+
+    const int qrow = min(q0 + r, n - 1);
+    v4i qf[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ks++) qf[ks] = *reinterpret_cast<const v4i *>(base + (unsigned)qrow * ld + ks * 32 + g * 16);
+
+    float sc[16];
+    float mx = -INFINITY;
+    for (int j0 = w * 32; j0 < n; j0 += 128) {
+        score_tile_i8(base, ld, H, j0, n, r, g, qf, m_sc, sc);
+#pragma unroll
+        for (int e = 0; e < 16; e++) mx = __builtin_fmaxf(mx, sc[e]);
+    }
+    mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32, 64));
+    if (g == 0) smax[w][r] = mx;
+    __syncthreads();
+    mx = __builtin_fmaxf(__builtin_fmaxf(smax[0][r], smax[1][r]), __builtin_fmaxf(smax[2][r], smax[3][r]));
+
+    double part = 0.0;
+    for (int j0 = w * 32; j0 < n; j0 += 128) {
+        score_tile_i8(base, ld, H, j0, n, r, g, qf, m_sc, sc);
+#pragma unroll
+        for (int e = 0; e < 16; e++) part += (double)(float)exp_nonpos((double)__builtin_fmaxf(sc[e] - mx, -746.0f));
+    }
+    part += __shfl_xor(part, 32, 64);
+    if (g == 0) ssum[w][r] = part;
+    __syncthreads();
+    const float S = (float)(((ssum[0][r] + ssum[1][r]) + ssum[2][r]) + ssum[3][r]);
+    const float rS = __fdiv_rn(1.0f, S);
+
+    v16i o[2], o1[PU ? 2 : 1];
+#pragma unroll
+    for (int cb = 0; cb < 2; cb++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) { o[cb][e] = 0; if (PU) o1[cb][e] = 0; }
+    const float lo = PU ? 0.0f : -127.0f, hi = PU ? 255.0f : 127.0f;
+    const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
+    const int8_t *vp = base + 2 * H;
+    for (int j0 = w * 32; j0 < n; j0 += 128) {
+        score_tile_i8(base, ld, H, j0, n, r, g, qf, m_sc, sc);
+        // V^T of this key tile into the wave's own LDS slab (4 keys x 4 channels byte blocks transposed in
+        // registers); the slab is written and read by this wave only, in program order
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int u = 0; u < 2; u++) {
+            const int cq = lane & 15, kq = (lane >> 4) + 4 * u;
+            unsigned d[4];
+#pragma unroll
+            for (int t = 0; t < 4; t++)
+                d[t] = *reinterpret_cast<const unsigned *>(vp + (unsigned)min(j0 + 4 * kq + t, n - 1) * ld + 4 * cq);
+            const unsigned t01l = __builtin_amdgcn_perm(d[1], d[0], 0x05010400u), t23l = __builtin_amdgcn_perm(d[3], d[2], 0x05010400u);
+            const unsigned t01h = __builtin_amdgcn_perm(d[1], d[0], 0x07030602u), t23h = __builtin_amdgcn_perm(d[3], d[2], 0x07030602u);
+            unsigned *dst = reinterpret_cast<unsigned *>(&vt[w][(4 * cq) * VT_STRIDE_I8 + 4 * kq]);
+            dst[0 * (VT_STRIDE_I8 / 4)] = __builtin_amdgcn_perm(t23l, t01l, 0x05040100u);
+            dst[1 * (VT_STRIDE_I8 / 4)] = __builtin_amdgcn_perm(t23l, t01l, 0x07060302u);
+            dst[2 * (VT_STRIDE_I8 / 4)] = __builtin_amdgcn_perm(t23h, t01h, 0x05040100u);
+            dst[3 * (VT_STRIDE_I8 / 4)] = __builtin_amdgcn_perm(t23h, t01h, 0x07060302u);
+        }
+        __builtin_amdgcn_wave_barrier();
+        v4i pf;
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+            float f[4];
+#pragma unroll
+            for (int t = 0; t < 4; t++) {
+                const float ev = (float)exp_nonpos((double)__builtin_fmaxf(sc[4 * q + t] - mx, -746.0f));
+                f[t] = __builtin_amdgcn_fmed3f((ev * rS) * inv_sp, lo, hi) + SAMP_RNE_MAGIC;
+                if (HIST && q0 + r < n && j0 + 8 * q + 4 * g + t < n) atomicAdd(&hist[__float_as_uint(f[t]) & 0xffu], 1u);
+            }
+            pf[q] = pack_codes(f[0], f[1], f[2], f[3]);
+            if (PU) pf[q] ^= (int)0x80808080u;
+        }
+#pragma unroll
+        for (int cb = 0; cb < 2; cb++) {
+            v4i vf;
+#pragma unroll
+            for (int q = 0; q < 4; q++)
+                vf[q] = *reinterpret_cast<const int *>(&vt[w][(cb * 32 + r) * VT_STRIDE_I8 + 8 * q + 4 * g]);
+            o[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(pf, vf, o[cb], 0, 0, 0);
+            if (PU) o1[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ones, vf, o1[cb], 0, 0, 0);
+        }
+    }
+    if (PU) {
+#pragma unroll
+        for (int cb = 0; cb < 2; cb++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) o[cb][e] += o1[cb][e] * 128;
+    }
+#pragma unroll
+    for (int cb = 0; cb < 2; cb++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) so[w][8 * (e >> 2) + 4 * g + (e & 3)][cb * 32 + r] = o[cb][e];
+    __syncthreads();
+
+    const int query = tid >> 3, c0 = (tid & 7) * 8;
+    if (q0 + query < n) {
+        int codes[8];
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+            const int O = ((so[0][query][c0 + e] + so[1][query][c0 + e]) + so[2][query][c0 + e]) + so[3][query][c0 + e];
+            codes[e] = qcode((float)O * m_ctx);
+        }
+        v2i pk = {pack4(codes[0], codes[1], codes[2], codes[3]), pack4(codes[4], codes[5], codes[6], codes[7])};
+        *reinterpret_cast<v2i *>(ctx + (size_t)(sq.t0 + q0 + query) * H + head * 64 + c0) = pk;
+    }
+    if (HIST && hist[tid]) atomicAdd(&p_hist[tid], (unsigned long long)hist[tid]);
+}
+
+__device__ __forceinline__ void score_tile_f16(const __half *base, unsigned ld, int H, int j0, int n, int r, int g,
+                                               const v8h (&qf)[4], float scale, float (&sc)[16])
+{
+    const __half *kp = base + (unsigned)min(j0 + r, n - 1) * ld + H;
+    v16f acc;
+#pragma unroll
+    for (int e = 0; e < 16; e++) acc[e] = 0.0f;
+#pragma unroll
+    for (int ks = 0; ks < 4; ks++)
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(*reinterpret_cast<const v8h *>(kp + ks * 16 + g * 8), qf[ks], acc, 0, 0, 0);
+#pragma unroll
+    for (int e = 0; e < 16; e++) {
+        const int key = j0 + 8 * (e >> 2) + 4 * g + (e & 3);
+        sc[e] = key < n ? acc[e] * scale : -INFINITY;
+    }
+}
+
+__global__ __launch_bounds__(256) void attention_f16_long_kernel(const __half *__restrict__ qkv, const int *__restrict__ cu,
+                                                                 int max_len, int H, float scale, __half *__restrict__ ctx,
+                                                                 float *__restrict__ p_absmax)
+{
+    __shared__ __attribute__((aligned(16))) char vt[4][64 * VT_STRIDE_F16];
+    __shared__ __attribute__((aligned(16))) float so[4][QB][64];
+    __shared__ float smax[4][QB];
+    __shared__ float ssum[4][QB];
+
+    const int nqb = (max_len + QB - 1) / QB, heads = H >> 6;
+    const int item = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int seq = item / (nqb * heads), head = (item / nqb) % heads;
+    const SeqInfo sq = seq_info(cu, seq, max_len);
+    const int q0 = (item % nqb) * QB;
+    if (q0 >= sq.n) return;
+    const int n = sq.n;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, g = lane >> 5;
+    const unsigned ld = 3u * (unsigned)H;
+    const __half *base = qkv + (size_t)sq.t0 * ld + head * 64;
+
+    const int qrow = min(q0 + r, n - 1);
+    v8h qf[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ks++) qf[ks] = *reinterpret_cast<const v8h *>(base + (unsigned)qrow * ld + ks * 16 + g * 8);
+
+    float sc[16];
+    float mx = -INFINITY;
+    for (int j0 = w * 32; j0 < n; j0 += 128) {
+        score_tile_f16(base, ld, H, j0, n, r, g, qf, scale, sc);
+#pragma unroll
+        for (int e = 0; e < 16; e++) mx = __builtin_fmaxf(mx, sc[e]);
+    }
+    mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32, 64));
+    if (g == 0) smax[w][r] = mx;
+    __syncthreads();
+    mx = __builtin_fmaxf(__builtin_fmaxf(smax[0][r], smax[1][r]), __builtin_fmaxf(smax[2][r], smax[3][r]));
+
+    float part = 0.0f;
+    for (int j0 = w * 32; j0 < n; j0 += 128) {
+        score_tile_f16(base, ld, H, j0, n, r, g, qf, scale, sc);
+#pragma unroll
+        for (int e = 0; e < 16; e++) part += __builtin_amdgcn_exp2f((sc[e] - mx) * 1.44269504088896341f);
+    }
+    part += __shfl_xor(part, 32, 64);
+    if (g == 0) ssum[w][r] = part;
+    __syncthreads();
+    const float S = ((ssum[0][r] + ssum[1][r]) + ssum[2][r]) + ssum[3][r];
+    const float rS = __fdiv_rn(1.0f, S);
+    if (p_absmax && w == 0 && g == 0 && q0 + r < n)
+        atomicMax(reinterpret_cast<int *>(p_absmax), __float_as_int((float)(_Float16)rS));
+
+    v16f o[2];
+#pragma unroll
+    for (int cb = 0; cb < 2; cb++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) o[cb][e] = 0.0f;
+    const __half *vp = base + 2 * H;
+    for (int j0 = w * 32; j0 < n; j0 += 128) {
+        score_tile_f16(base, ld, H, j0, n, r, g, qf, scale, sc);
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            const int idx = lane + 64 * u, key = idx >> 3, c0 = (idx & 7) * 8;
+            const v8h v = *reinterpret_cast<const v8h *>(vp + (unsigned)min(j0 + key, n - 1) * ld + c0);
+#pragma unroll
+            for (int e = 0; e < 8; e++)
+                *reinterpret_cast<_Float16 *>(&vt[w][(c0 + e) * VT_STRIDE_F16 + key * 2]) = v[e];
+        }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int hf = 0; hf < 2; hf++) {
+            v8h pf;
+#pragma unroll
+            for (int e = 0; e < 8; e++)
+                pf[e] = to_half(__builtin_amdgcn_exp2f((sc[8 * hf + e] - mx) * 1.44269504088896341f) * rS);
+#pragma unroll
+            for (int cb = 0; cb < 2; cb++) {
+                const char *rowp = &vt[w][(cb * 32 + r) * VT_STRIDE_F16];
+                const v4h lo = *reinterpret_cast<const v4h *>(rowp + (16 * hf + 4 * g) * 2);
+                const v4h hi = *reinterpret_cast<const v4h *>(rowp + (16 * hf + 8 + 4 * g) * 2);
+                const v8h vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(pf, vf, o[cb], 0, 0, 0);
+            }
+        }
+    }
+#pragma unroll
+    for (int cb = 0; cb < 2; cb++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) so[w][8 * (e >> 2) + 4 * g + (e & 3)][cb * 32 + r] = o[cb][e];
+    __syncthreads();
+
+    const int query = tid >> 3, c0 = (tid & 7) * 8;
+    if (q0 + query < n) {
+        v8h outv;
+#pragma unroll
+        for (int e = 0; e < 8; e++)
+            outv[e] = to_half(((so[0][query][c0 + e] + so[1][query][c0 + e]) + so[2][query][c0 + e]) + so[3][query][c0 + e]);
+        *reinterpret_cast<v8h *>(ctx + (size_t)(sq.t0 + q0 + query) * H + head * 64 + c0) = outv;
+    }
+}
+
 }  // namespace
 
 template <bool PU, bool HIST>
@@ -369,8 +645,10 @@ static void launch_attention_i8_variant(const int8_t *qkv, const int *cu, int B,
         launch_kernel(attention_i8_kernel<1, PU, HIST>, grid, block, 0, st, tm, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx, p_hist);
     else if (max_len <= 256)
         launch_kernel(attention_i8_kernel<2, PU, HIST>, grid, block, 0, st, tm, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx, p_hist);
-    else
+    else if (max_len <= ONE_PASS_MAX_LEN)
         launch_kernel(attention_i8_kernel<4, PU, HIST>, grid, block, 0, st, tm, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx, p_hist);
+    else
+        launch_kernel(attention_i8_long_kernel<PU, HIST>, grid, block, 0, st, tm, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx, p_hist);
 }
 
 hipError_t launch_attention_i8(const int8_t *qkv, const int *cu, int B, int max_len, int H, int heads, float m_sc,
@@ -395,8 +673,10 @@ hipError_t launch_attention_f16(const __half *qkv, const int *cu, int B, int max
         launch_kernel(attention_f16_kernel<1>, grid, block, 0, st, tm, qkv, cu, max_len, H, scale, ctx, p_absmax);
     else if (max_len <= 256)
         launch_kernel(attention_f16_kernel<2>, grid, block, 0, st, tm, qkv, cu, max_len, H, scale, ctx, p_absmax);
-    else
+    else if (max_len <= ONE_PASS_MAX_LEN)
         launch_kernel(attention_f16_kernel<4>, grid, block, 0, st, tm, qkv, cu, max_len, H, scale, ctx, p_absmax);
+    else
+        launch_kernel(attention_f16_long_kernel, grid, block, 0, st, tm, qkv, cu, max_len, H, scale, ctx, p_absmax);
     return hipGetLastError();
 }
 

@@ -47,8 +47,11 @@ def test_invalid_arguments_become_error_codes_on_the_host(L):
     bad_head = _Config(2, 768, 8, 3072, 8, 128, 1e-12)
     assert L.samp_encoder_arena_bytes(C.byref(bad_head), modes) == 0
     assert b"head size" in L.samp_last_error()
-    bad_seq = _Config(2, 768, 12, 3072, 8, 1024, 1e-12)
+    long_seq = _Config(2, 768, 12, 3072, 8, 4096, 1e-12)
+    assert L.samp_encoder_arena_bytes(C.byref(long_seq), modes) > 0
+    bad_seq = _Config(2, 768, 12, 3072, 8, 4097, 1e-12)
     assert L.samp_encoder_arena_bytes(C.byref(bad_seq), modes) == 0
+    assert b"max_seq" in L.samp_last_error()
     assert L.samp_encoder_arena_bytes(C.byref(ok), (C.c_uint8 * 2)(8, 0)) == 0
     assert L.samp_encoder_arena_bytes(C.byref(ok), (C.c_uint8 * 2)(6, 0)) == 0       # unsigned softmax codes need an INT8 MHA
     assert L.samp_encoder_arena_bytes(C.byref(ok), (C.c_uint8 * 2)(7, 5)) > 0

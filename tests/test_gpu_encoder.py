@@ -386,6 +386,26 @@ def test_random_small_configurations(P, seed):
         assert (d == 0).all()
 
 
+@pytest.mark.parametrize("modes", [(FULL_INT8, FULL_INT8 | P_UNSIGNED), (FP16, MHA_INT8), (FFN_INT8, FP16)])
+def test_encoder_with_sequences_longer_than_512_tokens(P, modes):
+    """Rows of up to 700 tokens (with padding: lengths 520..700): attention runs in the three-sweep kernels, every
+    other kernel is indifferent to the length.  Fully-Quant stays bit-identical to the oracle."""
+    w = W.Workload("long", 2, 128, 2, 256, 3, 700, tuple(modes), varlen=True, min_len=520, plain_params=False,
+                   calib_batch=2, calib_seq=600)
+    wts = W.make_weights(w)
+    hid, lens, mask = W.make_hidden(w)
+    sc = oracle.calibrate(*args(w), wts, W.make_calibration_batch(w))
+    for l, m in enumerate(modes):
+        if m & P_UNSIGNED:
+            sc[l, 4] = np.float32(sc[l, 4] * np.float32(127.0 / 255.0))
+    want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid, lens)
+    got = run_gpu(P, w, wts, sc, hid, mask)
+    exact = all((m & 3) == FULL_INT8 for m in modes)
+    d = compare(got, want, lens, exact, f"long rows {modes}")
+    if exact:
+        assert (d == 0).all()
+
+
 def test_gpu_calibration_matches_the_oracle_calibration(P):
     import torch
     w = W.config("C1").with_modes(FP16)

@@ -297,6 +297,52 @@ def test_fp16_attention_within_tolerance(P, lens, heads):
     assert np.abs(got - want).mean() <= 1e-4
 
 
+@pytest.mark.parametrize("lens,heads", [([513], 1), ([700, 31, 1024], 2), ([2048, 515], 1)])
+def test_long_sequence_attention_matches_the_oracle(P, lens, heads):
+    """More than 512 keys: the three-sweep kernels (row maxima, row sums, codes and P.V, recomputing the integer
+    scores each time) must give what the oracle's plain definition gives: int8 contexts bit-exact for signed and
+    unsigned softmax codes, the code histogram exact, the fp16 flavour within its tolerance."""
+    rng = np.random.default_rng(sum(lens) + 9)
+    H = heads * 64
+    cu = _cu(lens)
+    qkv = np.clip(np.rint(rng.standard_normal((int(cu[-1]), 3 * H)) * 26), -127, 127).astype(np.int8)
+    for p_unsigned, sc in ((False, (0.0209, 0.0249, 0.021, 0.0003, 0.0021)), (True, (0.03, 0.03, 0.021, 0.0004, 0.0012)),
+                           (False, (0.05, 0.05, 0.021, 0.004, 0.006))):
+        want = oracle.attention_i8(qkv, cu, heads, *sc, p_unsigned=p_unsigned)
+        got, hist = P.attention_i8(dev(qkv), dev(cu), max(lens), heads, *sc, p_unsigned=p_unsigned, want_hist=True)
+        assert np.array_equal(host(got), want)
+        assert np.abs(want).max() > 10
+        assert int(host(hist).sum()) == heads * sum(n * n for n in lens)
+        plain = P.attention_i8(dev(qkv), dev(cu), max(lens), heads, *sc, p_unsigned=p_unsigned)
+        assert np.array_equal(host(plain), want)
+    b = len(lens) - 1                                         # code usage of the last sequence against the oracle's dump
+    sl = slice(cu[b], cu[b + 1])
+    sc = (0.03, 0.03, 0.021, 0.0004, 0.0012)
+    one = np.array([0, lens[b]], np.int32)
+    _, Pq = oracle.attention_i8(qkv[sl], one, heads, *sc, dump_p=True, p_unsigned=True)
+    _, hist = P.attention_i8(dev(qkv[sl]), dev(one), lens[b], heads, *sc, p_unsigned=True, want_hist=True)
+    assert np.array_equal(host(hist), np.bincount(Pq.view(np.uint8).ravel(), minlength=256))
+    f = (rng.standard_normal((int(cu[-1]), 3 * H)) * 0.6).astype(np.float16)
+    want = oracle.attention_f16(f, cu, heads).astype(np.float64)
+    got = host(P.attention_f16(dev(f), dev(cu), max(lens), heads)).astype(np.float64)
+    assert np.abs(got - want).max() <= 2e-3
+    assert np.abs(got - want).mean() <= 1e-4
+
+
+def test_long_kernel_equals_one_pass_kernel_on_short_sequences(P):
+    """A batch whose longest row exceeds 512 tokens runs every sequence, also the short ones, through the three-sweep
+    kernel: their contexts must be the bytes the one-pass kernel writes when the same short sequences come alone."""
+    rng = np.random.default_rng(77)
+    heads, lens = 2, [600, 128, 37, 512]
+    H = heads * 64
+    cu = _cu(lens)
+    qkv = np.clip(np.rint(rng.standard_normal((int(cu[-1]), 3 * H)) * 26), -127, 127).astype(np.int8)
+    sc = (0.0209, 0.0249, 0.021, 0.0003, 0.0021)
+    mixed = host(P.attention_i8(dev(qkv), dev(cu), max(lens), heads, *sc))
+    short = host(P.attention_i8(dev(qkv[cu[1]:]), dev(_cu(lens[1:])), 512, heads, *sc))
+    assert np.array_equal(mixed[cu[1]:], short)
+
+
 # ------------------------------------------------------------------ fused bias + residual + LayerNorm (+ quant)
 @pytest.mark.parametrize("H", [128, 768, 1024])
 @pytest.mark.parametrize("in8,res8,out8", [(1, 1, 1), (1, 1, 0), (0, 0, 1), (0, 0, 0), (1, 0, 1), (0, 1, 0)])
