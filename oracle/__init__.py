@@ -193,6 +193,18 @@ def attention_i8(qkv: np.ndarray, cu: np.ndarray, heads: int, s_q, s_k, s_v, s_p
     return (ctx, pd) if dump_p else ctx
 
 
+def attention_i8_p16(qkv: np.ndarray, cu: np.ndarray, heads: int, s_q, s_k, s_v, s_ctx) -> np.ndarray:
+    """INT8 attention block whose softmax output stays in binary16 (no step s_p): int8 context [T, H]."""
+    qkv = np.ascontiguousarray(qkv, np.int8)
+    cu = np.ascontiguousarray(cu, np.int32)
+    T, H3 = qkv.shape
+    H = H3 // 3
+    ctx = np.zeros((T, H), np.int8)
+    lib().orc_attention_i8_p16(_p(qkv), _p(cu), cu.size - 1, H, heads, C.c_float(s_q), C.c_float(s_k), C.c_float(s_v),
+                               C.c_float(s_ctx), _p(ctx))
+    return ctx
+
+
 def attention_f16(qkv: np.ndarray, cu: np.ndarray, heads: int) -> np.ndarray:
     qkv = _f16(qkv)
     cu = np.ascontiguousarray(cu, np.int32)
@@ -286,7 +298,8 @@ def _config(layers, hidden, heads, ffn, ln_eps):
 
 
 class Encoder:
-    """The mixed-precision encoder of Section 3.2 on the CPU.  modes[l]: bit0 = MHA INT8, bit1 = FFN INT8."""
+    """The mixed-precision encoder of Section 3.2 on the CPU.  modes[l]: bit0 = MHA INT8, bit1 = FFN INT8; with bit0, bit2 = unsigned
+    softmax codes or bit3 = binary16 softmax output."""
 
     def __init__(self, layers, hidden, heads, ffn, ln_eps, modes, weights, scales):
         self.cfg = _config(layers, hidden, heads, ffn, ln_eps)

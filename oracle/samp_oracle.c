@@ -45,7 +45,8 @@
 #define ORC_API __attribute__((visibility("default")))
 
 enum { ORC_MHA_INT8 = 1, ORC_FFN_INT8 = 2,
-       ORC_P_UNSIGNED = 4 };   /* with ORC_MHA_INT8: softmax codes 0..255 instead of the symmetric range */
+       ORC_P_UNSIGNED = 4,     /* with ORC_MHA_INT8: softmax codes 0..255 instead of the symmetric range */
+       ORC_P_FP16 = 8 };       /* with ORC_MHA_INT8, not with ORC_P_UNSIGNED: the softmax output stays binary16 */
 
 /* ------------------------------------------------------------------------ */
 /* binary16 <-> binary32 (IEEE 754, round to nearest even)                   */
@@ -284,6 +285,47 @@ ORC_API void orc_attention_i8(const int8_t *qkv, const int32_t *cu, int B, int H
                 }
             }
         free(sc); free(e); free(pq);
+    }
+}
+
+/* INT8 attention block whose softmax output is NOT put on the 8-bit grid (the
+ * other way out of the problem Section 4.2 / Appendix B describe: a softmax
+ * output wastes most of a symmetric int8 code): scores from integers exactly
+ * as above; the normalised value is rounded to binary16 and multiplies the
+ * integer V codes:
+ *   P16 = fl16(e[j] * rS);  ctx = rne(fl32(sum_j P16[j] * V[j]) * m),  m = s_v / s_ctx.
+ * Every P16 is an integer multiple of 2^-24 not above 1 and V an integer below
+ * 2^7, so each product and every partial sum (below 2^53 * 2^-24 for any row
+ * length here) is exact in binary64: fl32 rounds the true sum once.            */
+ORC_API void orc_attention_i8_p16(const int8_t *qkv, const int32_t *cu, int B, int H, int heads,
+                                  float s_q, float s_k, float s_v, float s_ctx, int8_t *ctx)
+{
+    int d = H / heads;
+    float m_sc = (float)((double)s_q * (double)s_k / sqrt((double)d));
+    float m = (float)((double)s_v / (double)s_ctx);
+    for (int b = 0; b < B; b++) {
+        int t0 = cu[b], n = cu[b + 1] - cu[b];
+        float *sc = (float *)malloc(sizeof(float) * n), *e = (float *)malloc(sizeof(float) * n);
+        double *p = (double *)malloc(sizeof(double) * n);
+        for (int h = 0; h < heads; h++)
+            for (int i = 0; i < n; i++) {
+                const int8_t *q = qkv + (size_t)(t0 + i) * 3 * H + h * d;
+                for (int j = 0; j < n; j++) {
+                    const int8_t *k = qkv + (size_t)(t0 + j) * 3 * H + H + h * d;
+                    int32_t acc = 0;
+                    for (int c = 0; c < d; c++) acc += (int32_t)q[c] * (int32_t)k[c];
+                    sc[j] = (float)acc * m_sc;
+                }
+                float rS = softmax_row(sc, n, e);
+                for (int j = 0; j < n; j++) p[j] = (double)h2f(f2h(e[j] * rS));
+                for (int c = 0; c < d; c++) {
+                    double O = 0.0;
+                    for (int j = 0; j < n; j++)
+                        O += p[j] * (double)qkv[(size_t)(t0 + j) * 3 * H + 2 * H + h * d + c];
+                    ctx[(size_t)(t0 + i) * H + h * d + c] = qcode((float)O * m);
+                }
+            }
+        free(sc); free(e); free(p);
     }
 }
 
@@ -598,7 +640,10 @@ static void forward_sequence(const orc_encoder *E, const uint16_t *hidden, const
         if (mha8) {
             gemm_i8_t((const int8_t *)x, Y->qkv_t, acc, n, 3 * H, H);
             orc_epilogue_requant(acc, n, 3 * H, Y->m_qkv, Y->b_qkv_q, (int8_t *)qkv);
-            orc_attention_i8((const int8_t *)qkv, cu, 1, H, heads, s->q, s->k, s->v, s->p, s->ctx, pu, (int8_t *)ctx, NULL);
+            if (Y->mode & ORC_P_FP16)
+                orc_attention_i8_p16((const int8_t *)qkv, cu, 1, H, heads, s->q, s->k, s->v, s->ctx, (int8_t *)ctx);
+            else
+                orc_attention_i8((const int8_t *)qkv, cu, 1, H, heads, s->q, s->k, s->v, s->p, s->ctx, pu, (int8_t *)ctx, NULL);
             gemm_i8_t((const int8_t *)ctx, Y->o_t, acc, n, H, H);
             orc_epilogue_requant(acc, n, H, Y->m_o, Y->zero_h, (int8_t *)ao);
         } else {

@@ -19,8 +19,10 @@ import numpy as np
 # per-layer precision mode: bit0 = attention block INT8, bit1 = feed-forward block INT8
 FP16, MHA_INT8, FFN_INT8, FULL_INT8 = 0, 1, 2, 3
 P_UNSIGNED = 4          # flag on top of MHA_INT8 / FULL_INT8: softmax codes 0..255 instead of the symmetric range
+P_FP16 = 8              # flag on top of MHA_INT8 / FULL_INT8 (not with P_UNSIGNED): the softmax output stays binary16
 MODE_NAMES = {FP16: "FP16", MHA_INT8: "MHA_INT8", FFN_INT8: "FFN_INT8", FULL_INT8: "FULL_INT8",
-              MHA_INT8 | P_UNSIGNED: "MHA_INT8+PU", FULL_INT8 | P_UNSIGNED: "FULL_INT8+PU"}
+              MHA_INT8 | P_UNSIGNED: "MHA_INT8+PU", FULL_INT8 | P_UNSIGNED: "FULL_INT8+PU",
+              MHA_INT8 | P_FP16: "MHA_INT8+P16", FULL_INT8 | P_FP16: "FULL_INT8+P16"}
 
 
 @dataclass(frozen=True)

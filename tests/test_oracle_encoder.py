@@ -12,7 +12,7 @@ import pytest
 
 import oracle
 import samp_workloads as W
-from samp_workloads import FP16, MHA_INT8, FFN_INT8, FULL_INT8, P_UNSIGNED
+from samp_workloads import FP16, MHA_INT8, FFN_INT8, FULL_INT8, P_UNSIGNED, P_FP16
 
 
 def small(layers=2, modes=FULL_INT8, batch=3, seq=24, varlen=True, **kw):
@@ -134,7 +134,10 @@ def _replay_layer(t, lw, s, mode, heads, eps, next_sx):
             sl = slice(part * H, (part + 1) * H)
             m[sl], b[sl] = oracle.fold_requant(sx, sw[sl], lw["b_qkv"][sl], so)
         out["qkv"] = oracle.epilogue_requant(oracle.gemm_i8_i32(x, Wq), m, b)
-        out["ctx"] = oracle.attention_i8(out["qkv"], cu, heads, sq, sk, sv, sp, sctx, p_unsigned=bool(mode & 4))
+        if mode & P_FP16:
+            out["ctx"] = oracle.attention_i8_p16(out["qkv"], cu, heads, sq, sk, sv, sctx)
+        else:
+            out["ctx"] = oracle.attention_i8(out["qkv"], cu, heads, sq, sk, sv, sp, sctx, p_unsigned=bool(mode & 4))
         Wq, sw = oracle.quantize_weight(lw["w_o"])
         m, b = oracle.fold_requant(sctx, sw, None, sao)
         out["attn_out"] = oracle.epilogue_requant(oracle.gemm_i8_i32(out["ctx"], Wq), m, b)
@@ -163,7 +166,8 @@ def _replay_layer(t, lw, s, mode, heads, eps, next_sx):
 @pytest.mark.parametrize("modes", [(FULL_INT8, FULL_INT8), (FFN_INT8, FFN_INT8), (MHA_INT8, MHA_INT8),
                                    (FP16, FP16), (FP16, FULL_INT8), (FULL_INT8, FP16), (FFN_INT8, MHA_INT8),
                                    (MHA_INT8, FFN_INT8), (FULL_INT8 | P_UNSIGNED, MHA_INT8 | P_UNSIGNED),
-                                   (FULL_INT8, FULL_INT8 | P_UNSIGNED)])
+                                   (FULL_INT8, FULL_INT8 | P_UNSIGNED), (FULL_INT8 | P_FP16, MHA_INT8 | P_FP16),
+                                   (FP16, FULL_INT8 | P_FP16)])
 def test_every_mode_is_wired_as_section_3_2_says(modes):
     w = small(layers=2, modes=modes, batch=1)
     wts, hid, lens, sc = make(w)

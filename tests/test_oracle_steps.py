@@ -428,6 +428,71 @@ def test_int8_attention_unsigned_softmax_codes():
     assert P1.shape == (heads, 1, 1) and (P1 == 255).all()
 
 
+def test_int8_attention_with_binary16_softmax_output():
+    """The variant that keeps the softmax output out of the 8-bit grid (Section 4.2 / Appendix B name its quantisation
+    as the accuracy problem of a fully quantised attention block): P is rounded to binary16, V stays integer codes.
+    Pins: brute force through float64 probabilities rounded by numpy to float16 and summed in exact integer arithmetic;
+    closed forms (one key; identical keys with a power-of-two and a non-power-of-two count); the error against the
+    unrounded context must be that of the final rounding alone, and below the 8-bit softmax variant's."""
+    from fractions import Fraction
+    rng = np.random.default_rng(19)
+    heads, d = 2, 64
+    H = heads * d
+    n = 37
+    cu = np.array([0, 2, 2 + n], np.int32)
+    qkv = rng.integers(-127, 128, (int(cu[-1]), 3 * H), dtype=np.int8)
+    s_q, s_k, s_v, s_ctx = map(np.float32, (0.021, 0.025, 0.02, 0.0067))
+    m = np.float32(np.float64(s_v) / np.float64(s_ctx))
+    ctx = oracle.attention_i8_p16(qkv, cu, heads, s_q, s_k, s_v, s_ctx)
+    x = qkv[cu[1]:cu[2]].astype(np.int64)
+    differ, ideal_err, int8_err = 0, [], []
+    P_all = []
+    for h in range(heads):
+        q, k, v = x[:, h * d:(h + 1) * d], x[:, H + h * d:H + (h + 1) * d], x[:, 2 * H + h * d:2 * H + (h + 1) * d]
+        P = _softmax64((q @ k.T).astype(np.float64) * float(s_q) * float(s_k) / math.sqrt(d))
+        P_all.append(P)
+        # float16 values are multiples of 2^-24: the sum over keys as an exact integer, rounded once to float32
+        P24 = np.rint(P.astype(np.float16).astype(np.float64) * 2.0 ** 24).astype(np.int64)
+        O = (P24 @ v).astype(np.float64) * 2.0 ** -24                      # |sum| < 2^31: exact in float64
+        want = np.clip(np.rint(O.astype(np.float32) * m), -127, 127).astype(np.int64)
+        got = ctx[cu[1]:cu[2], h * d:(h + 1) * d].astype(np.int64)
+        # the oracle reaches P through binary32 (e * rS) before binary16: a few P differ by one float16 ulp
+        assert np.abs(got - want).max() <= 1
+        differ += int((got != want).sum())
+        ideal = (P @ v) * float(m)
+        ideal_err.append(np.abs(got - np.clip(ideal, -127, 127)))
+    assert differ <= 0.01 * n * H
+    # each P16 is within 2^-12 relative of P and the P of a row sum to 1: the unrounded context moves by at most
+    # 127 * m * 2^-12 steps (twice that allowed for the binary32 detour), then comes the one final rounding
+    assert np.concatenate(ideal_err).max() <= 0.5 + 127 * float(m) * 2.0 ** -11
+    # the 8-bit softmax code with the best static step is much further from the ideal context
+    s_p = np.float32(max(p.max() for p in P_all) / 127)
+    ctx8 = oracle.attention_i8(qkv, cu, heads, s_q, s_k, s_v, s_p, s_ctx)
+    for h in range(heads):
+        v = x[:, 2 * H + h * d:2 * H + (h + 1) * d]
+        ideal = np.clip((P_all[h] @ v) * float(m), -127, 127)
+        int8_err.append(np.abs(ctx8[cu[1]:cu[2], h * d:(h + 1) * d].astype(np.float64) - ideal))
+    assert np.concatenate(ideal_err).mean() < 0.8 * np.concatenate(int8_err).mean()
+
+    # one key: P = 1, context = rne(v * m)
+    first = qkv[:2].copy()
+    one = oracle.attention_i8_p16(first[:1], np.array([0, 1], np.int32), heads, s_q, s_k, s_v, s_ctx)
+    assert np.array_equal(one[0], np.clip(np.rint(first[0, 2 * H:].astype(np.float32) * m), -127, 127).astype(np.int8))
+    # identical keys: P = 1/n for every key; n = 64 is exact in binary16, n = 3 and 48 round twice (binary32, binary16;
+    # leaving out the binary16 rounding changes some of these contexts)
+    for cnt in (64, 3, 48):
+        z = np.zeros((cnt, 3 * H), np.int8)
+        z[:, :H] = rng.integers(-50, 50, (cnt, H))
+        z[:, H:2 * H] = 5
+        z[:, 2 * H:] = rng.integers(-127, 128, (cnt, H))
+        got = oracle.attention_i8_p16(z, np.array([0, cnt], np.int32), heads, s_q, s_k, s_v, s_ctx)
+        p16 = Fraction(float(np.float16(np.float32(1.0) / np.float32(cnt))))
+        vsum = z[:, 2 * H:].astype(np.int64).sum(axis=0)
+        want = [int(np.clip(np.rint(np.float32(float(p16 * int(t))) * m), -127, 127)) for t in vsum]
+        for i in range(cnt):
+            assert got[i].astype(np.int64).tolist() == want
+
+
 def test_attention_sequences_are_independent():
     rng = np.random.default_rng(16)
     heads, d = 2, 64
