@@ -115,7 +115,14 @@ def main() -> int:
     if a.workload != "C2":
         mode_list = [("CONFIG", None)]
     if a.only_mode:
+        # the softmax-output variants of the INT8 attention block are timed on request only
+        mode_list += [("FULL_INT8+PU", P.FULL_INT8 | P.P_UNSIGNED), ("FULL_INT8+P16", P.FULL_INT8 | P.P_FP16)]
         mode_list = [m for m in mode_list if m[0] == a.only_mode]
+        if not mode_list:
+            raise SystemExit(f"unknown mode {a.only_mode}")
+        if mode_list[0][1] is not None and mode_list[0][1] & P.P_UNSIGNED:
+            scales = scales.copy()
+            scales[:, 4] *= np.float32(127.0 / 255.0)          # the same range on 255 levels
 
     results = {}
     roof = None

@@ -56,8 +56,12 @@ typedef struct samp_encoder samp_encoder_t;
  * SAMP_P_UNSIGNED, valid only together with bit 0, stores the softmax output of that layer as
  * unsigned codes rne(P / s_p) in [0, 255] instead of the symmetric [-127, 127], whose negative
  * half a softmax never uses (the loss Section 4.2 and Appendix B describe); the caller then
- * passes the step s_p = absmax(P) / 255 in samp_layer_scales_t.                                  */
-enum { SAMP_FP16 = 0, SAMP_MHA_INT8 = 1, SAMP_FFN_INT8 = 2, SAMP_FULL_INT8 = 3, SAMP_P_UNSIGNED = 4 };
+ * passes the step s_p = absmax(P) / 255 in samp_layer_scales_t.
+ * SAMP_P_FP16, valid only together with bit 0 and not with SAMP_P_UNSIGNED, is the other remedy:
+ * the softmax output of that layer is rounded to binary16 instead of being put on an 8-bit grid
+ * and multiplies the integer V codes, ctx = rne(fl32(sum P16 V) * s_v / s_ctx); the sum is
+ * evaluated exactly (integer digit planes of P16 * 2^24 on the matrix cores); s_p is not used.   */
+enum { SAMP_FP16 = 0, SAMP_MHA_INT8 = 1, SAMP_FFN_INT8 = 2, SAMP_FULL_INT8 = 3, SAMP_P_UNSIGNED = 4, SAMP_P_FP16 = 8 };
 
 enum {
     SAMP_OK = 0,
@@ -247,13 +251,15 @@ SAMP_API int samp_gemm_f16(const uint16_t *A, const uint16_t *W, const float *bi
 /* Softmax attention over packed rows.  qkv: dev [T,3H] (int8 or fp16), columns [0,H) Q, [H,2H) K,
  * [2H,3H) V.  cu_seqlens: dev int32 [B+1], sequence b owns rows cu[b]..cu[b+1); max_len >= every
  * length, <= SAMP_MAX_SEQ.  INT8 flavour (Section 4.2 / Appendix B: quantised softmax output):
- * score = float(q.k) * (s_q s_k / 8); P = softmax; Pq = rne(P / s_p) clamped to [-127, 127], or to
- * [0, 255] if p_unsigned != 0; ctx = rne(float(Pq.V) * s_p s_v / s_ctx).
+ * score = float(q.k) * (s_q s_k / 8); P = softmax; p_kind 0: Pq = rne(P / s_p) clamped to
+ * [-127, 127]; p_kind 1: clamped to [0, 255]; ctx = rne(float(Pq.V) * s_p s_v / s_ctx).
+ * p_kind 2: P is rounded to binary16 instead, ctx = rne(fl32(sum P16 V) * s_v / s_ctx), s_p is
+ * ignored and p_hist must be NULL.
  * p_hist: NULL, or dev uint64 [256] to which the kernel ADDS the number of times each code byte
  * (index = the code as an unsigned byte) occurs among the softmax codes of valid query/key pairs
  * (the caller zeroes it): the code-usage statistic of Appendix B.                                 */
 SAMP_API int samp_attention_i8(const int8_t *qkv, const int32_t *cu_seqlens, int32_t B, int32_t max_len, int32_t hidden,
-                               int32_t heads, float s_q, float s_k, float s_v, float s_p, float s_ctx, int32_t p_unsigned,
+                               int32_t heads, float s_q, float s_k, float s_v, float s_p, float s_ctx, int32_t p_kind,
                                int8_t *ctx, uint64_t *p_hist, void *stream);
 SAMP_API int samp_attention_f16(const uint16_t *qkv, const int32_t *cu_seqlens, int32_t B, int32_t max_len, int32_t hidden,
                                 int32_t heads, uint16_t *ctx, void *stream);

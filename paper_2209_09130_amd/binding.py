@@ -10,6 +10,7 @@ import torch
 
 FP16, MHA_INT8, FFN_INT8, FULL_INT8 = 0, 1, 2, 3
 P_UNSIGNED = 4
+P_FP16 = 8
 (PROF_OFF, PROF_QKV, PROF_ATTN, PROF_ATTN_OUT, PROF_LN1, PROF_FFN1, PROF_FFN2, PROF_LN2, PROF_ENTRY) = range(9)
 SCALE_FIELDS = ("x", "q", "k", "v", "p", "ctx", "attn_out", "ffn_in", "ffn_mid", "ffn_out")
 
@@ -254,14 +255,16 @@ def gemm_f16(A, W, bias, gelu: bool) -> torch.Tensor:
 
 
 def attention_i8(qkv, cu, max_len: int, heads: int, s_q, s_k, s_v, s_p, s_ctx, p_unsigned: bool = False,
-                 want_hist: bool = False):
-    """Returns ctx, or (ctx, hist) with hist = int64 [256] counts of the softmax codes (index = code byte)."""
+                 want_hist: bool = False, p_fp16: bool = False):
+    """Returns ctx, or (ctx, hist) with hist = int64 [256] counts of the softmax codes (index = code byte).
+    p_fp16: the softmax output stays binary16 (s_p unused, no histogram)."""
+    assert not (p_fp16 and (p_unsigned or want_hist))
     T, H3 = qkv.shape
     H = H3 // 3
     ctx = torch.zeros((T, H), dtype=torch.int8, device=qkv.device)
     hist = torch.zeros(256, dtype=torch.int64, device=qkv.device) if want_hist else None
     _check(lib().samp_attention_i8(_dp(qkv), _dp(cu), cu.numel() - 1, max_len, H, heads, _f(s_q), _f(s_k), _f(s_v),
-                                   _f(s_p), _f(s_ctx), int(bool(p_unsigned)), _dp(ctx), _dp(hist), _stream()))
+                                   _f(s_p), _f(s_ctx), 2 if p_fp16 else int(bool(p_unsigned)), _dp(ctx), _dp(hist), _stream()))
     return (ctx, hist) if want_hist else ctx
 
 

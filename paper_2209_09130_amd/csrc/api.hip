@@ -57,8 +57,13 @@ size_t staging_bytes(const samp_config_t &c)
     return up(big * 2) + up((size_t)std::max(3 * c.hidden, c.ffn) * sizeof(float));
 }
 
-// bit 0: MHA INT8, bit 1: FFN INT8, bit 2 (only with bit 0): unsigned softmax codes
-bool valid_mode(int m) { return m >= 0 && m <= 7 && (!(m & SAMP_P_UNSIGNED) || (m & SAMP_MHA_INT8)); }
+// bit 0: MHA INT8, bit 1: FFN INT8; only with bit 0, and not both: bit 2 unsigned softmax codes, bit 3 binary16 softmax output
+bool valid_mode(int m)
+{
+    if (m < 0 || m > 15) return false;
+    const int p = m & (SAMP_P_UNSIGNED | SAMP_P_FP16);
+    return !p || ((m & SAMP_MHA_INT8) && p != (SAMP_P_UNSIGNED | SAMP_P_FP16));
+}
 
 int check_config(const samp_config_t *c)
 {
@@ -228,9 +233,13 @@ int run(samp_encoder_t *enc, const void *hidden, const Ids *ids, const int32_t *
         if (mha8) {
             HIP_TRY(launch_gemm_i8(EPI_REQUANT, (const int8_t *)x, (const int8_t *)Y.w_qkv, w.qkv, Y.m_qkv, Y.bq_qkv, 0.f,
                                    rows, 3 * H, H, st, timing(enc, SAMP_PROF_QKV)));
-            HIP_TRY(launch_attention_i8((const int8_t *)w.qkv, cu, B, S, H, heads, Y.m_sc, Y.inv_sp, Y.m_ctx,
-                                        (Y.mode & SAMP_P_UNSIGNED) != 0, (int8_t *)w.ctx, nullptr, st,
-                                        timing(enc, SAMP_PROF_ATTN)));
+            if (Y.mode & SAMP_P_FP16)
+                HIP_TRY(launch_attention_i8_p16((const int8_t *)w.qkv, cu, B, S, H, heads, Y.m_sc, Y.m_ctx, (int8_t *)w.ctx, st,
+                                                timing(enc, SAMP_PROF_ATTN)));
+            else
+                HIP_TRY(launch_attention_i8((const int8_t *)w.qkv, cu, B, S, H, heads, Y.m_sc, Y.inv_sp, Y.m_ctx,
+                                            (Y.mode & SAMP_P_UNSIGNED) != 0, (int8_t *)w.ctx, nullptr, st,
+                                            timing(enc, SAMP_PROF_ATTN)));
             HIP_TRY(launch_gemm_i8(EPI_REQUANT, (const int8_t *)w.ctx, (const int8_t *)Y.w_o, w.ao, Y.m_o, nullptr, 0.f,
                                    rows, H, H, st, timing(enc, SAMP_PROF_ATTN_OUT)));
         } else {
@@ -315,8 +324,8 @@ int samp_encoder_create(const samp_config_t *cfg, const uint8_t *modes, const sa
     for (int l = 0; l < cfg->layers && any8; l++) {
         const samp_layer_scales_t &s = scales[l];
         const bool need_x = (modes[l] & 1);
-        if (need_x && !(good_scale(s.x) && good_scale(s.q) && good_scale(s.k) && good_scale(s.v) && good_scale(s.p) &&
-                        good_scale(s.ctx) && good_scale(s.attn_out)))
+        if (need_x && !(good_scale(s.x) && good_scale(s.q) && good_scale(s.k) && good_scale(s.v) &&
+                        ((modes[l] & SAMP_P_FP16) || good_scale(s.p)) && good_scale(s.ctx) && good_scale(s.attn_out)))
             return fail(SAMP_ERR_SCALE, "layer %d: an attention-block scale is not finite and positive", l);
         if ((modes[l] & 2) && !(good_scale(s.ffn_in) && good_scale(s.ffn_mid) && good_scale(s.ffn_out)))
             return fail(SAMP_ERR_SCALE, "layer %d: a feed-forward-block scale is not finite and positive", l);
@@ -380,7 +389,8 @@ int samp_encoder_create(const samp_config_t *cfg, const uint8_t *modes, const sa
                                         Y.m_qkv + part * H, Y.bq_qkv + part * H, st));
                 Y.m_sc = (float)((double)Y.s.q * (double)Y.s.k / std::sqrt(64.0));
                 Y.inv_sp = 1.0f / Y.s.p;
-                Y.m_ctx = (float)((double)Y.s.p * (double)Y.s.v / (double)Y.s.ctx);
+                Y.m_ctx = (Y.mode & SAMP_P_FP16) ? (float)((double)Y.s.v / (double)Y.s.ctx)
+                                                 : (float)((double)Y.s.p * (double)Y.s.v / (double)Y.s.ctx);
             }
             if (int rc = matrix(w.w_o, H, H, mha8, &Y.w_o)) return rc;
             if (mha8) HIP_TRY(launch_fold(nullptr, Y.s.ctx, s_w, nullptr, Y.s.attn_out, (int)H, Y.m_o, nullptr, st));
@@ -679,15 +689,22 @@ static int check_attention(const void *qkv, const int32_t *cu, int B, int max_le
 }
 
 int samp_attention_i8(const int8_t *qkv, const int32_t *cu, int32_t B, int32_t max_len, int32_t hidden, int32_t heads,
-                      float s_q, float s_k, float s_v, float s_p, float s_ctx, int32_t p_unsigned, int8_t *ctx,
+                      float s_q, float s_k, float s_v, float s_p, float s_ctx, int32_t p_kind, int8_t *ctx,
                       uint64_t *p_hist, void *stream)
 {
     if (int rc = check_attention(qkv, cu, B, max_len, hidden, heads, ctx)) return rc;
-    if (!(good_scale(s_q) && good_scale(s_k) && good_scale(s_v) && good_scale(s_p) && good_scale(s_ctx)))
+    if (p_kind < 0 || p_kind > 2) return fail(SAMP_ERR_ARG, "p_kind must be 0, 1 or 2");
+    if (!(good_scale(s_q) && good_scale(s_k) && good_scale(s_v) && (p_kind == 2 || good_scale(s_p)) && good_scale(s_ctx)))
         return fail(SAMP_ERR_SCALE, "attention scales must be finite and positive");
     const float m_sc = (float)((double)s_q * (double)s_k / std::sqrt(64.0));
+    if (p_kind == 2) {
+        if (p_hist) return fail(SAMP_ERR_ARG, "a binary16 softmax output has no code histogram");
+        HIP_TRY(launch_attention_i8_p16(qkv, cu, B, max_len, hidden, heads, m_sc, (float)((double)s_v / (double)s_ctx), ctx,
+                                        (hipStream_t)stream, nullptr));
+        return SAMP_OK;
+    }
     const float m_ctx = (float)((double)s_p * (double)s_v / (double)s_ctx);
-    HIP_TRY(launch_attention_i8(qkv, cu, B, max_len, hidden, heads, m_sc, 1.0f / s_p, m_ctx, p_unsigned != 0, ctx,
+    HIP_TRY(launch_attention_i8(qkv, cu, B, max_len, hidden, heads, m_sc, 1.0f / s_p, m_ctx, p_kind == 1, ctx,
                                 reinterpret_cast<unsigned long long *>(p_hist), (hipStream_t)stream, nullptr));
     return SAMP_OK;
 }

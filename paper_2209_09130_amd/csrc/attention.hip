@@ -515,6 +515,210 @@ __global__ __launch_bounds__(256) void attention_i8_long_kernel(const int8_t *__
     if (HIST && hist[tid]) atomicAdd(&p_hist[tid], (unsigned long long)hist[tid]);
 }
 
+// ---- INT8 attention block whose softmax output stays binary16 (not on the 8-bit grid) ---------------
+// P16 = fl16(e * rS), ctx = rne(fl32(sum_k P16[k] V[k]) * m) with m = s_v / s_ctx.  The sum is evaluated
+// exactly: a binary16 value in [0, 1] is an integer multiple of 2^-24, so P16 * 2^24 is an integer below
+// 2^28 that splits into four 7-bit digits; each digit plane is one more int8 operand for the matrix core
+// (non-negative, so no sign trick), the four int32 products recombine in 64-bit integers, and one
+// conversion rounds the true sum to binary32.
+
+// V^T of key tile j0 into a wave's own LDS slab: 4 keys x 4 channels byte blocks transposed in registers
+__device__ __forceinline__ void stage_vt_i8(const int8_t *vp, unsigned ld, int j0, int n, int lane, int8_t *slab)
+{
+#pragma unroll
+    for (int u = 0; u < 2; u++) {
+        const int cq = lane & 15, kq = (lane >> 4) + 4 * u;
+        unsigned d[4];
+#pragma unroll
+        for (int t = 0; t < 4; t++)
+            d[t] = *reinterpret_cast<const unsigned *>(vp + (unsigned)min(j0 + 4 * kq + t, n - 1) * ld + 4 * cq);
+        const unsigned t01l = __builtin_amdgcn_perm(d[1], d[0], 0x05010400u), t23l = __builtin_amdgcn_perm(d[3], d[2], 0x05010400u);
+        const unsigned t01h = __builtin_amdgcn_perm(d[1], d[0], 0x07030602u), t23h = __builtin_amdgcn_perm(d[3], d[2], 0x07030602u);
+        unsigned *dst = reinterpret_cast<unsigned *>(&slab[(4 * cq) * VT_STRIDE_I8 + 4 * kq]);
+        dst[0 * (VT_STRIDE_I8 / 4)] = __builtin_amdgcn_perm(t23l, t01l, 0x05040100u);
+        dst[1 * (VT_STRIDE_I8 / 4)] = __builtin_amdgcn_perm(t23l, t01l, 0x07060302u);
+        dst[2 * (VT_STRIDE_I8 / 4)] = __builtin_amdgcn_perm(t23h, t01h, 0x05040100u);
+        dst[3 * (VT_STRIDE_I8 / 4)] = __builtin_amdgcn_perm(t23h, t01h, 0x07060302u);
+    }
+}
+
+// digit planes of one key tile: ev[e] = fl32(exp(score - max)) of the lane's 16 keys; pf[k] is the int8 operand
+// holding digit k (7 bits) of P16 * 2^24 for those keys
+__device__ __forceinline__ void p16_digits(const float (&ev)[16], float rS, v4i (&pf)[4])
+{
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+        unsigned fixed[4];                                        // P16 * 2^24 of four consecutive keys
+#pragma unroll
+        for (int t = 0; t < 4; t++) fixed[t] = (unsigned)((float)to_half(ev[4 * q + t] * rS) * 16777216.0f);
+#pragma unroll
+        for (int k = 0; k < 4; k++)
+            pf[k][q] = (int)(((fixed[0] >> (7 * k)) & 127u) | (((fixed[1] >> (7 * k)) & 127u) << 8) |
+                             (((fixed[2] >> (7 * k)) & 127u) << 16) | (((fixed[3] >> (7 * k)) & 127u) << 24));
+    }
+}
+
+// digit planes times the V^T tile in the slab, channel block cb: o[k] += pf[k] . V
+__device__ __forceinline__ void p16_mfma(const v4i (&pf)[4], const int8_t *slab, int cb, int r, int g, v16i (&o)[4])
+{
+    v4i vf;
+#pragma unroll
+    for (int q = 0; q < 4; q++) vf[q] = *reinterpret_cast<const int *>(&slab[(cb * 32 + r) * VT_STRIDE_I8 + 8 * q + 4 * g]);
+#pragma unroll
+    for (int k = 0; k < 4; k++) o[k] = __builtin_amdgcn_mfma_i32_32x32x32_i8(pf[k], vf, o[k], 0, 0, 0);
+}
+
+// channel block cb: 2^24 times a wave's partial context in 64-bit integers, the four waves added, scaled back
+// (exact) and rounded once to binary32.  Contains block-wide barriers.
+__device__ __forceinline__ void p16_finish(const v16i (&o)[4], int cb, long long (&so)[4][QB][32], float m_ctx,
+                                           int8_t *ctx_rows, int H, int rows_left, int tid)
+{
+    const int lane = tid & 63, w = tid >> 6, r = lane & 31, g = lane >> 5;
+    const int query = tid >> 3, c0 = (tid & 7) * 4;
+    if (cb) __syncthreads();                                      // the previous block's partials have been read
+#pragma unroll
+    for (int e = 0; e < 16; e++) {
+        const long long v = ((((long long)o[3][e] * 128 + o[2][e]) * 128 + o[1][e]) * 128) + o[0][e];
+        so[w][8 * (e >> 2) + 4 * g + (e & 3)][r] = v;
+    }
+    __syncthreads();
+    if (query < rows_left) {
+        int codes[4];
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            const long long O = ((so[0][query][c0 + e] + so[1][query][c0 + e]) + so[2][query][c0 + e]) + so[3][query][c0 + e];
+            const float Of = (float)((double)O * 5.9604644775390625e-08);              // * 2^-24
+            codes[e] = qcode(Of * m_ctx);
+        }
+        *reinterpret_cast<int *>(ctx_rows + (size_t)query * H + cb * 32 + c0) = pack4(codes[0], codes[1], codes[2], codes[3]);
+    }
+}
+
+// NT > 0: up to 128 NT keys, the strip of scores stays in registers (one pass, as attention_i8_kernel);
+// NT == 0: any length, three sweeps (as attention_i8_long_kernel).
+template <int NT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void
+attention_i8_p16_kernel(const int8_t *__restrict__ qkv, const int *__restrict__ cu, int max_len, int H, float m_sc, float m_ctx,
+                        int8_t *__restrict__ ctx)
+{
+    constexpr int NSLAB = NT > 0 ? NT : 1;
+    __shared__ __attribute__((aligned(16))) int8_t vt[4][NSLAB][64 * VT_STRIDE_I8];
+    __shared__ long long so[4][QB][32];
+    __shared__ float smax[4][QB];
+    __shared__ double ssum[4][QB];
+
+    const int nqb = (max_len + QB - 1) / QB, heads = H >> 6;
+    const int item = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int seq = item / (nqb * heads), head = (item / nqb) % heads;
+    const SeqInfo sq = seq_info(cu, seq, max_len);
+    const int q0 = (item % nqb) * QB;
+    if (q0 >= sq.n) return;
+    const int n = sq.n;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, g = lane >> 5;
+    const unsigned ld = 3u * (unsigned)H;
+    const int8_t *base = qkv + (size_t)sq.t0 * ld + head * 64;
+    const int8_t *vp = base + 2 * H;
+
+    const int qrow = min(q0 + r, n - 1);
+    v4i qf[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ks++) qf[ks] = *reinterpret_cast<const v4i *>(base + (unsigned)qrow * ld + ks * 32 + g * 16);
+
+    float scr[NSLAB][16];
+    float sc[16];
+    float mx = -INFINITY;
+    if constexpr (NT > 0) {
+#pragma unroll
+        for (int i = 0; i < NT; i++) {
+            const int j0 = (w + 4 * i) * 32;
+            if (j0 < n) {
+                score_tile_i8(base, ld, H, j0, n, r, g, qf, m_sc, scr[i]);
+                stage_vt_i8(vp, ld, j0, n, lane, vt[w][i]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; e++) scr[i][e] = -INFINITY;
+            }
+#pragma unroll
+            for (int e = 0; e < 16; e++) mx = __builtin_fmaxf(mx, scr[i][e]);
+        }
+    } else {
+        for (int j0 = w * 32; j0 < n; j0 += 128) {
+            score_tile_i8(base, ld, H, j0, n, r, g, qf, m_sc, sc);
+#pragma unroll
+            for (int e = 0; e < 16; e++) mx = __builtin_fmaxf(mx, sc[e]);
+        }
+    }
+    mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32, 64));
+    if (g == 0) smax[w][r] = mx;
+    __syncthreads();
+    mx = __builtin_fmaxf(__builtin_fmaxf(smax[0][r], smax[1][r]), __builtin_fmaxf(smax[2][r], smax[3][r]));
+
+    double part = 0.0;
+    if constexpr (NT > 0) {
+#pragma unroll
+        for (int i = 0; i < NT; i++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) {
+                scr[i][e] = (float)exp_nonpos((double)__builtin_fmaxf(scr[i][e] - mx, -746.0f));
+                part += (double)scr[i][e];
+            }
+    } else {
+        for (int j0 = w * 32; j0 < n; j0 += 128) {
+            score_tile_i8(base, ld, H, j0, n, r, g, qf, m_sc, sc);
+#pragma unroll
+            for (int e = 0; e < 16; e++) part += (double)(float)exp_nonpos((double)__builtin_fmaxf(sc[e] - mx, -746.0f));
+        }
+    }
+    part += __shfl_xor(part, 32, 64);
+    if (g == 0) ssum[w][r] = part;
+    __syncthreads();
+    const float S = (float)(((ssum[0][r] + ssum[1][r]) + ssum[2][r]) + ssum[3][r]);
+    const float rS = __fdiv_rn(1.0f, S);
+
+    int8_t *ctx_rows = ctx + (size_t)(sq.t0 + q0) * H + head * 64;
+    if constexpr (NT > 0) {
+        // the digit planes of all tiles stay in registers; one channel block at a time halves the accumulators
+        v4i pf[NT][4];
+#pragma unroll
+        for (int i = 0; i < NT; i++) p16_digits(scr[i], rS, pf[i]);
+#pragma unroll
+        for (int cb = 0; cb < 2; cb++) {
+            v16i o[4];
+#pragma unroll
+            for (int k = 0; k < 4; k++)
+#pragma unroll
+                for (int e = 0; e < 16; e++) o[k][e] = 0;
+#pragma unroll
+            for (int i = 0; i < NT; i++)
+                if ((w + 4 * i) * 32 < n) p16_mfma(pf[i], vt[w][i], cb, r, g, o);
+            p16_finish(o, cb, so, m_ctx, ctx_rows, H, n - q0, tid);
+        }
+    } else {
+        v16i o[2][4];                                         // [channel block][digit plane]
+#pragma unroll
+        for (int cb = 0; cb < 2; cb++)
+#pragma unroll
+            for (int k = 0; k < 4; k++)
+#pragma unroll
+                for (int e = 0; e < 16; e++) o[cb][k][e] = 0;
+        for (int j0 = w * 32; j0 < n; j0 += 128) {
+            score_tile_i8(base, ld, H, j0, n, r, g, qf, m_sc, sc);
+            // the slab is written and read by this wave only, in program order
+            __builtin_amdgcn_wave_barrier();
+            stage_vt_i8(vp, ld, j0, n, lane, vt[w][0]);
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int e = 0; e < 16; e++) sc[e] = (float)exp_nonpos((double)__builtin_fmaxf(sc[e] - mx, -746.0f));
+            v4i pf[4];
+            p16_digits(sc, rS, pf);
+            p16_mfma(pf, vt[w][0], 0, r, g, o[0]);
+            p16_mfma(pf, vt[w][0], 1, r, g, o[1]);
+        }
+        p16_finish(o[0], 0, so, m_ctx, ctx_rows, H, n - q0, tid);
+        p16_finish(o[1], 1, so, m_ctx, ctx_rows, H, n - q0, tid);
+    }
+}
+
 __device__ __forceinline__ void score_tile_f16(const __half *base, unsigned ld, int H, int j0, int n, int r, int g,
                                                const v8h (&qf)[4], float scale, float (&sc)[16])
 {
@@ -662,6 +866,17 @@ hipError_t launch_attention_i8(const int8_t *qkv, const int *cu, int B, int max_
         if (p_hist) launch_attention_i8_variant<false, true>(qkv, cu, B, max_len, H, heads, m_sc, inv_sp, m_ctx, ctx, p_hist, st, tm);
         else launch_attention_i8_variant<false, false>(qkv, cu, B, max_len, H, heads, m_sc, inv_sp, m_ctx, ctx, p_hist, st, tm);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_attention_i8_p16(const int8_t *qkv, const int *cu, int B, int max_len, int H, int heads, float m_sc,
+                                   float m_ctx, int8_t *ctx, hipStream_t st, const Timing *tm)
+{
+    dim3 grid((unsigned)((max_len + QB - 1) / QB) * heads * B), block(256);
+    if (max_len <= 128) launch_kernel(attention_i8_p16_kernel<1>, grid, block, 0, st, tm, qkv, cu, max_len, H, m_sc, m_ctx, ctx);
+    else if (max_len <= 256) launch_kernel(attention_i8_p16_kernel<2>, grid, block, 0, st, tm, qkv, cu, max_len, H, m_sc, m_ctx, ctx);
+    else if (max_len <= ONE_PASS_MAX_LEN) launch_kernel(attention_i8_p16_kernel<4>, grid, block, 0, st, tm, qkv, cu, max_len, H, m_sc, m_ctx, ctx);
+    else launch_kernel(attention_i8_p16_kernel<0>, grid, block, 0, st, tm, qkv, cu, max_len, H, m_sc, m_ctx, ctx);
     return hipGetLastError();
 }
 

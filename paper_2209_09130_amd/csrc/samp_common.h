@@ -175,6 +175,8 @@ hipError_t launch_attention_i8(const int8_t *qkv, const int *cu, int B, int max_
                                float inv_sp, float m_ctx, bool p_unsigned, int8_t *ctx, unsigned long long *p_hist,
                                hipStream_t st, const Timing *tm);
 hipError_t launch_code_histogram(const int8_t *codes, size_t n, unsigned long long *hist, hipStream_t st);
+hipError_t launch_attention_i8_p16(const int8_t *qkv, const int *cu, int B, int max_len, int H, int heads, float m_sc,
+                                   float m_ctx, int8_t *ctx, hipStream_t st, const Timing *tm);
 hipError_t launch_attention_f16(const __half *qkv, const int *cu, int B, int max_len, int H, int heads, float scale,
                                 __half *ctx, float *p_absmax, hipStream_t st, const Timing *tm);
 

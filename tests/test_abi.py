@@ -52,7 +52,10 @@ def test_invalid_arguments_become_error_codes_on_the_host(L):
     bad_seq = _Config(2, 768, 12, 3072, 8, 4097, 1e-12)
     assert L.samp_encoder_arena_bytes(C.byref(bad_seq), modes) == 0
     assert b"max_seq" in L.samp_last_error()
-    assert L.samp_encoder_arena_bytes(C.byref(ok), (C.c_uint8 * 2)(8, 0)) == 0
+    assert L.samp_encoder_arena_bytes(C.byref(ok), (C.c_uint8 * 2)(16, 0)) == 0
+    assert L.samp_encoder_arena_bytes(C.byref(ok), (C.c_uint8 * 2)(8, 0)) == 0       # a binary16 softmax output needs an INT8 MHA
+    assert L.samp_encoder_arena_bytes(C.byref(ok), (C.c_uint8 * 2)(13, 0)) == 0      # ... and excludes the unsigned codes
+    assert L.samp_encoder_arena_bytes(C.byref(ok), (C.c_uint8 * 2)(9, 11)) > 0
     assert L.samp_encoder_arena_bytes(C.byref(ok), (C.c_uint8 * 2)(6, 0)) == 0       # unsigned softmax codes need an INT8 MHA
     assert L.samp_encoder_arena_bytes(C.byref(ok), (C.c_uint8 * 2)(7, 5)) > 0
     assert L.samp_encoder_arena_bytes(None, modes) == 0

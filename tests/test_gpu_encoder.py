@@ -21,7 +21,7 @@ import pytest
 
 import oracle
 import samp_workloads as W
-from samp_workloads import FP16, MHA_INT8, FFN_INT8, FULL_INT8, P_UNSIGNED
+from samp_workloads import FP16, MHA_INT8, FFN_INT8, FULL_INT8, P_UNSIGNED, P_FP16
 
 pytestmark = pytest.mark.gpu
 
@@ -238,6 +238,41 @@ def test_c2_fully_quant_with_unsigned_softmax_codes(P):
     print(f"[parity] C2 mean |out - unquantised reference|: symmetric {dist['symmetric']:.4g}  unsigned {dist['unsigned']:.4g}",
           flush=True)
     assert dist["unsigned"] <= 1.02 * dist["symmetric"]
+
+
+@pytest.mark.parametrize("varlen", [False, True])
+def test_small_encoder_with_binary16_softmax_output_is_bit_identical(P, varlen):
+    """INT8 attention blocks that keep the softmax output in binary16: the kernel sums P16 * V exactly (integer digit
+    planes), so Fully-Quant stacks stay bit-identical to the oracle; mixed with the 8-bit softmax variants and with
+    FP16 blocks the usual tolerance applies."""
+    w = small((FULL_INT8 | P_FP16,) * 3, varlen=varlen)
+    wts = W.make_weights(w)
+    hid, lens, mask = W.make_hidden(w)
+    sc = oracle.calibrate(*args(w), wts, W.make_calibration_batch(w))
+    want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid, lens)
+    got = run_gpu(P, w, wts, sc, hid, mask if varlen else None)
+    assert (compare(got, want, lens, True, f"small binary16-P varlen={varlen}") == 0).all()
+    w = small((FULL_INT8 | P_FP16, MHA_INT8 | P_FP16, FULL_INT8 | P_UNSIGNED, FULL_INT8), varlen=varlen)
+    wts = W.make_weights(w)
+    sc = oracle.calibrate(*args(w), wts, W.make_calibration_batch(w))
+    sc[2:3] = unsigned_p_scales(sc[2:3])
+    sc[0, 4] = np.float32("nan")                                # the softmax step of a binary16-P layer is never read
+    want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid, lens)
+    got = run_gpu(P, w, wts, sc, hid, mask if varlen else None)
+    compare(got, want, lens, False, f"small mixed softmax variants varlen={varlen}")
+
+
+def test_c2_fully_quant_with_binary16_softmax_output(P):
+    """The variant at the benchmark shape, sampled sequences bit-identical to the oracle."""
+    base = W.config("C2")
+    wts = W.make_weights(base)
+    hid, lens, _ = W.make_hidden(base)
+    sc = oracle.calibrate(*args(base), wts, W.make_calibration_batch(base))
+    pick = [0, 17]
+    w = base.with_modes(FULL_INT8 | P_FP16)
+    got = run_gpu(P, w, wts, sc, hid, None)
+    want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid[pick], lens[pick])
+    assert (compare(got[pick], want, lens[pick], True, "C2 FULL_INT8 binary16 softmax output") == 0).all()
 
 
 @pytest.mark.parametrize("varlen", [False, True])

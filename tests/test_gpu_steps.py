@@ -252,6 +252,22 @@ def test_int8_attention_unsigned_softmax_codes_bit_exact(P, lens, heads):
         assert np.abs(want).max() > 20
 
 
+@pytest.mark.parametrize("lens,heads", [([128], 2), ([1, 5, 32, 33, 64, 17, 2], 3), ([300, 512, 129], 1), ([700, 1, 1030], 1)])
+def test_int8_attention_with_binary16_softmax_output_bit_exact(P, lens, heads):
+    """P rounded to binary16 times integer V: the kernel splits P16 * 2^24 into four 7-bit digit planes for the int8
+    matrix core and recombines in 64-bit integers, so the context must equal the oracle's exact binary64 sum, also for
+    a single key (P = 1 = 2^24 units, the largest digit pattern) and for subnormal probabilities (peaked softmax)."""
+    rng = np.random.default_rng(sum(lens) + 5)
+    H = heads * 64
+    cu = _cu(lens)
+    qkv = np.clip(np.rint(rng.standard_normal((int(cu[-1]), 3 * H)) * 30), -127, 127).astype(np.int8)
+    for s_q, s_k, s_v, s_ctx in ((0.0209, 0.0249, 0.021, 0.0021), (0.08, 0.08, 0.021, 0.02), (0.004, 0.004, 0.03, 0.001)):
+        want = oracle.attention_i8_p16(qkv, cu, heads, s_q, s_k, s_v, s_ctx)
+        got = host(P.attention_i8(dev(qkv), dev(cu), max(lens), heads, s_q, s_k, s_v, float("nan"), s_ctx, p_fp16=True))
+        assert np.array_equal(got, want)
+    assert np.abs(want).max() > 20
+
+
 def test_softmax_code_usage_histogram(P):
     """The statistic of Appendix B (how many of the 256 integers a tensor's codes use) on synthetic data: the
     kernel's count of the softmax codes equals the count of the oracle's dumped codes, and samp_code_histogram of the
