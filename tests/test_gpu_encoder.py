@@ -441,6 +441,21 @@ def test_encoder_with_sequences_longer_than_512_tokens(P, modes):
         assert (d == 0).all()
 
 
+@pytest.mark.parametrize("modes", [(FULL_INT8,), (FP16,), (FFN_INT8,)])
+def test_widest_supported_hidden_size(P, modes):
+    """hidden = 2048 (32 heads), the largest the library takes: one layer, short ragged batch."""
+    w = W.Workload("wide", 1, 2048, 32, 256, 3, 21, tuple(modes), varlen=True, min_len=2, plain_params=False,
+                   calib_batch=2, calib_seq=16)
+    wts = W.make_weights(w)
+    hid, lens, mask = W.make_hidden(w)
+    sc = oracle.calibrate(*args(w), wts, W.make_calibration_batch(w))
+    want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid, lens)
+    got = run_gpu(P, w, wts, sc, hid, mask)
+    d = compare(got, want, lens, modes[0] in (FULL_INT8, FP16), f"hidden 2048 {modes}")
+    if modes[0] == FULL_INT8:
+        assert (d == 0).all()
+
+
 def test_gpu_calibration_matches_the_oracle_calibration(P):
     import torch
     w = W.config("C1").with_modes(FP16)

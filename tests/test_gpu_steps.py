@@ -345,6 +345,23 @@ def test_long_sequence_attention_matches_the_oracle(P, lens, heads):
     assert np.abs(got - want).mean() <= 1e-4
 
 
+def test_attention_at_the_longest_supported_sequence(P):
+    """4096 tokens, the largest max_len the library takes: all three INT8 softmax-output forms bit-exact."""
+    rng = np.random.default_rng(4096)
+    heads, n = 1, 4096
+    cu = _cu([n])
+    qkv = np.clip(np.rint(rng.standard_normal((n, 3 * 64)) * 26), -127, 127).astype(np.int8)
+    sc = (0.0209, 0.0249, 0.021, 0.0001, 0.0012)
+    for kw in ({}, {"p_unsigned": True}):
+        want = oracle.attention_i8(qkv, cu, heads, *sc, **kw)
+        assert np.array_equal(host(P.attention_i8(dev(qkv), dev(cu), n, heads, *sc, **kw)), want)
+        assert np.abs(want).max() > 10
+    want = oracle.attention_i8_p16(qkv, cu, heads, sc[0], sc[1], sc[2], sc[4])
+    assert np.array_equal(host(P.attention_i8(dev(qkv), dev(cu), n, heads, *sc, p_fp16=True)), want)
+    with pytest.raises(P.SampError):
+        P.attention_i8(dev(qkv), dev(cu), n + 1, heads, *sc)
+
+
 def test_long_kernel_equals_one_pass_kernel_on_short_sequences(P):
     """A batch whose longest row exceeds 512 tokens runs every sequence, also the short ones, through the three-sweep
     kernel: their contexts must be the bytes the one-pass kernel writes when the same short sequences come alone."""
