@@ -75,8 +75,10 @@ enum {
 /* Supported shapes: head size hidden/heads == 64; hidden % 128 == 0; ffn % 128 == 0;
  * hidden <= 2048; 1 <= max_seq <= SAMP_MAX_SEQ; max_batch >= 1.  Up to 512 tokens a sequence's
  * attention scores stay in registers; longer sequences take a three-sweep attention kernel that
- * recomputes them (same results, about half the rate per token pair).                            */
+ * recomputes them (same results, about half the rate per token pair).  Row counts are 32-bit:
+ * max_batch * max_seq <= SAMP_MAX_TOKENS.                                                         */
 #define SAMP_MAX_SEQ 4096
+#define SAMP_MAX_TOKENS (1 << 24)
 typedef struct {
     int32_t layers, hidden, heads, ffn, max_batch, max_seq;
     float ln_eps;

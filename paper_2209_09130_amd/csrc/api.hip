@@ -73,6 +73,8 @@ int check_config(const samp_config_t *c)
     if (c->hidden % 128 || c->hidden > 2048) return fail(SAMP_ERR_SHAPE, "hidden must be a multiple of 128, at most 2048");
     if (c->ffn < 128 || c->ffn % 128) return fail(SAMP_ERR_SHAPE, "ffn must be a positive multiple of 128");
     if (c->max_seq < 1 || c->max_seq > SAMP_MAX_SEQ) return fail(SAMP_ERR_SHAPE, "max_seq must be in [1, %d]", SAMP_MAX_SEQ);
+    if ((long long)c->max_batch * c->max_seq > SAMP_MAX_TOKENS)
+        return fail(SAMP_ERR_SHAPE, "max_batch * max_seq must not exceed %d tokens", SAMP_MAX_TOKENS);
     if (!(c->ln_eps >= 0.0f) || !std::isfinite(c->ln_eps)) return fail(SAMP_ERR_ARG, "ln_eps must be finite and >= 0");
     return SAMP_OK;
 }

@@ -52,6 +52,9 @@ def test_invalid_arguments_become_error_codes_on_the_host(L):
     bad_seq = _Config(2, 768, 12, 3072, 8, 4097, 1e-12)
     assert L.samp_encoder_arena_bytes(C.byref(bad_seq), modes) == 0
     assert b"max_seq" in L.samp_last_error()
+    too_many = _Config(2, 768, 12, 3072, 8192, 4096, 1e-12)                         # 2^25 token rows
+    assert L.samp_encoder_arena_bytes(C.byref(too_many), modes) == 0
+    assert b"tokens" in L.samp_last_error()
     assert L.samp_encoder_arena_bytes(C.byref(ok), (C.c_uint8 * 2)(16, 0)) == 0
     assert L.samp_encoder_arena_bytes(C.byref(ok), (C.c_uint8 * 2)(8, 0)) == 0       # a binary16 softmax output needs an INT8 MHA
     assert L.samp_encoder_arena_bytes(C.byref(ok), (C.c_uint8 * 2)(13, 0)) == 0      # ... and excludes the unsigned codes
