@@ -160,7 +160,9 @@ SAMP_API int samp_encoder_set_groups(samp_encoder_t *enc, int32_t groups);
 /* A forward is a few hundred short kernels, so by default the library records them once per distinct
  * argument set (pointers, B, S) into a HIP graph -- on the second call with those arguments, on a
  * stream of its own -- and replays that graph on the caller's stream afterwards.  enabled = 0 keeps
- * plain launches.  Timing via samp_encoder_profile always uses plain launches.                     */
+ * plain launches: choose that when the caller's stream is itself under graph capture (the plain
+ * launches, events and side streams of a forward are capturable; a nested capture is not attempted).
+ * Timing via samp_encoder_profile always uses plain launches.                                      */
 SAMP_API int samp_encoder_set_graph(samp_encoder_t *enc, int32_t enabled);
 
 /* Min-max calibration (Table 2 caption; Appendix B): runs the all-FP16 encoder `enc` (every mode
