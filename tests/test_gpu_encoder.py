@@ -577,6 +577,38 @@ def test_batch_groups_and_graph_replay_do_not_change_results(P, varlen):
     compare(base.cpu().numpy(), want, lens, False, f"groups/graph varlen={varlen}")
 
 
+@pytest.mark.parametrize("varlen", [False, True])
+def test_forward_captured_into_a_graph_of_the_caller(P, varlen):
+    """A caller that records the forward into a HIP graph of its own switches the library's graph cache off; the plain
+    launches with their fork / join over the group streams are then captured, and every replay (with eager work and
+    synchronisations in between) must give the eager result."""
+    import torch
+    w = small((FULL_INT8, FFN_INT8, MHA_INT8 | P_FP16), batch=6, varlen=varlen)
+    wts = W.make_weights(w)
+    hid, lens, mask = W.make_hidden(w)
+    sc = oracle.calibrate(*args(w), wts, W.make_calibration_batch(w))
+    enc = P.Encoder(*args(w), w.modes, wts, sc, max_batch=hid.shape[0], max_seq=hid.shape[1])
+    enc.set_graph(False)
+    enc.set_groups(2)
+    h = torch.from_numpy(hid).cuda()
+    m = torch.from_numpy(mask).cuda() if varlen else None
+    eager = torch.empty_like(h)
+    enc.forward(h, m, eager)                                     # also creates the encoder's streams and events
+    torch.cuda.synchronize()
+    out = torch.empty_like(h)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        enc.forward(h, m, out)
+    for _ in range(3):
+        out.fill_(5.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager)
+    del graph
+    enc.close()
+
+
 def test_error_paths_on_the_device_side(P):
     import torch
     w = small((FULL_INT8,), batch=2, seq=16, varlen=False)
