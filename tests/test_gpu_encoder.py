@@ -389,18 +389,19 @@ def test_c4_and_c5_at_full_depth_on_sampled_sequences(P, name, pick):
     assert (d == 0).all()
 
 
-@pytest.mark.parametrize("seed", range(12))
+@pytest.mark.parametrize("seed", range(16))
 def test_random_small_configurations(P, seed):
     """Seeded random shapes and per-layer modes (hidden 128..384, ffn 128..640, 1..3 layers, batch 1..7, length 1..70,
-    with and without padding, unsigned softmax codes on some INT8 attention blocks)."""
+    with and without padding, unsigned softmax codes or a binary16 softmax output on some INT8 attention blocks)."""
     rng = np.random.default_rng(1000 + seed)
     heads = 2 * int(rng.integers(1, 4))                    # hidden = 128, 256 or 384
     layers = int(rng.integers(1, 4))
     modes = []
     for _ in range(layers):
         m = int(rng.integers(0, 4))
-        if m & 1 and rng.random() < 0.4:
-            m |= P_UNSIGNED
+        if m & 1:
+            u = rng.random()
+            m |= P_UNSIGNED if u < 0.3 else (P_FP16 if u < 0.6 else 0)
         modes.append(m)
     seq = int(rng.integers(1, 71))
     w = W.Workload(f"rand{seed}", layers, heads * 64, heads, int(rng.integers(1, 6)) * 128, int(rng.integers(1, 8)), seq,
