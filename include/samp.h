@@ -73,12 +73,13 @@ enum {
 };
 
 /* Supported shapes: head size hidden/heads == 64; hidden % 128 == 0; ffn % 128 == 0;
- * hidden <= 2048; 1 <= max_seq <= SAMP_MAX_SEQ; max_batch >= 1.  Up to 512 tokens a sequence's
+ * hidden <= 2048; 1 <= max_seq <= SAMP_MAX_SEQ; 1 <= max_batch <= SAMP_MAX_BATCH.  Up to 512 tokens a sequence's
  * attention scores stay in registers; longer sequences take a three-sweep attention kernel that
  * recomputes them (same results, about half the rate per token pair).  Row counts are 32-bit:
  * max_batch * max_seq <= SAMP_MAX_TOKENS.                                                         */
 #define SAMP_MAX_SEQ 4096
 #define SAMP_MAX_TOKENS (1 << 24)
+#define SAMP_MAX_BATCH 8192
 typedef struct {
     int32_t layers, hidden, heads, ffn, max_batch, max_seq;
     float ln_eps;
@@ -125,6 +126,9 @@ SAMP_API size_t samp_encoder_workspace_bytes(const samp_encoder_t *enc, int32_t 
  * right-padded (a sequence's tokens form a prefix, at least one token), or NULL = every sequence
  * has S tokens.  With a mask, padding is removed on entry (only valid tokens are computed) and
  * restored on exit: padded rows of `out` are written as zeros and never influence valid rows.
+ * The mask is device memory and a forward never synchronises, so its contents are not checked: a
+ * sequence whose mask row is all zero takes part in nothing (no packed rows, no attention work) and
+ * all S rows of its output are zeros; a mask that is not a prefix is read as its number of ones.
  * out: dev fp16 [B,S,H], must not alias hidden.  workspace: dev, 256-byte aligned,
  * >= samp_encoder_workspace_bytes(enc,B,S); calls sharing a workspace must be stream-ordered.     */
 SAMP_API int samp_encoder_forward(samp_encoder_t *enc, const void *hidden, const int32_t *mask, int32_t B, int32_t S,
@@ -279,6 +283,11 @@ SAMP_API int samp_add_ln(const void *in, int32_t in_i8, float s_in, const float 
  * dev binary32 vector y of n elements; GELU in its exact-erf form.  fast (dev float [n], may be NULL)
  * receives the kernel's fast-path GELU values, whose error bound the tests verify.                 */
 SAMP_API int samp_gelu_quant(const float *y, int64_t n, float s_out, int8_t *codes, float *fast, void *stream);
+
+/* The entry quantiser on its own (Section 3.2: the producer of a quantised block's input emits INT8):
+ * out[i] = clamp(rne(float(x[i]) * (1/s_x)), -127, 127) for a dev fp16 vector of n elements, n % 8 == 0;
+ * x 16-byte aligned, out 8-byte aligned.  (With a mask, samp_pack_rows does the same while packing.) */
+SAMP_API int samp_quantize_f16_i8(const uint16_t *x, int64_t n, float s_x, int8_t *out, void *stream);
 
 /* Per-output-channel weight quantisation: W dev fp16 [N,K] -> Wq dev int8 [N,K], s_w dev float [N]. */
 SAMP_API int samp_quantize_weight(const uint16_t *W, int32_t N, int32_t K, int8_t *Wq, float *s_w, void *stream);

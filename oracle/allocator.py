@@ -2,11 +2,11 @@
 
 TEST INFRASTRUCTURE ONLY, like the rest of this package.
 
-Two procedures of the paper, written in its notation:
+Two procedures of the paper:
 
 * decay_aware_allocate(A, L): the Accuracy-Decay-Aware allocator (Section 3.2, Algorithm 1).  A[i], L[i] are the
   accuracy and the latency of setting i of a mode (i = 0 is the all-FP16 setting, larger i quantises more layers);
-  the result Lq is the index of the recommended setting.
+  the result is the index of the recommended setting.
 * recommend(A, L, max_latency, min_accuracy): the threshold rules of Appendix A.
 
 Readings where the paper is silent (the library takes the same readings):
@@ -23,24 +23,29 @@ import math
 from typing import List, Optional, Sequence
 
 
+def decay_rate(A: Sequence[float], L: Sequence[float], frm: int, to: int) -> Optional[float]:
+    """Accuracy change per unit of latency change when moving from setting `frm` to setting `to`.  Equal latencies
+    (the quotient is undefined): -inf for an accuracy gain, +inf for a loss, None when nothing changes."""
+    gain, cost = A[to] - A[frm], L[to] - L[frm]
+    if cost != 0.0:
+        return gain / cost
+    if gain == 0.0:
+        return None
+    return -math.inf if gain > 0.0 else math.inf
+
+
 def decay_aware_allocate(A: Sequence[float], L: Sequence[float]) -> int:
-    """Algorithm 1.  Walks the settings in order, keeping a recommended setting (A_rec, L_rec); setting i replaces it
-    when its decay rate dr = (A_i - A_rec) / (L_i - L_rec) is negative or smaller than the smallest rate seen."""
+    """Algorithm 1.  One pass over the settings in order of increasing quantisation, starting from the all-FP16
+    setting.  A candidate takes over as the recommendation when its decay rate against the current recommendation is
+    negative, or lower than every rate that has taken over before; the rate it took over with becomes the bar for
+    the candidates after it."""
     assert len(A) == len(L) and len(A) >= 1
-    dr_min = math.inf                       # MAX_FLOAT
-    A_rec, L_rec, Lq = A[0], L[0], 0        # i == 0: the FP16 setting
-    for i in range(1, len(A)):
-        dA, dL = A[i] - A_rec, L[i] - L_rec
-        if dL == 0.0:
-            if dA == 0.0:
-                continue
-            dr = -math.inf if dA > 0.0 else math.inf
-        else:
-            dr = dA / dL
-        if dr < 0.0 or dr < dr_min:
-            dr_min = dr
-            A_rec, L_rec, Lq = A[i], L[i], i
-    return Lq
+    chosen, bar = 0, math.inf
+    for cand in range(1, len(A)):
+        rate = decay_rate(A, L, chosen, cand)
+        if rate is not None and (rate < 0.0 or rate < bar):
+            chosen, bar = cand, rate
+    return chosen
 
 
 def recommend(A: Sequence[float], L: Sequence[float], max_latency: Optional[float] = None,

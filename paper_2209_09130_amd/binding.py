@@ -164,6 +164,9 @@ class Encoder:
 
     def forward(self, hidden: torch.Tensor, mask: Optional[torch.Tensor] = None,
                 out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """samp_encoder_forward.  Pass the same `out` tensor on every call to get graph replay: the library keys its
+        recorded graphs on the argument pointers, and a fresh output tensor per call is a new argument set each time
+        (plain launches, and it pushes older graphs out of the cache)."""
         assert hidden.dtype == torch.float16 and hidden.dim() == 3
         B, S, H = hidden.shape
         ws = self._workspace(B, S)
@@ -308,6 +311,14 @@ def gelu_quant(y: torch.Tensor, s_out: float, want_fast: bool = False):
     fast = torch.empty(n, dtype=torch.float32, device=y.device) if want_fast else None
     _check(lib().samp_gelu_quant(_dp(y), C.c_int64(n), _f(s_out), _dp(codes), _dp(fast), _stream()))
     return (codes, fast) if want_fast else codes
+
+
+def quantize_f16_i8(x: torch.Tensor, s_x: float) -> torch.Tensor:
+    """samp_quantize_f16_i8: int8 codes of an fp16 tensor (element count a multiple of 8)."""
+    assert x.dtype == torch.float16
+    out = torch.empty(x.shape, dtype=torch.int8, device=x.device)
+    _check(lib().samp_quantize_f16_i8(_dp(x), C.c_int64(x.numel()), _f(s_x), _dp(out), _stream()))
+    return out
 
 
 def quantize_weight(W: torch.Tensor):

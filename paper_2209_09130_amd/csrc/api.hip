@@ -69,6 +69,7 @@ int check_config(const samp_config_t *c)
 {
     if (!c) return fail(SAMP_ERR_ARG, "config is NULL");
     if (c->layers < 1 || c->heads < 1 || c->max_batch < 1) return fail(SAMP_ERR_SHAPE, "layers, heads, max_batch must be >= 1");
+    if (c->max_batch > SAMP_MAX_BATCH) return fail(SAMP_ERR_SHAPE, "max_batch must not exceed %d sequences", SAMP_MAX_BATCH);
     if (c->hidden != c->heads * 64) return fail(SAMP_ERR_SHAPE, "head size hidden/heads must be 64 (hidden=%d heads=%d)", c->hidden, c->heads);
     if (c->hidden % 128 || c->hidden > 2048) return fail(SAMP_ERR_SHAPE, "hidden must be a multiple of 128, at most 2048");
     if (c->ffn < 128 || c->ffn % 128) return fail(SAMP_ERR_SHAPE, "ffn must be a positive multiple of 128");
@@ -111,7 +112,7 @@ struct samp_encoder {
     bool streams_ready = false;
     // whole-forward HIP graphs, one per distinct argument set (the forward is launch-bound: a few
     // hundred kernels of 5..30 microseconds); captured on an internal stream, replayed on the caller's
-    struct Graph { const void *hidden, *mask, *out, *ws; int B, S, G; int seen; hipGraphExec_t exec; const void *seg; samp_embedding_t emb; };
+    struct Graph { const void *hidden, *mask, *out, *ws; int B, S, G; int seen; hipGraphExec_t exec; const void *seg; samp_embedding_t emb; int tuning; };
     std::vector<Graph> graphs;
     bool graphs_enabled = true;
     hipStream_t cap = nullptr;
@@ -538,17 +539,20 @@ static int forward_common(samp_encoder_t *enc, const void *hidden, const Ids *id
     if (!enc->graphs_enabled || enc->prof_which != SAMP_PROF_OFF) return forward_eager(enc, hidden, ids, mask, B, S, out, workspace, st);
 
     const int G = choose_groups(enc, B, S);
+    // a recorded graph holds the tile configurations in force when it was captured: the process-wide tuning
+    // override is part of the key, so that a changed override records anew instead of replaying the old choice
+    const int tuning = gemm_config_override.load(std::memory_order_relaxed);
     samp_encoder::Graph *g = nullptr;
     for (auto &e : enc->graphs)
         if (e.hidden == key && e.seg == key_seg && std::memcmp(&e.emb, &key_emb, sizeof(key_emb)) == 0 && e.mask == mask && e.out == out && e.ws == workspace &&
-            e.B == B && e.S == S && e.G == G) g = &e;
+            e.B == B && e.S == S && e.G == G && e.tuning == tuning) g = &e;
     if (g && g->exec) { HIP_TRY(hipGraphLaunch(g->exec, st)); return SAMP_OK; }
     if (!g) {                                       // first sight of these arguments: run eagerly (one-off set-up happens here)
         if (enc->graphs.size() >= 8) {
             if (enc->graphs.front().exec) (void)hipGraphExecDestroy(enc->graphs.front().exec);
             enc->graphs.erase(enc->graphs.begin());
         }
-        enc->graphs.push_back({key, mask, out, workspace, B, S, G, 1, nullptr, key_seg, key_emb});
+        enc->graphs.push_back({key, mask, out, workspace, B, S, G, 1, nullptr, key_seg, key_emb, tuning});
         return forward_eager(enc, hidden, ids, mask, B, S, out, workspace, st);
     }
     // second sight: record the same launches into a graph on an internal stream, then replay it
@@ -584,6 +588,7 @@ int samp_encoder_calibrate(samp_encoder_t *enc, const void *hidden, const int32_
 {
     if (int rc = check_forward_args(enc, hidden, B, S, workspace, workspace_bytes)) return rc;
     if (!scales_out) return fail(SAMP_ERR_ARG, "scales_out is NULL");
+    if (!aligned(hidden, 16)) return fail(SAMP_ERR_ARG, "hidden must be 16-byte aligned");
     if (!enc->all_fp16) return fail(SAMP_ERR_ARG, "calibration needs an encoder whose layers are all SAMP_FP16");
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (int rc = run(enc, hidden, nullptr, mask, B, S, nullptr, workspace, st, true)) return rc;
@@ -743,6 +748,16 @@ int samp_gelu_quant(const float *y, int64_t n, float s_out, int8_t *codes, float
     return SAMP_OK;
 }
 
+int samp_quantize_f16_i8(const uint16_t *x, int64_t n, float s_x, int8_t *out, void *stream)
+{
+    if (!x || !out) return fail(SAMP_ERR_ARG, "NULL pointer");
+    if (n < 8 || n % 8) return fail(SAMP_ERR_SHAPE, "n must be a positive multiple of 8");
+    if (!good_scale(s_x)) return fail(SAMP_ERR_SCALE, "s_x must be finite and positive");
+    if (!aligned(x, 16) || !aligned(out, 8)) return fail(SAMP_ERR_ARG, "x must be 16-byte and out 8-byte aligned");
+    HIP_TRY(launch_quantize_rows((const __half *)x, (size_t)n, s_x, out, (hipStream_t)stream, nullptr));
+    return SAMP_OK;
+}
+
 int samp_quantize_weight(const uint16_t *W, int32_t N, int32_t K, int8_t *Wq, float *s_w, void *stream)
 {
     if (!W || !Wq || !s_w) return fail(SAMP_ERR_ARG, "NULL pointer");
@@ -814,7 +829,7 @@ int samp_pack_rows(const uint16_t *hidden, const int32_t *mask, int32_t B, int32
 {
     if (!hidden || !mask || !packed || !cu || !row_map) return fail(SAMP_ERR_ARG, "NULL pointer");
     if (B < 1 || S < 1 || H < 8 || H % 8) return fail(SAMP_ERR_SHAPE, "B, S >= 1 and H %% 8 == 0 required");
-    if (B > 8192) return fail(SAMP_ERR_SHAPE, "B too large");
+    if (B > SAMP_MAX_BATCH) return fail(SAMP_ERR_SHAPE, "B must not exceed %d sequences", SAMP_MAX_BATCH);
     HIP_TRY(launch_seq_offsets(mask, B, S, cu, (hipStream_t)stream));
     HIP_TRY(launch_pack_rows((const __half *)hidden, cu, B, S, H, s_x, packed, row_map, nullptr, (hipStream_t)stream, nullptr));
     return SAMP_OK;

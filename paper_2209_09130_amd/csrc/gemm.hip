@@ -148,6 +148,48 @@ struct EpiGeluQuant {
     }
 };
 
+// The same decision through the threshold table of gelu_table.hip: the bin of y comes out of one fused
+// multiply-add (the addend carries 2^23, so the adder rounds to an integer that sits in the low mantissa
+// bits), the bin's entry holds the binary32 number at which the code changes inside the bin and the codes
+// on either side.  Exact by construction (the table is built from the binary64 definition), about ten
+// vector operations and one 8-byte LDS read per element, no transcendental and no slow path.
+// The table (at most 16 KiB) is copied into LDS behind the per-channel tables when the block starts.
+struct EpiGeluTable {
+    const float *m, *bias; const uint32_t *entries; float rate, offset, t_max; int bins;
+    static constexpr int OUT_BYTES = 1;
+    static constexpr bool STAGED = true;
+    static constexpr int NTAB = 2;
+    typedef int pack_t;
+    __host__ __device__ int extra_lds_bytes() const { return bins * 8; }
+    __device__ __forceinline__ void load_tables(float *tab, int n0, int bn, int tid, int nthreads) const
+    {
+        copy_table(tab, m, n0, bn, tid, nthreads);
+        copy_table(tab + bn, bias, n0, bn, tid, nthreads);
+        v2i *lut = reinterpret_cast<v2i *>(tab + 2 * bn);
+        for (int i = tid; i < bins; i += nthreads) lut[i] = reinterpret_cast<const v2i *>(entries)[i];
+    }
+    __device__ __forceinline__ void tile(const v16i &acc, const float *tab, int bn, int n_loc, int n_glob, int g, int (&pk)[4]) const
+    {
+        const v2i *lut = reinterpret_cast<const v2i *>(tab + 2 * bn);
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+            const int n = n_loc + 8 * q + 4 * g;
+            const v4f mm = *reinterpret_cast<const v4f *>(tab + n);
+            const v4f bb = *reinterpret_cast<const v4f *>(tab + bn + n);
+            unsigned c[4];
+#pragma unroll
+            for (int t = 0; t < 4; t++) {
+                const float y = __builtin_fmaf((float)acc[4 * q + t], mm[t], bb[t]);
+                const float pos = __builtin_amdgcn_fmed3f(__builtin_fmaf(y, rate, offset), 8388608.0f, t_max);
+                const v2i e = lut[__float_as_uint(pos) - 0x4B000000u];
+                c[t] = y >= __int_as_float(e.x) ? (unsigned)e.y >> 8 : (unsigned)e.y;
+            }
+            const unsigned lo = __builtin_amdgcn_perm(c[1], c[0], 0x0c0c0400u), hi = __builtin_amdgcn_perm(c[3], c[2], 0x0c0c0400u);
+            pk[q] = (int)__builtin_amdgcn_perm(hi, lo, 0x05040100u);
+        }
+    }
+};
+
 struct EpiF16 {                                   // fp16(act(acc + bias[n]))
     const float *bias; bool gelu;
     static constexpr int OUT_BYTES = 2;
@@ -168,6 +210,9 @@ struct EpiF16 {                                   // fp16(act(acc + bias[n]))
         }
     }
 };
+
+template <class Epi> auto extra_lds_of(const Epi &e, int) -> decltype(e.extra_lds_bytes()) { return e.extra_lds_bytes(); }
+template <class Epi> int extra_lds_of(const Epi &, long) { return 0; }
 
 // wait until at most N vector-memory operations of this wave are outstanding and all of its LDS
 // reads have returned, then barrier.  The "memory" clobber keeps the compiler from moving LDS

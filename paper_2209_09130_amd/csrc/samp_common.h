@@ -161,11 +161,21 @@ inline void launch_kernel(K kern, dim3 grid, dim3 block, size_t lds, hipStream_t
 // Row limit of a launch: rows = *dev_rows if dev_rows != nullptr, else host_rows.
 struct Rows { int host_rows; const int *dev_rows; };
 
+// Threshold table of the FFN1 epilogue (gelu_table.hip): bin(y) = low mantissa bits of
+// med3(fmaf(y, rate, offset), 2^23, t_max); entry i = { binary32 Y_i, lo | hi << 8 }, code = y >= Y_i ? hi : lo.
+constexpr int GELU_TABLE_MAX_BINS = 2048;
+struct GeluTableSpec { float rate, offset, t_max; int bins; };
+bool gelu_table_build(float inv_s, GeluTableSpec *sp, uint32_t *entries /* host, 2 * GELU_TABLE_MAX_BINS */);
+struct GeluTable { GeluTableSpec spec; const uint32_t *entries; };        // entries: device memory, 2 * spec.bins words
+
 enum GemmEpilogue { EPI_RAW_I32, EPI_REQUANT, EPI_GELU_QUANT };
 extern std::atomic<int> gemm_config_override;                           // < 0: choose the tile configuration by shape
 
+// gelu_table (EPI_GELU_QUANT only, may be null): the threshold table of this inv_s_out; without it the epilogue
+// evaluates GELU per element (certified binary32 fast path, binary64 where a rounding tie is near)
 hipError_t launch_gemm_i8(GemmEpilogue epi, const int8_t *A, const int8_t *W, void *out, const float *m, const float *b,
-                          float inv_s_out, Rows rows, int N, int K, hipStream_t st, const Timing *tm);
+                          float inv_s_out, const GeluTable *gelu_table, Rows rows, int N, int K, hipStream_t st,
+                          const Timing *tm);
 hipError_t launch_gemm_f16(const __half *A, const __half *W, const float *bias, bool gelu, __half *out, Rows rows,
                            int N, int K, hipStream_t st, const Timing *tm);
 

@@ -55,6 +55,9 @@ def test_invalid_arguments_become_error_codes_on_the_host(L):
     too_many = _Config(2, 768, 12, 3072, 8192, 4096, 1e-12)                         # 2^25 token rows
     assert L.samp_encoder_arena_bytes(C.byref(too_many), modes) == 0
     assert b"tokens" in L.samp_last_error()
+    too_wide = _Config(2, 768, 12, 3072, 8193, 16, 1e-12)                           # the sequence-offset kernel's limit
+    assert L.samp_encoder_arena_bytes(C.byref(too_wide), modes) == 0
+    assert b"max_batch" in L.samp_last_error()
     assert L.samp_encoder_arena_bytes(C.byref(ok), (C.c_uint8 * 2)(16, 0)) == 0
     assert L.samp_encoder_arena_bytes(C.byref(ok), (C.c_uint8 * 2)(8, 0)) == 0       # a binary16 softmax output needs an INT8 MHA
     assert L.samp_encoder_arena_bytes(C.byref(ok), (C.c_uint8 * 2)(13, 0)) == 0      # ... and excludes the unsigned codes

@@ -6,9 +6,12 @@ Bar: layer outputs within max-abs 2e-2 and mean-abs 2e-3 of the oracle.
   * A layer that mixes an FP16 block with a quantised one can differ from the oracle by one int8 code
     at isolated elements of the quantised residual stream: binary32 MFMA accumulation order against
     binary64 in the oracle decides an fp16 rounding, which decides a code; both codes are valid
-    roundings of values that agree to ~1e-5.  Such a layer is required to have mean-abs <= 2e-3 on
-    all elements, max-abs <= 2e-2 on all but a fraction <= 2e-3 of them, nothing off by more than a
-    few code steps ("flips" below).
+    roundings of values that agree to ~1e-5 (tests/test_gpu_code_flips.py shows, tensor by tensor,
+    that these one-step flips are the only differences and that rows without one meet the bar).  Such a
+    stack is required here to have mean-abs <= 2e-3 on all elements, max-abs <= 2e-2 on all but a
+    fraction <= 2e-3 of them, and nothing off by more than loose_bound(): one step of the coarsest code on
+    the residual stream moves a LayerNorm output by about 1.5 steps at most (step / row deviation, times
+    gamma), and two such flips may meet in one element of a short stack.
   * A flipped code perturbs the next layer's input and quantisers amplify perturbations (each
     flipped element of the residual stream flips a few more codes per layer), so after many mixed
     layers two correct implementations decorrelate at the level of the quantisation noise itself.
@@ -74,7 +77,8 @@ def teacher_forced_layers(P, w, wts, sc, hid, lens, mask, label):
                         ln_eps=w.ln_eps)
         want = oracle.Encoder(*layer_args(w, l), w1.modes, wts[l:l + 1], sc[l:l + 1]).forward(x, lens)
         got = run_gpu(P, w1, wts[l:l + 1], sc[l:l + 1], x, mask)
-        compare(got, want, lens, STRICT[w.modes[l]], f"{label} layer {l} {W.MODE_NAMES[w.modes[l]]} (teacher forced)")
+        compare(got, want, lens, STRICT_ONE_LAYER[w.modes[l]], f"{label} layer {l} {W.MODE_NAMES[w.modes[l]]} (teacher forced)",
+                loose_bound(w1.modes, sc[l:l + 1]) if w.modes[l] else None)
         x = want
 
 
@@ -94,7 +98,15 @@ def valid_against_reference(got, want, ref, lens, label):
     assert dd.mean() <= 2.0 * dw.mean()
 
 
-def compare(got, want, lens, strict, label=""):
+def loose_bound(modes, sc):
+    """Largest difference a stack with fp16 -> int8 hand-overs may show on isolated elements: three steps of the
+    coarsest code on its residual stream (layer inputs of INT8 attention blocks, LayerNorm-1 outputs of INT8
+    feed-forward blocks)."""
+    steps = [float(sc[l, 0]) for l, m in enumerate(modes) if m & 1] + [float(sc[l, 7]) for l, m in enumerate(modes) if m & 2]
+    return 3.0 * max(steps)
+
+
+def compare(got, want, lens, strict, label="", bound=None):
     B, S, H = got.shape
     diffs = []
     for b in range(B):
@@ -110,7 +122,7 @@ def compare(got, want, lens, strict, label=""):
         assert d.max() <= MAX_ABS
     else:
         assert frac_bad <= 2e-3
-        assert d.max() <= 0.25
+        assert d.max() <= bound, f"{d.max():.4g} exceeds the flip bound {bound:.4g}"
     return d
 
 
@@ -121,6 +133,9 @@ def small(modes, batch=5, seq=48, varlen=True, layers=None):
 
 
 STRICT = {FP16: True, FULL_INT8: True, MHA_INT8: False, FFN_INT8: False}
+# a layer on its own (its input is fp16, its output too): an INT8 attention block followed by an FP16 feed-forward
+# block has no quantiser behind an fp16 GEMM, so it meets the plain bar; Quant-FFN-Only has one (LayerNorm-1)
+STRICT_ONE_LAYER = {FP16: True, FULL_INT8: True, MHA_INT8: True, FFN_INT8: False}
 
 
 @pytest.mark.parametrize("mode", [FP16, FULL_INT8, FFN_INT8, MHA_INT8])
@@ -132,7 +147,7 @@ def test_small_encoder_every_mode(P, mode, varlen):
     sc = oracle.calibrate(*args(w), wts, W.make_calibration_batch(w))
     want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid, lens)
     got = run_gpu(P, w, wts, sc, hid, mask if varlen else None)
-    d = compare(got, want, lens, STRICT[mode], f"small {W.MODE_NAMES[mode]} varlen={varlen}")
+    d = compare(got, want, lens, STRICT[mode], f"small {W.MODE_NAMES[mode]} varlen={varlen}", loose_bound(w.modes, sc) if mode else None)
     if mode == FULL_INT8:
         # every decision on this path is reproducible: the fp16 outputs are bit-identical
         assert (d == 0).all()
@@ -147,7 +162,7 @@ def test_small_encoder_mixed_masks_and_transitions(P, modes):
     sc = oracle.calibrate(*args(w), wts, W.make_calibration_batch(w))
     want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid, lens)
     got = run_gpu(P, w, wts, sc, hid, mask)
-    compare(got, want, lens, False, f"small mixed {modes}")
+    compare(got, want, lens, False, f"small mixed {modes}", loose_bound(modes, sc))
 
 
 def test_padding_is_inert_and_single_token_sequences_work(P):
@@ -165,7 +180,7 @@ def test_padding_is_inert_and_single_token_sequences_work(P):
     got2 = run_gpu(P, w, wts, sc, hid2, mask)
     assert np.array_equal(got, got2)
     want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid, lens)
-    compare(got, want, lens, False, "padding")
+    compare(got, want, lens, False, "padding", loose_bound(w.modes, sc))
 
 
 def test_c1_single_layer_bert_base_ffn_int8(P):
@@ -175,7 +190,7 @@ def test_c1_single_layer_bert_base_ffn_int8(P):
     sc = oracle.calibrate(*args(w), wts, W.make_calibration_batch(w))
     want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid, lens)
     got = run_gpu(P, w, wts, sc, hid, None)
-    compare(got, want, lens, False, "C1")
+    compare(got, want, lens, False, "C1", loose_bound(w.modes, sc))
 
 
 
@@ -210,7 +225,7 @@ def test_small_encoder_with_unsigned_softmax_codes_is_bit_identical(P, varlen):
     sc = unsigned_p_scales(oracle.calibrate(*args(w), wts, W.make_calibration_batch(w)))
     want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid, lens)
     got = run_gpu(P, w, wts, sc, hid, mask if varlen else None)
-    compare(got, want, lens, False, f"small unsigned-P varlen={varlen}")     # layer 1 has an FP16 FFN
+    compare(got, want, lens, False, f"small unsigned-P varlen={varlen}", loose_bound(w.modes, sc))     # layer 1 has an FP16 FFN
     w = small((FULL_INT8 | P_UNSIGNED,) * 3, varlen=varlen)
     want = oracle.Encoder(*args(w), w.modes, wts[:3], sc[:3]).forward(hid, lens)
     got = run_gpu(P, w, wts[:3], sc[:3], hid, mask if varlen else None)
@@ -259,7 +274,7 @@ def test_small_encoder_with_binary16_softmax_output_is_bit_identical(P, varlen):
     sc[0, 4] = np.float32("nan")                                # the softmax step of a binary16-P layer is never read
     want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid, lens)
     got = run_gpu(P, w, wts, sc, hid, mask if varlen else None)
-    compare(got, want, lens, False, f"small mixed softmax variants varlen={varlen}")
+    compare(got, want, lens, False, f"small mixed softmax variants varlen={varlen}", loose_bound(w.modes, sc))
 
 
 def test_c2_fully_quant_with_binary16_softmax_output(P):
@@ -305,7 +320,7 @@ def test_encoder_from_ids_through_the_embedding_kernel(P, modes, varlen):
     enc.close()
     for o in outs[1:]:
         assert np.array_equal(o, outs[0])
-    d = compare(outs[0], want, lens, modes[0] == FULL_INT8, f"from ids {modes} varlen={varlen}")
+    d = compare(outs[0], want, lens, modes[0] == FULL_INT8, f"from ids {modes} varlen={varlen}", loose_bound(modes, sc))
     if all(m == FULL_INT8 for m in modes):
         assert (d == 0).all()
 
@@ -373,6 +388,17 @@ def test_c5_long_sequences(P):
     assert (d == 0).all()
 
 
+def test_c4_quant_ffn_only_all_24_layers_teacher_forced(P):
+    """BERT-large, batch 32 x 256 with outlier channels, Quant-FFN-Only at full depth: every one of the 24 layers on
+    its own at the full batch shape, GPU and oracle fed the oracle's previous output on two sampled sequences."""
+    w = W.config("C4").with_modes(FFN_INT8)
+    wts = W.make_weights(w)
+    hid, lens, _ = W.make_hidden(w)
+    sc = oracle.calibrate(*args(w), wts, W.make_calibration_batch(w))
+    pick = [0, 31]
+    teacher_forced_layers(P, w, wts, sc, hid[pick], lens[pick], None, "C4 FFN_INT8")
+
+
 @pytest.mark.parametrize("name,pick", [("C4", [0, 31]), ("C5", [0, 127])])
 def test_c4_and_c5_at_full_depth_on_sampled_sequences(P, name, pick):
     """The two large configurations exactly as bench.py runs them (all layers, full batch, Fully-Quant, no mask):
@@ -417,7 +443,8 @@ def test_random_small_configurations(P, seed):
     want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid, lens)
     got = run_gpu(P, w, wts, sc, hid, mask if w.varlen else None)
     exact = all((m & 3) == FULL_INT8 for m in modes)
-    d = compare(got, want, lens, exact or all(m == FP16 for m in modes), f"random {seed}: H{w.hidden} F{w.ffn} B{w.batch} S{seq} {modes}")
+    d = compare(got, want, lens, exact or all(m == FP16 for m in modes), f"random {seed}: H{w.hidden} F{w.ffn} B{w.batch} S{seq} {modes}",
+                loose_bound(modes, sc) if any(modes) else None)
     if exact:
         assert (d == 0).all()
 
@@ -437,7 +464,7 @@ def test_encoder_with_sequences_longer_than_512_tokens(P, modes):
     want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid, lens)
     got = run_gpu(P, w, wts, sc, hid, mask)
     exact = all((m & 3) == FULL_INT8 for m in modes)
-    d = compare(got, want, lens, exact, f"long rows {modes}")
+    d = compare(got, want, lens, exact, f"long rows {modes}", loose_bound(modes, sc))
     if exact:
         assert (d == 0).all()
 
@@ -452,7 +479,7 @@ def test_widest_supported_hidden_size(P, modes):
     sc = oracle.calibrate(*args(w), wts, W.make_calibration_batch(w))
     want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid, lens)
     got = run_gpu(P, w, wts, sc, hid, mask)
-    d = compare(got, want, lens, modes[0] in (FULL_INT8, FP16), f"hidden 2048 {modes}")
+    d = compare(got, want, lens, modes[0] in (FULL_INT8, FP16), f"hidden 2048 {modes}", loose_bound(modes, sc) if modes[0] else None)
     if modes[0] == FULL_INT8:
         assert (d == 0).all()
 
@@ -575,7 +602,7 @@ def test_batch_groups_and_graph_replay_do_not_change_results(P, varlen):
                 assert torch.equal(out, base), (groups, graph, rep)
     enc.close()
     want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid, lens)
-    compare(base.cpu().numpy(), want, lens, False, f"groups/graph varlen={varlen}")
+    compare(base.cpu().numpy(), want, lens, False, f"groups/graph varlen={varlen}", loose_bound(w.modes, sc))
 
 
 @pytest.mark.parametrize("varlen", [False, True])

@@ -458,3 +458,40 @@ def test_classification_target_within_accumulation_tolerance(P, B, S, H, Cn):
     # binary32 accumulation over H terms and a binary32 tanh against binary64: a few 1e-6 relative
     assert np.abs(got - want).max() <= 2e-5 * max(1.0, np.abs(want).max())
     assert np.array_equal(got.argmax(axis=1), want.argmax(axis=1))
+
+
+def test_entry_quantiser_bit_exact(P):
+    """samp_quantize_f16_i8: the un-masked entry quantiser, incl. ties, values beyond the clamp and a ragged tail of
+    the grid (element count not a multiple of the block size)."""
+    rng = np.random.default_rng(3)
+    s_x = 0.0371
+    x = (rng.standard_normal(1000 * 768 + 8) * 1.3).astype(np.float16)
+    x[:16] = np.float16([0.5 * s_x, 1.5 * s_x, 2.5 * s_x, -0.5 * s_x, 127.4 * s_x, 127.6 * s_x, 400.0, -400.0,
+                         0.0, -0.0, 6e-8, -6e-8, 65504.0, -65504.0, s_x, -s_x])
+    got = host(P.quantize_f16_i8(dev(x), s_x))
+    assert np.array_equal(got, oracle.quantize_f16(x, s_x))
+    assert got.max() == 127 and got.min() == -127
+
+
+def test_a_sequence_with_an_all_zero_mask_row_is_inert(P):
+    """The mask is not checked on the host (no synchronisation): an empty sequence takes part in nothing, its output
+    rows are zeros, and the other sequences get exactly what they get without it."""
+    import torch
+    import samp_workloads as W
+    w = W.Workload("empty", 2, 128, 2, 256, 4, 24, (W.FULL_INT8, W.FFN_INT8), varlen=True, min_len=1, plain_params=False,
+                   calib_batch=2, calib_seq=24)
+    wts = W.make_weights(w)
+    hid, _, _ = W.make_hidden(w)
+    a = (w.layers, w.hidden, w.heads, w.ffn, w.ln_eps)
+    sc = oracle.calibrate(*a, wts, W.make_calibration_batch(w))
+    lens = np.array([5, 0, 24, 1], np.int32)
+    mask = (np.arange(w.seq)[None, :] < lens[:, None]).astype(np.int32)
+    enc = P.Encoder(*a, w.modes, wts, sc, max_batch=4, max_seq=24)
+    out = host(enc.forward(dev(hid), dev(mask)))
+    keep = [0, 2, 3]
+    out3 = host(enc.forward(dev(hid[keep]), dev(mask[keep])))
+    enc.close()
+    assert not out[1].any()
+    assert np.array_equal(out[keep], out3)
+    for b in range(4):
+        assert not out[b, lens[b]:].any()
