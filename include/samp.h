@@ -228,11 +228,14 @@ SAMP_API int samp_classify(const uint16_t *hidden, int32_t B, int32_t S, int32_t
  * an unsigned byte) the number of occurrences of each code among codes[0..n).                     */
 SAMP_API int samp_code_histogram(const int8_t *codes, size_t n, uint64_t *hist, void *stream);
 
-/* Tuning aid: force the tile configuration of every GEMM launched afterwards by this process
- * (0: 128x128 tile with 64-byte K stages, 1: 128x128 with 128-byte stages, 2: 64 tokens x 128
- * channels), or -1 (default) to choose by problem shape (which may also take 64 x 96 tiles).  Configurations 1 and 2 need the operand
- * rows to be multiples of 128 bytes and fall back to 0 otherwise.  Results do not depend on it
- * for INT8; FP16 sums are formed in the same order in all three.                                   */
+/* Tuning aid: force the tile configuration of every GEMM launched afterwards by this process:
+ * 0: 128x128 tile with 64-byte K stages, 1: 128x128 with 128-byte stages, 2: 64 tokens x 128 channels
+ * (32x32 .. 64x64 per wave); the large tiles with double-buffered operand fragments, 3: 256x256 with two
+ * 128-byte stages, 4: 128 tokens x 256 channels, 5: 256 tokens x 128 channels, 6: 128x192, 7: 256x256 with
+ * four 64-byte stages (64x96 .. 128x128 per wave); or -1 (default) to choose by problem shape (which may
+ * also take 64x96 tiles).  1..7 need operand rows that are multiples of 128 bytes (else 0 is taken), 3..7 a
+ * channel count that is a multiple of their tile width (else the default choice is taken).  Results do not
+ * depend on it for INT8; FP16 sums are formed in the same order in all of them.                      */
 SAMP_API int samp_set_gemm_config(int32_t config);
 
 /* ---- single steps of the path (what the encoder is made of; used by the parity tests) --------- */
@@ -246,10 +249,27 @@ SAMP_API int samp_gemm_i8_i32(const int8_t *A, const int8_t *W, int32_t *C, int3
 SAMP_API int samp_gemm_i8_requant(const int8_t *A, const int8_t *W, const float *m, const float *b, int8_t *out,
                                   int32_t M, int32_t N, int32_t K, void *stream);
 
+/* Threshold table of the FFN1 epilogue for one output step (host function, no GPU work).  The code
+ * rne(GELU(y) / s_out) is a step function of the binary32 number y alone; the table cuts the y axis
+ * into uniform bins that hold at most one step each and stores, per bin, the binary32 number at which
+ * the code changes and the codes on either side, found by bisection with the binary64 definition
+ * below.  bin(y) = low mantissa bits of clamp(fmaf(y, rate, offset), 2^23, t_max); entry i is two
+ * 32-bit words { Y_i, lo | hi << 8 }; code = y >= Y_i ? hi : lo.  host_entries: host memory of at
+ * least SAMP_GELU_TABLE_BYTES, of which the first 8 * bins bytes are written (copy those to the
+ * device).  SAMP_ERR_SCALE if the step would need more bins than the table holds.                  */
+#define SAMP_GELU_TABLE_BYTES 16384
+typedef struct { float rate, offset, t_max; int32_t bins; } samp_gelu_table_t;
+SAMP_API int samp_gelu_table_build(float s_out, samp_gelu_table_t *table, void *host_entries, size_t entries_bytes);
+
 /* INT8 GEMM + dequantise + bias + GELU + quantise (FFN1): y = fmaf(float(acc), m[n], bias[n]);
- * g = 0.5 y (1 + erf(y / sqrt 2)); out = clamp(rne(g * (1/s_out))).                               */
+ * g = 0.5 y (1 + erf(y / sqrt 2)) in binary64, rounded once; out = clamp(rne(g * (1/s_out))).
+ * table / table_entries: both NULL (GELU is evaluated per element: a certified binary32 form, and
+ * binary64 where a rounding tie is near), or the description samp_gelu_table_build wrote for this
+ * s_out and a dev copy of its entries, 8-byte aligned: the epilogue then looks the code up (same
+ * results, a third of the vector work).  The encoder builds and uses such a table per layer.        */
 SAMP_API int samp_gemm_i8_gelu_quant(const int8_t *A, const int8_t *W, const float *m, const float *bias, float s_out,
-                                     int8_t *out, int32_t M, int32_t N, int32_t K, void *stream);
+                                     const samp_gelu_table_t *table, const void *table_entries, int8_t *out, int32_t M,
+                                     int32_t N, int32_t K, void *stream);
 
 /* FP16 GEMM, binary32 accumulation: out = fp16(act(A . W^T + bias)); bias dev float [N] or NULL;
  * gelu != 0 applies GELU.  N % 128 == 0, K % 32 == 0.                                             */

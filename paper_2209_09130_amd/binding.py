@@ -241,11 +241,26 @@ def gemm_i8_requant(A, W, m, b) -> torch.Tensor:
     return out
 
 
-def gemm_i8_gelu_quant(A, W, m, bias, s_out: float) -> torch.Tensor:
+class _GeluTable(C.Structure):
+    _fields_ = [("rate", C.c_float), ("offset", C.c_float), ("t_max", C.c_float), ("bins", C.c_int32)]
+
+
+def gelu_table_build(s_out: float):
+    """samp_gelu_table_build: (description struct, host entries uint32 [bins, 2]) of the FFN1 epilogue's table."""
+    buf = np.zeros(4096, np.uint32)
+    spec = _GeluTable()
+    _check(lib().samp_gelu_table_build(_f(s_out), C.byref(spec), buf.ctypes.data_as(C.c_void_p), C.c_size_t(buf.nbytes)))
+    return spec, buf[: 2 * spec.bins].reshape(spec.bins, 2).copy()
+
+
+def gemm_i8_gelu_quant(A, W, m, bias, s_out: float, table=None) -> torch.Tensor:
+    """table: None for the per-element evaluation, or (description, device entries) from gelu_table_build(s_out)."""
     M, K = A.shape
     N = W.shape[0]
     out = torch.empty((M, N), dtype=torch.int8, device=A.device)
-    _check(lib().samp_gemm_i8_gelu_quant(_dp(A), _dp(W), _dp(m), _dp(bias), _f(s_out), _dp(out), M, N, K, _stream()))
+    spec, entries = (None, None) if table is None else table
+    _check(lib().samp_gemm_i8_gelu_quant(_dp(A), _dp(W), _dp(m), _dp(bias), _f(s_out),
+                                         C.byref(spec) if spec is not None else None, _dp(entries), _dp(out), M, N, K, _stream()))
     return out
 
 

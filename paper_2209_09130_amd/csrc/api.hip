@@ -44,6 +44,7 @@ struct Layer {
     float *m_qkv, *bq_qkv, *m_o, *m_f1, *m_f2;
     float *b_qkv, *b_o, *b_f1, *b_f2, *g1, *be1, *g2, *be2;
     float m_sc, inv_sp, m_ctx;                      // attention multipliers of an INT8 MHA block
+    GeluTable gelu;                                 // FFN1 epilogue's threshold table (entries == nullptr: none for this step)
 };
 
 struct Carver {                                     // hands out aligned pieces of a device buffer
@@ -88,6 +89,7 @@ size_t layer_arena_bytes(const samp_config_t &c, int mode)
     n += up(3 * H * H * e_mha) + up(H * H * e_mha) + up(F * H * e_ffn) + up(H * F * e_ffn);
     n += 2 * up(3 * H * 4) + up(H * 4) + up(F * 4) + up(H * 4);             // m_qkv, bq_qkv, m_o, m_f1, m_f2
     n += up(3 * H * 4) + up(F * 4) + 6 * up(H * 4);                         // biases and LayerNorm vectors
+    if (mode & 2) n += up((size_t)GELU_TABLE_MAX_BINS * 8);                 // FFN1 epilogue's threshold table
     return n;
 }
 
@@ -235,7 +237,7 @@ int run(samp_encoder_t *enc, const void *hidden, const Ids *ids, const int32_t *
 
         if (mha8) {
             HIP_TRY(launch_gemm_i8(EPI_REQUANT, (const int8_t *)x, (const int8_t *)Y.w_qkv, w.qkv, Y.m_qkv, Y.bq_qkv, 0.f,
-                                   rows, 3 * H, H, st, timing(enc, SAMP_PROF_QKV)));
+                                   nullptr, rows, 3 * H, H, st, timing(enc, SAMP_PROF_QKV)));
             if (Y.mode & SAMP_P_FP16)
                 HIP_TRY(launch_attention_i8_p16((const int8_t *)w.qkv, cu, B, S, H, heads, Y.m_sc, Y.m_ctx, (int8_t *)w.ctx, st,
                                                 timing(enc, SAMP_PROF_ATTN)));
@@ -244,7 +246,7 @@ int run(samp_encoder_t *enc, const void *hidden, const Ids *ids, const int32_t *
                                             (Y.mode & SAMP_P_UNSIGNED) != 0, (int8_t *)w.ctx, nullptr, st,
                                             timing(enc, SAMP_PROF_ATTN)));
             HIP_TRY(launch_gemm_i8(EPI_REQUANT, (const int8_t *)w.ctx, (const int8_t *)Y.w_o, w.ao, Y.m_o, nullptr, 0.f,
-                                   rows, H, H, st, timing(enc, SAMP_PROF_ATTN_OUT)));
+                                   nullptr, rows, H, H, st, timing(enc, SAMP_PROF_ATTN_OUT)));
         } else {
             if (am) HIP_TRY(launch_absmax_f16((const __half *)x, rows, H, H, am + 0, st));
             HIP_TRY(launch_gemm_f16((const __half *)x, (const __half *)Y.w_qkv, Y.b_qkv, false, (__half *)w.qkv, rows,
@@ -266,9 +268,9 @@ int run(samp_encoder_t *enc, const void *hidden, const Ids *ids, const int32_t *
         }
         if (ffn8) {
             HIP_TRY(launch_gemm_i8(EPI_GELU_QUANT, (const int8_t *)w.h1, (const int8_t *)Y.w_f1, w.f1, Y.m_f1, Y.b_f1,
-                                   1.0f / Y.s.ffn_mid, rows, F, H, st, timing(enc, SAMP_PROF_FFN1)));
+                                   1.0f / Y.s.ffn_mid, &Y.gelu, rows, F, H, st, timing(enc, SAMP_PROF_FFN1)));
             HIP_TRY(launch_gemm_i8(EPI_REQUANT, (const int8_t *)w.f1, (const int8_t *)Y.w_f2, w.f2, Y.m_f2, nullptr, 0.f,
-                                   rows, H, F, st, timing(enc, SAMP_PROF_FFN2)));
+                                   nullptr, rows, H, F, st, timing(enc, SAMP_PROF_FFN2)));
         } else {
             HIP_TRY(launch_gemm_f16((const __half *)w.h1, (const __half *)Y.w_f1, Y.b_f1, true, (__half *)w.f1, rows, F, H,
                                     st, timing(enc, SAMP_PROF_FFN1)));
@@ -349,6 +351,7 @@ int samp_encoder_create(const samp_config_t *cfg, const uint8_t *modes, const sa
     __half *stage = cv.take<__half>(big * H);
     float *s_w = cv.take<float>(big);
 
+    std::vector<std::vector<uint32_t>> gelu_host;                // staging of the tables until the stream has copied them
     auto body = [&]() -> int {
         for (int l = 0; l < cfg->layers; l++) {
             Layer &Y = E->L[l];
@@ -399,6 +402,17 @@ int samp_encoder_create(const samp_config_t *cfg, const uint8_t *modes, const sa
             if (mha8) HIP_TRY(launch_fold(nullptr, Y.s.ctx, s_w, nullptr, Y.s.attn_out, (int)H, Y.m_o, nullptr, st));
             if (int rc = matrix(w.w_ffn1, F, H, ffn8, &Y.w_f1)) return rc;
             if (ffn8) HIP_TRY(launch_fold(nullptr, Y.s.ffn_in, s_w, nullptr, 1.0f, (int)F, Y.m_f1, nullptr, st));
+            Y.gelu = GeluTable{{0.f, 0.f, 0.f, 0}, nullptr};
+            if (ffn8) {
+                // built on the host from the binary64 definition; a step too fine for a table of this size keeps the
+                // per-element evaluation
+                uint32_t *dev_entries = cv.take<uint32_t>((size_t)GELU_TABLE_MAX_BINS * 2);
+                gelu_host.emplace_back((size_t)GELU_TABLE_MAX_BINS * 2);
+                if (gelu_table_build(1.0f / Y.s.ffn_mid, &Y.gelu.spec, gelu_host.back().data())) {
+                    HIP_TRY(hipMemcpyAsync(dev_entries, gelu_host.back().data(), (size_t)Y.gelu.spec.bins * 8, hipMemcpyHostToDevice, st));
+                    Y.gelu.entries = dev_entries;
+                }
+            }
             if (int rc = matrix(w.w_ffn2, H, F, ffn8, &Y.w_f2)) return rc;
             if (ffn8) HIP_TRY(launch_fold(nullptr, Y.s.ffn_mid, s_w, nullptr, Y.s.ffn_out, (int)H, Y.m_f2, nullptr, st));
         }
@@ -654,7 +668,7 @@ static int check_gemm(const void *A, const void *W, const void *out, int M, int 
 int samp_gemm_i8_i32(const int8_t *A, const int8_t *W, int32_t *C, int32_t M, int32_t N, int32_t K, void *stream)
 {
     if (int rc = check_gemm(A, W, C, M, N, K, 64)) return rc;
-    HIP_TRY(launch_gemm_i8(EPI_RAW_I32, A, W, C, nullptr, nullptr, 0.f, Rows{M, nullptr}, N, K, (hipStream_t)stream, nullptr));
+    HIP_TRY(launch_gemm_i8(EPI_RAW_I32, A, W, C, nullptr, nullptr, 0.f, nullptr, Rows{M, nullptr}, N, K, (hipStream_t)stream, nullptr));
     return SAMP_OK;
 }
 
@@ -663,17 +677,41 @@ int samp_gemm_i8_requant(const int8_t *A, const int8_t *W, const float *m, const
 {
     if (int rc = check_gemm(A, W, out, M, N, K, 64)) return rc;
     if (!m) return fail(SAMP_ERR_ARG, "multiplier table is NULL");
-    HIP_TRY(launch_gemm_i8(EPI_REQUANT, A, W, out, m, b, 0.f, Rows{M, nullptr}, N, K, (hipStream_t)stream, nullptr));
+    HIP_TRY(launch_gemm_i8(EPI_REQUANT, A, W, out, m, b, 0.f, nullptr, Rows{M, nullptr}, N, K, (hipStream_t)stream, nullptr));
     return SAMP_OK;
 }
 
-int samp_gemm_i8_gelu_quant(const int8_t *A, const int8_t *W, const float *m, const float *bias, float s_out, int8_t *out,
-                            int32_t M, int32_t N, int32_t K, void *stream)
+int samp_gemm_i8_gelu_quant(const int8_t *A, const int8_t *W, const float *m, const float *bias, float s_out,
+                            const samp_gelu_table_t *table, const void *table_entries, int8_t *out, int32_t M, int32_t N,
+                            int32_t K, void *stream)
 {
     if (int rc = check_gemm(A, W, out, M, N, K, 64)) return rc;
     if (!m || !bias) return fail(SAMP_ERR_ARG, "multiplier or bias table is NULL");
     if (!good_scale(s_out)) return fail(SAMP_ERR_SCALE, "s_out must be finite and positive");
-    HIP_TRY(launch_gemm_i8(EPI_GELU_QUANT, A, W, out, m, bias, 1.0f / s_out, Rows{M, nullptr}, N, K, (hipStream_t)stream, nullptr));
+    GeluTable gt{{0.f, 0.f, 0.f, 0}, nullptr};
+    if (table || table_entries) {
+        if (!table || !table_entries) return fail(SAMP_ERR_ARG, "a threshold table needs both its description and its entries");
+        if (!aligned(table_entries, 8)) return fail(SAMP_ERR_ARG, "table_entries must be 8-byte aligned");
+        if (table->bins < 2 || table->bins > GELU_TABLE_MAX_BINS || table->t_max != 8388608.0f + (float)(table->bins - 1) ||
+            !(table->rate > 0.0f) || !std::isfinite(table->rate) || !std::isfinite(table->offset))
+            return fail(SAMP_ERR_ARG, "the threshold table's description is not one samp_gelu_table_build wrote");
+        gt = GeluTable{{table->rate, table->offset, table->t_max, table->bins}, static_cast<const uint32_t *>(table_entries)};
+    }
+    HIP_TRY(launch_gemm_i8(EPI_GELU_QUANT, A, W, out, m, bias, 1.0f / s_out, gt.entries ? &gt : nullptr, Rows{M, nullptr}, N, K,
+                           (hipStream_t)stream, nullptr));
+    return SAMP_OK;
+}
+
+int samp_gelu_table_build(float s_out, samp_gelu_table_t *table, void *host_entries, size_t entries_bytes)
+{
+    if (!table || !host_entries) return fail(SAMP_ERR_ARG, "NULL pointer");
+    if (!good_scale(s_out)) return fail(SAMP_ERR_SCALE, "s_out must be finite and positive");
+    if (entries_bytes < SAMP_GELU_TABLE_BYTES)
+        return fail(SAMP_ERR_SPACE, "entries buffer has %zu bytes, %d needed", entries_bytes, SAMP_GELU_TABLE_BYTES);
+    GeluTableSpec sp;
+    if (!gelu_table_build(1.0f / s_out, &sp, static_cast<uint32_t *>(host_entries)))
+        return fail(SAMP_ERR_SCALE, "the step %g needs more than %d bins", (double)s_out, GELU_TABLE_MAX_BINS);
+    table->rate = sp.rate; table->offset = sp.offset; table->t_max = sp.t_max; table->bins = sp.bins;
     return SAMP_OK;
 }
 
@@ -819,7 +857,7 @@ int samp_code_histogram(const int8_t *codes, size_t n, uint64_t *hist, void *str
 
 int samp_set_gemm_config(int32_t config)
 {
-    if (config < -1 || config > 2) return fail(SAMP_ERR_ARG, "config must be -1, 0, 1 or 2");
+    if (config < -1 || config > 7) return fail(SAMP_ERR_ARG, "config must be in [-1, 7]");
     gemm_config_override = config;
     return SAMP_OK;
 }

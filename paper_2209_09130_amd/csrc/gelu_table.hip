@@ -63,24 +63,24 @@ int bin_of(float y, const GeluTableSpec &sp)
 // smallest binary32 number whose bin is >= i (i >= 1)
 float first_of_bin(int i, const GeluTableSpec &sp)
 {
-    int32_t lo = key_of(-3.0e38f), hi = key_of(3.0e38f);          // bin(lo) = 0 < i <= bin(hi)
+    int64_t lo = key_of(-3.0e38f), hi = key_of(3.0e38f);          // bin(lo) = 0 < i <= bin(hi)
     while (hi - lo > 1) {
-        const int32_t mid = lo + (hi - lo) / 2;
-        if (bin_of(float_of(mid), sp) >= i) hi = mid; else lo = mid;
+        const int64_t mid = lo + (hi - lo) / 2;
+        if (bin_of(float_of((int32_t)mid), sp) >= i) hi = mid; else lo = mid;
     }
-    return float_of(hi);
+    return float_of((int32_t)hi);
 }
 
 // Q is monotone on [a, b] and Q(a) != Q(b): smallest number in (a, b] at which Q already equals Q(b)
 float change_point(float a, float b, float inv_s)
 {
     const int qb = q_exact(b, inv_s);
-    int32_t lo = key_of(a), hi = key_of(b);
+    int64_t lo = key_of(a), hi = key_of(b);
     while (hi - lo > 1) {
-        const int32_t mid = lo + (hi - lo) / 2;
-        if (q_exact(float_of(mid), inv_s) == qb) hi = mid; else lo = mid;
+        const int64_t mid = lo + (hi - lo) / 2;
+        if (q_exact(float_of((int32_t)mid), inv_s) == qb) hi = mid; else lo = mid;
     }
-    return float_of(hi);
+    return float_of((int32_t)hi);
 }
 
 }  // namespace

@@ -22,6 +22,7 @@
 
 #include <atomic>
 #include <type_traits>
+#include <utility>
 
 namespace samp {
 namespace {
@@ -377,14 +378,17 @@ hipError_t launch_cfg(const void *A, const void *W, void *out, const Epi &epi, R
                       const Timing *tm)
 {
     constexpr int BM = 32 * WGM * TM, BN = 32 * WGN * TN;
-    constexpr size_t LDS = (size_t)NSTAGE * (BM + BN) * BKB + (size_t)Epi::NTAB * BN * sizeof(float);
+    constexpr size_t LDS_FIXED = (size_t)NSTAGE * (BM + BN) * BKB + (size_t)Epi::NTAB * BN * sizeof(float);
+    const size_t LDS = LDS_FIXED + extra_lds_of(epi, 0);
     if (N % BN) return hipErrorInvalidValue;
     if ((K * T::ELEM) % BKB) return hipErrorInvalidValue;
     auto kern = gemm_nt_kernel<T, Epi, TM, TN, BKB, NSTAGE, WPE, WGM, WGN>;
-    // > 64 KiB of dynamic LDS must be enabled once per kernel; setting it twice from two threads is harmless
+    // > 64 KiB of dynamic LDS must be enabled once per kernel (for the largest table an epilogue may bring);
+    // setting it twice from two threads is harmless
     static std::atomic<bool> attr_set{false};
     if (!attr_set.load(std::memory_order_acquire)) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)(LDS_FIXED + GELU_TABLE_MAX_BINS * 8));
         if (e != hipSuccess) return e;
         attr_set.store(true, std::memory_order_release);
     }
@@ -392,6 +396,246 @@ hipError_t launch_cfg(const void *A, const void *W, void *out, const Epi &epi, R
     launch_kernel(kern, dim3(total), dim3(64 * WGM * WGN), LDS, st, tm,
                           (const char *)A, (const char *)W, (char *)out, epi, rows.host_rows, rows.dev_rows, N, K * T::ELEM,
                           tiles_n);
+    return hipGetLastError();
+}
+
+
+// Fragment fetches of the large-tile kernel are written as ds_read_b128 instructions of its own, with
+// explicit waits: left to the compiler, every group of MFMAs is preceded by a wait for ALL outstanding
+// LDS reads, including the ones just issued for the step after it, which puts the LDS latency in front
+// of every step instead of behind the MFMAs of the step before.  tie() makes later uses of a fragment
+// depend on the wait that precedes it (an empty instruction that "rewrites" the register).
+template <int OFFSET> __device__ __forceinline__ v4i lds_read128(unsigned addr)
+{
+    v4i v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFFSET));
+    return v;
+}
+template <int STRIDE, int N, int... I>
+__device__ __forceinline__ void lds_read_frags(unsigned addr, v4i (&f)[N], std::integer_sequence<int, I...>)
+{
+    ((f[I] = lds_read128<I * STRIDE>(addr)), ...);
+}
+__device__ __forceinline__ int tie_one(v4i &f)
+{
+    asm volatile("" : "+v"(f));
+    return 0;
+}
+template <int N, int... I> __device__ __forceinline__ void tie(v4i (&f)[N], std::integer_sequence<int, I...>)
+{
+    (void)(tie_one(f[I]) + ... + 0);
+}
+template <int N> __device__ __forceinline__ void wait_lds_reads()
+{
+    static_assert(N >= 0 && N < 16, "lgkmcnt range");
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// ---- large tiles ---------------------------------------------------------------------------------
+// For many tokens the block tile grows to (64 TM) x (64 TN) with wave tiles of (32 TM) x (32 TN), up to
+// 256 x 256 with 128 x 128 per wave: a 32 x 32 x 32 MFMA takes 32 clocks and eats 2 KiB of LDS operands,
+// so a wave tile of TM x TN such products needs (TM + TN) / (TM TN) KiB per 32 clocks -- with 2 x 2 the
+// four SIMDs of a CU ask for the whole LDS bandwidth, with 4 x 4 for half of it -- and a block tile of
+// BM x BN pulls (BM + BN) bytes per BM BN multiply-adds out of L2.  One wave per SIMD, so the latencies
+// are hidden by software pipelining instead of by other waves: the K stages (64 bytes) travel through
+// an NSTAGE-deep ring of direct global->LDS loads, and the operand fragments of the next 32-byte step
+// are fetched from LDS into a second register set while the MFMAs of the current one run.
+template <class T, class Epi, int TM, int TN, int BKB, int NSTAGE, int WPE>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
+void gemm_nt_big_kernel(const char *__restrict__ A, const char *__restrict__ W, char *__restrict__ out, Epi epi, int host_rows,
+                        const int *__restrict__ dev_rows, int N, int Kbytes, int tiles_n)
+{
+    constexpr int CH = BKB / 16, RPI = 64 / CH, KS = BKB / 32, NWAVES = 4, NT = 256;
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int A_BYTES = BM * BKB, STAGE_BYTES = (BM + BN) * BKB;
+    constexpr int NLD = (BM + BN) / RPI / NWAVES;                 // 1 KiB pieces per wave and stage
+    constexpr int RING_BYTES = NSTAGE * STAGE_BYTES;
+    static_assert(BKB == 64 || BKB == 128, "stage depth");
+    static_assert(NSTAGE >= 2, "the ring must hold the stage in use and one in flight");
+    static_assert((BM + BN) % (RPI * NWAVES) == 0, "a stage must split into whole pieces per wave");
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    float *tab = reinterpret_cast<float *>(lds + RING_BYTES);
+
+    const int M = dev_rows ? *dev_rows : host_rows;
+    const int tiles = ((M + BM - 1) / BM) * tiles_n;
+    if ((int)blockIdx.x >= tiles) return;
+    const int tile = xcd_contiguous(blockIdx.x, tiles);
+    const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave >> 1) * 32 * TM, wn = (wave & 1) * 32 * TN;
+    const int r = lane & 31, g = lane >> 5;
+
+    const char *src[NLD];
+#pragma unroll
+    for (int j = 0; j < NLD; j++) {
+        const int srow = RPI * (wave + NWAVES * j) + lane / CH;
+        if (srow < BM) {
+            int am = m0 + srow; if (am > M - 1) am = M - 1;
+            src[j] = A + (size_t)am * Kbytes + (((lane % CH) ^ swz<BKB>(srow)) << 4);
+        } else {
+            const int row = srow - BM;
+            src[j] = W + (size_t)(n0 + row) * Kbytes + (((lane % CH) ^ swz<BKB>(row)) << 4);
+        }
+    }
+    const int KT = Kbytes / BKB;
+    int fill_slot = 0, fill_kt = 0;                               // next stage to request and the ring slot it goes to
+    auto issue = [&]() {
+        char *st = lds + fill_slot * STAGE_BYTES;
+#pragma unroll
+        for (int j = 0; j < NLD; j++)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[j] + (size_t)fill_kt * BKB),
+                                             (__attribute__((address_space(3))) void *)(st + (wave + NWAVES * j) * 1024), 16, 0, 0);
+        fill_kt++;
+        fill_slot = fill_slot + 1 == NSTAGE ? 0 : fill_slot + 1;
+    };
+    // LDS address of this lane's first fragment of either operand inside a stage, for each 32-byte step of a
+    // stage; the fragments of the other 32-row tiles of the wave lie whole multiples of 32 rows further on (the
+    // swizzle only looks at row bits 0..3)
+    const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
+    unsigned offa[KS], offw[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) {
+        offa[ks] = lds_base + (wm + r) * BKB + (((2 * ks + g) ^ swz<BKB>(wm + r)) << 4);
+        offw[ks] = lds_base + A_BYTES + (wn + r) * BKB + (((2 * ks + g) ^ swz<BKB>(wn + r)) << 4);
+    }
+    auto fetch = [&](int slot_bytes, int ks, v4i (&fa)[TM], v4i (&fw)[TN]) {
+        lds_read_frags<32 * BKB>(offa[ks] + slot_bytes, fa, std::make_integer_sequence<int, TM>());
+        lds_read_frags<32 * BKB>(offw[ks] + slot_bytes, fw, std::make_integer_sequence<int, TN>());
+    };
+    auto ready = [&](v4i (&fa)[TM], v4i (&fw)[TN]) {
+        tie(fa, std::make_integer_sequence<int, TM>());
+        tie(fw, std::make_integer_sequence<int, TN>());
+    };
+
+#pragma unroll
+    for (int s = 0; s < NSTAGE - 1; s++)
+        if (s < KT) issue();
+    epi.load_tables(tab, n0, BN, tid, NT);
+
+    typename T::acc_t acc[TN][TM];
+#pragma unroll
+    for (int i = 0; i < TN; i++)
+#pragma unroll
+        for (int j = 0; j < TM; j++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) acc[i][j][e] = 0;
+    auto multiply = [&](const v4i (&fa)[TM], const v4i (&fw)[TN]) {
+#pragma unroll
+        for (int i = 0; i < TN; i++)
+#pragma unroll
+            for (int j = 0; j < TM; j++) acc[i][j] = T::mma(fw[i], fa[j], acc[i][j]);
+    };
+
+    v4i fa[2][TM], fw[2][TN];                                     // fragments of the current and of the next 32-byte step
+    // stage 0 has landed when only the later prologue stages are outstanding
+    if (KT > NSTAGE - 2) wait_vm_and_barrier<(NSTAGE - 2) * NLD>(); else wait_vm_and_barrier<0>();
+    fetch(0, 0, fa[0], fw[0]);
+    // One iteration per stage.  Its first step refills the ring slot that was read last in the iteration before
+    // (that iteration's barrier lies between); every step first requests the fragments of the step after it --
+    // the last one from the next stage, after waiting for that stage -- then waits for its own fragments only
+    // (requested a step ago: the TM + TN requests just made stay outstanding) and multiplies.  The scheduling
+    // fences keep the steps apart.  Three copies of the body (stages that still refill the ring, stages that
+    // only drain it, the last stage) keep every wait count a constant.
+    int slot_bytes = 0;
+    auto next_slot = [&]() { slot_bytes = slot_bytes + STAGE_BYTES == RING_BYTES ? 0 : slot_bytes + STAGE_BYTES; };
+    auto step = [&](int ks, bool refill, bool more, auto vm_tag) {
+        constexpr int VM = decltype(vm_tag)::value;
+        if (ks + 1 < KS) {
+            fetch(slot_bytes, ks + 1, fa[(ks + 1) & 1], fw[(ks + 1) & 1]);
+            wait_lds_reads<TM + TN>();
+        } else if (more) {
+            wait_vm_and_barrier<VM>();                            // own fragments too (lgkmcnt 0): the slot may be refilled after this
+            next_slot();
+            fetch(slot_bytes, 0, fa[0], fw[0]);
+        } else {
+            wait_lds_reads<0>();
+        }
+        ready(fa[ks & 1], fw[ks & 1]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (refill && ks == 0) issue();
+        multiply(fa[ks & 1], fw[ks & 1]);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    int kt = 0;
+    for (; kt + NSTAGE - 1 < KT; kt++)
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++) step(ks, true, true, std::integral_constant<int, (NSTAGE - 2) * NLD>());
+    for (; kt + 1 < KT; kt++)
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++) step(ks, false, true, std::integral_constant<int, 0>());
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) step(ks, false, false, std::integral_constant<int, 0>());
+    wait_vm_and_barrier<0>();                                     // the ring is idle from here on
+
+    if constexpr (!Epi::STAGED) {
+#pragma unroll
+        for (int io = 0; io < TN; io++)
+#pragma unroll
+            for (int j = 0; j < TM; j++) {
+                const int row = m0 + wm + j * 32 + r;
+                if (row < M) {
+#pragma unroll
+                    for (int q = 0; q < 4; q++) {
+                        const int n = n0 + wn + io * 32 + 8 * q + 4 * g;
+                        epi.direct(row, n, acc[io][j][4 * q], acc[io][j][4 * q + 1], acc[io][j][4 * q + 2], acc[io][j][4 * q + 3]);
+                    }
+                }
+            }
+    } else {
+        // the output tile goes through LDS 64 token rows at a time (32 of each wave row), then out as full rows
+        constexpr int OB = Epi::OUT_BYTES;
+        constexpr int STRIDE = BN * OB + 16;
+        constexpr int CHUNKS = BN * OB / 16;
+        static_assert(2 * 64 * STRIDE <= RING_BYTES, "two staging slabs must fit in the ring");
+        static_assert((64 * CHUNKS) % NT == 0, "output chunks must split evenly over the threads");
+#pragma unroll
+        for (int j = 0; j < TM; j++) {
+            char *slab = lds + (j & 1) * 64 * STRIDE;             // alternate slabs: one barrier per pass
+            const int lrow = (wave >> 1) * 32 + r;
+#pragma unroll
+            for (int io = 0; io < TN; io++) {
+                typename Epi::pack_t pk[4];
+                const int nl = wn + io * 32;
+                epi.tile(acc[io][j], tab, BN, nl, n0 + nl, g, pk);
+#pragma unroll
+                for (int q = 0; q < 4; q++)
+                    *reinterpret_cast<typename Epi::pack_t *>(slab + lrow * STRIDE + (nl + 8 * q + 4 * g) * OB) = pk[q];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int p = 0; p < 64 * CHUNKS / NT; p++) {
+                const int idx = p * NT + tid;
+                const int srow = idx / CHUNKS, ochunk = idx % CHUNKS;
+                const int grow = m0 + (srow >> 5) * 32 * TM + j * 32 + (srow & 31);
+                if (grow < M) {
+                    const v4i v = *reinterpret_cast<const v4i *>(slab + srow * STRIDE + ochunk * 16);
+                    *reinterpret_cast<v4i *>(out + ((size_t)grow * N + n0) * OB + ochunk * 16) = v;
+                }
+            }
+        }
+    }
+}
+
+template <class T, class Epi, int TM, int TN, int BKB, int NSTAGE, int WPE = 1>
+hipError_t launch_big(const void *A, const void *W, void *out, const Epi &epi, Rows rows, int N, int K, hipStream_t st,
+                      const Timing *tm)
+{
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr size_t LDS_FIXED = (size_t)NSTAGE * (BM + BN) * BKB + (size_t)Epi::NTAB * BN * sizeof(float);
+    const size_t LDS = LDS_FIXED + extra_lds_of(epi, 0);
+    if (N % BN || (K * T::ELEM) % BKB || LDS > 160 * 1024) return hipErrorInvalidValue;
+    auto kern = gemm_nt_big_kernel<T, Epi, TM, TN, BKB, NSTAGE, WPE>;
+    static std::atomic<bool> attr_set{false};
+    if (!attr_set.load(std::memory_order_acquire)) {
+        const size_t cap = std::min<size_t>(LDS_FIXED + GELU_TABLE_MAX_BINS * 8, 160 * 1024);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)cap);
+        if (e != hipSuccess) return e;
+        attr_set.store(true, std::memory_order_release);
+    }
+    const int tiles_n = N / BN, tiles_m = (rows.host_rows + BM - 1) / BM;
+    launch_kernel(kern, dim3(tiles_n * tiles_m), dim3(256), LDS, st, tm,
+                  (const char *)A, (const char *)W, (char *)out, epi, rows.host_rows, rows.dev_rows, N, K * T::ELEM, tiles_n);
     return hipGetLastError();
 }
 
@@ -404,29 +648,54 @@ hipError_t launch_cfg(const void *A, const void *W, void *out, const Epi &epi, R
 //      3072 bytes or more (FFN2) get a 3-deep ring (72 KB, still two blocks per CU) when there is at most one
 //      block per CU: -4 % on the BERT-base forward (with more blocks than CUs it measured slower); a 4-deep ring is faster for the kernel alone but crowds out the other group's kernels
 constexpr int LONG_K_BYTES = 3072;
+constexpr int BIG_TILE_MIN_ROWS = 16384;                         // from here on the 256 x 256 tiles fill the chip several times over
+
+constexpr int big_tile_width(int cfg) { return cfg == 6 ? 192 : 256; }
 
 template <class T, class Epi>
 hipError_t launch(const void *A, const void *W, void *out, const Epi &epi, Rows rows, int N, int K, hipStream_t st,
                   const Timing *tm)
 {
     int cfg = gemm_config_override.load(std::memory_order_relaxed);
-    if ((K * T::ELEM) % 128) cfg = 0;
-    else if (cfg < 0) {
-        const long tiles = (long)(N / 128) * ((rows.host_rows + 127) / 128);
-        cfg = tiles <= 640 ? 2 : 1;
+    const bool forced = cfg >= 0;
+    const int kbytes = K * T::ELEM;
+    if (cfg >= 3 && (N % big_tile_width(cfg) || kbytes % 128)) cfg = -1;   // whole columns of tiles, whole 128-byte stages
+    if (cfg >= 0 && cfg < 3 && kbytes % 128) cfg = 0;
+    if (cfg < 0) {
+        if (kbytes % 128) cfg = 0;
+        else {
+            const long tiles = (long)(N / 128) * ((rows.host_rows + 127) / 128);
+            cfg = tiles <= 640 ? 2 : 1;
+            // wide INT8 GEMMs (QKV, FFN1) from about a thousand tokens: 128 x 192 tiles, 64 x 96 per wave, two blocks
+            // per CU.  Measured in the BERT-base forward at 2 x 2048 tokens: -5 % with FFN1 (whose table-lookup epilogue
+            // in the 64 x 128 configuration costs more than it saves: its table in LDS takes the third resident block
+            // away), another -1.4 % with QKV
+            if (std::is_same<T, I8>::value && N % 192 == 0 && N >= 2304 && rows.host_rows >= 1024) cfg = 6;
+            // many tokens (INT8): wave tiles of 64 x 128 halve the LDS operand traffic per MFMA, two such blocks
+            // per CU overlap one's epilogue with the other's main loop; long operand rows amortise the epilogue of a
+            // 256 x 256 tile by themselves
+            if (std::is_same<T, I8>::value && N % 256 == 0 && rows.host_rows >= BIG_TILE_MIN_ROWS)
+                cfg = kbytes >= LONG_K_BYTES ? 7 : 4;
+        }
     }
     switch (cfg) {
+    case 3: return launch_big<T, Epi, 4, 4, 128, 2>(A, W, out, epi, rows, N, K, st, tm);      // 256 x 256, two 128-byte stages
+    case 4: return launch_big<T, Epi, 2, 4, 64, 3, 2>(A, W, out, epi, rows, N, K, st, tm);    // 128 tokens x 256 channels, two blocks per CU
+    case 5: return launch_big<T, Epi, 4, 2, 64, 3, 2>(A, W, out, epi, rows, N, K, st, tm);    // 256 tokens x 128 channels, two blocks per CU
+    case 6: return launch_big<T, Epi, 2, 3, 64, 3, 2>(A, W, out, epi, rows, N, K, st, tm);    // 128 x 192, two blocks per CU
+    case 7: return launch_big<T, Epi, 4, 4, 64, 4>(A, W, out, epi, rows, N, K, st, tm);       // 256 x 256, four 64-byte stages
     case 1:
         // the GELU epilogue is as much vector work as the main loop is matrix work: 64-byte stages leave room
         // for three resident blocks per CU, whose epilogues and main loops overlap (-3 % on the large forwards)
-        if constexpr (std::is_same<Epi, EpiGeluQuant>::value) return launch_cfg<T, Epi, 2, 2, 64, 3, 3>(A, W, out, epi, rows, N, K, st, tm);
+        if constexpr (std::is_same<Epi, EpiGeluQuant>::value || std::is_same<Epi, EpiGeluTable>::value)
+            return launch_cfg<T, Epi, 2, 2, 64, 3, 3>(A, W, out, epi, rows, N, K, st, tm);
         else return launch_cfg<T, Epi, 2, 2, 128, 2, 2>(A, W, out, epi, rows, N, K, st, tm);
     case 2: {
         const long row_tiles = (rows.host_rows + 63) / 64;
         const bool long_k = K * T::ELEM >= LONG_K_BYTES;
         // 64 x 96 tiles (six waves of 32 x 32) when they put the problem on more CUs without exceeding one block
         // per CU: the rate at which one CU pulls operands is what bounds these small problems
-        if (gemm_config_override.load(std::memory_order_relaxed) < 0 && N % 96 == 0 && (N / 96) * row_tiles <= 256) {
+        if (!forced && N % 96 == 0 && (N / 96) * row_tiles <= 256) {
             if (long_k) return launch_cfg<T, Epi, 1, 1, 128, 3, 2, 2, 3>(A, W, out, epi, rows, N, K, st, tm);
             return launch_cfg<T, Epi, 1, 1, 128, 2, 2, 2, 3>(A, W, out, epi, rows, N, K, st, tm);
         }
@@ -442,12 +711,16 @@ hipError_t launch(const void *A, const void *W, void *out, const Epi &epi, Rows 
 std::atomic<int> gemm_config_override{-1};                    // tuning aid: force one tile configuration (see launch())
 
 hipError_t launch_gemm_i8(GemmEpilogue epi, const int8_t *A, const int8_t *W, void *out, const float *m, const float *b,
-                          float inv_s_out, Rows rows, int N, int K, hipStream_t st, const Timing *tm)
+                          float inv_s_out, const GeluTable *gt, Rows rows, int N, int K, hipStream_t st, const Timing *tm)
 {
     switch (epi) {
     case EPI_RAW_I32: return launch<I8>(A, W, out, EpiRawI32{(int32_t *)out, N}, rows, N, K, st, tm);
     case EPI_REQUANT: return launch<I8>(A, W, out, EpiRequant{m, b}, rows, N, K, st, tm);
-    case EPI_GELU_QUANT: return launch<I8>(A, W, out, EpiGeluQuant{m, b, inv_s_out}, rows, N, K, st, tm);
+    case EPI_GELU_QUANT:
+        if (gt && gt->entries)
+            return launch<I8>(A, W, out, EpiGeluTable{m, b, gt->entries, gt->spec.rate, gt->spec.offset, gt->spec.t_max, gt->spec.bins},
+                              rows, N, K, st, tm);
+        return launch<I8>(A, W, out, EpiGeluQuant{m, b, inv_s_out}, rows, N, K, st, tm);
     }
     return hipErrorInvalidValue;
 }

@@ -108,7 +108,62 @@ def test_every_gemm_tile_configuration_gives_the_same_results(P, config):
     want = oracle.gemm_f16(Ah, Wh, bias, False).astype(np.float64)
     assert (np.abs(f16 - want) <= np.maximum(np.abs(want), 2.0 ** -14) * 2.0 ** -10 + 1e-6).all()
     with pytest.raises(P.SampError):
-        P.set_gemm_config(3)
+        P.set_gemm_config(99)
+
+
+@pytest.mark.parametrize("config", [3, 4, 5, 6, 7])
+@pytest.mark.parametrize("M,N,K", [(700, 512, 768), (257, 768, 256), (1100, 768, 3072), (130, 768, 128)])
+def test_large_tile_configurations_give_the_same_results(P, config, M, N, K):
+    """The large block tiles (128..256 tokens x 128..256 channels, 64 x 64 .. 128 x 128 per wave, rings of 64- or
+    128-byte stages, operand fragments double-buffered in registers), forced on problems with a ragged last row tile
+    and with fewer K stages than the ring is deep: all INT8 epilogues bit-exact, incl. the table-lookup GELU; FP16
+    within one ulp.  (A configuration whose tile width does not divide N falls back to the default choice.)"""
+    rng = np.random.default_rng(M + N + K + config)
+    A = rng.integers(-127, 128, (M, K), dtype=np.int8)
+    W = rng.integers(-127, 128, (N, K), dtype=np.int8)
+    s_w, bias = _tables(rng, N)
+    m, b = oracle.fold_requant(0.037, s_w, bias, 0.021 * np.sqrt(K / 768))
+    md = oracle.fold_dequant(0.05 * np.sqrt(768 / K), s_w)
+    s_out = 0.0147
+    spec, entries = P.gelu_table_build(s_out)
+    Ah = (rng.standard_normal((M, K // 2)) * 0.5).astype(np.float16)
+    Wh = (rng.standard_normal((N, K // 2)) * 0.05).astype(np.float16)
+    acc = oracle.gemm_i8_i32(A, W)
+    P.set_gemm_config(config)
+    try:
+        raw = host(P.gemm_i8_i32(dev(A), dev(W)))
+        req = host(P.gemm_i8_requant(dev(A), dev(W), dev(m), dev(b)))
+        gel = host(P.gemm_i8_gelu_quant(dev(A), dev(W), dev(md), dev(bias), s_out))
+        gel_t = host(P.gemm_i8_gelu_quant(dev(A), dev(W), dev(md), dev(bias), s_out, (spec, dev(entries))))
+        f16 = host(P.gemm_f16(dev(Ah), dev(Wh), dev(bias), True)).astype(np.float64)
+    finally:
+        P.set_gemm_config(-1)
+    assert np.array_equal(raw, acc)
+    assert np.array_equal(req, oracle.epilogue_requant(acc, m, b))
+    want = oracle.epilogue_gelu_quant(acc, md, bias, s_out)
+    assert np.array_equal(gel, want)
+    assert np.array_equal(gel_t, want)
+    assert want.max() == 127 and (want < 0).any()
+    wantf = oracle.gemm_f16(Ah, Wh, bias, True).astype(np.float64)
+    assert (np.abs(f16 - wantf) <= np.maximum(np.abs(wantf), 2.0 ** -14) * 2.0 ** -10 + 1e-6).all()
+
+
+@pytest.mark.parametrize("config", [-1, 0, 1, 2])
+def test_table_lookup_gelu_epilogue_in_the_small_tile_configurations(P, config):
+    rng = np.random.default_rng(5 + config)
+    M, N, K = 333, 384, 768
+    A = rng.integers(-127, 128, (M, K), dtype=np.int8)
+    W = rng.integers(-127, 128, (N, K), dtype=np.int8)
+    s_w, bias = _tables(rng, N)
+    md = oracle.fold_dequant(0.05, s_w)
+    for s_out in (0.0147, 0.031):
+        spec, entries = P.gelu_table_build(s_out)
+        P.set_gemm_config(config)
+        try:
+            got = host(P.gemm_i8_gelu_quant(dev(A), dev(W), dev(md), dev(bias), s_out, (spec, dev(entries))))
+        finally:
+            P.set_gemm_config(-1)
+        assert np.array_equal(got, oracle.epilogue_gelu_quant(oracle.gemm_i8_i32(A, W), md, bias, s_out))
 
 
 @pytest.mark.parametrize("N", [256, 384])
