@@ -3,23 +3,33 @@
 
 Workload: BERT-base 12-layer encoder, batch 32 x 128 tokens, all sequences full length (synthetic
 N(0,0.02) weights, N(0,1) inputs, min-max calibration on a seeded 8x128 batch run on the GPU).
-A step is one forward of the whole encoder.  The headline `value` is sequences/s of the full-INT8
-stack; the other precision modes are timed the same way and reported under "modes".
+A step is one forward of the whole encoder, inputs resident in HBM.  The headline `value` is
+sequences/s of the full-INT8 stack; the other precision modes are timed the same way and reported
+under "modes".  Every figure is the median of --repeats timed runs of --steps forwards each.
 
 Extra objects on the JSON line:
-  roofline     - the FFN1 INT8 GEMM (+bias+GELU+quantise) kernel: algorithmic ops per launch
-                 (2 * tokens * ffn * hidden) over its mean launch duration, measured with HIP events
-                 attached to the dispatches over a repeat of the timed steps, against the int8 MFMA dense peak.
-  cpu_baseline - the CPU oracle (as it stands, OpenMP over sequences) on the same batch.
-  kernels      - every kernel class of the headline mode timed the same way (one class per pass, launches
-                 isolated): mean launch duration, and its algorithmic ops or bytes over that duration against
-                 the MFMA or HBM peak.
+  roofline       - the FFN1 INT8 GEMM (+bias+GELU+quantise) kernel: algorithmic ops per launch
+                   (2 * tokens * ffn * hidden) over its mean launch duration, measured with HIP events
+                   attached to the dispatches over a repeat of the timed steps, against the int8 MFMA
+                   dense peak; `traffic` is the measured HBM bytes per launch, read from the rocprofv3
+                   summary under profiles/ that covers this workload, mode and launch size (null if none).
+  kernels        - every kernel class of the headline mode timed the same way (one class per pass,
+                   launches isolated): mean launch duration, and its algorithmic ops or bytes over
+                   that duration against the MFMA or HBM peak.  kernels_fp16: the same for the FP16 mode
+                   against the fp16 MFMA peak.
+  modes          - per precision mode: median ms per forward with graph replay (the default) and with
+                   plain launches, sequences/s.
+  peaks_measured - what this GPU delivers in the library's probes: int8 and fp16 matrix-instruction
+                   issue rate with constant and with pseudo-random operands, device copy rate.
+  cpu_baseline   - the CPU oracle (as it stands, OpenMP over sequences) on the same batch.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
+import statistics
 import sys
 import time
 
@@ -27,18 +37,30 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# HBM bytes per launch of the dominant kernel, from profiles/c2_full_int8_hbm_traffic.txt (rocprofv3 FETCH_SIZE x 2.0 +
-# WRITE_SIZE x 1.0, factors from a 256 MiB copy): workload C2, full-INT8, FFN1 kernel, 2048 tokens per launch.
-MEASURED_TRAFFIC_BYTES = {("C2", "FULL_INT8", 2048): 27.15e6}
-
 INT8_PEAK_TOPS = 5000.0        # MI355X dense int8 MFMA, published: 5.0 POP/s
 FP16_PEAK_TFLOPS = 2500.0      # dense fp16
 HBM_PEAK_GBS = 8000.0
 
 
+def measured_traffic(workload: str, mode: str, kernel: str, tokens_per_launch: int):
+    """HBM bytes per launch from the rocprofv3 counter summaries under profiles/ (lines of the form
+    `traffic_bytes_per_launch <workload> <mode> <kernel> <tokens per launch> <bytes>`), or None."""
+    pdir = os.path.join(ROOT, "profiles")
+    if not os.path.isdir(pdir):
+        return None
+    for name in sorted(os.listdir(pdir)):
+        if not name.endswith((".txt", ".md")):
+            continue
+        for line in open(os.path.join(pdir, name), errors="replace"):
+            m = re.match(r"\s*#?\s*traffic_bytes_per_launch\s+(\S+)\s+(\S+)\s+(\S+)\s+(\d+)\s+([0-9.eE+]+)", line)
+            if m and (m.group(1), m.group(2), m.group(3), int(m.group(4))) == (workload, mode, kernel, tokens_per_launch):
+                return float(m.group(5))
+    return None
+
+
 def algorithmic_work(w, modes, lens):
-    """Per kernel class, summed over one forward: (ops, bytes, bound, dtype-is-int8) that the method itself
-    needs - operands read once, results written once, weights once per layer."""
+    """Per kernel class, summed over one forward: (ops, bytes) that the method itself needs - operands read once,
+    results written once, weights once per layer."""
     T = int(lens.sum())
     H, F = w.hidden, w.ffn
     att = float((lens.astype("float64") ** 2).sum()) * 4 * H
@@ -60,18 +82,76 @@ def algorithmic_work(w, modes, lens):
     return work
 
 
+def timed(enc, hid, mask, out, steps, repeats, torch):
+    """Median over `repeats` runs of the wall-clock time of `steps` forwards, in ms per forward."""
+    runs = []
+    for _ in range(repeats):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            enc.forward(hid, mask, out)
+        torch.cuda.synchronize()
+        runs.append((time.perf_counter() - t0) / steps * 1e3)
+    return statistics.median(runs), runs
+
+
+def kernel_table(P, enc, hid, mask, out, w0, modes, lens, steps, torch):
+    """Every kernel class, one pass each, HIP events on the dispatches (groups run one after another meanwhile)."""
+    work = algorithmic_work(w0, modes, lens)
+    all_i8 = all((m & 3) == P.FULL_INT8 for m in modes)
+    all_f16 = all(m == P.FP16 for m in modes)
+    kernels = {}
+    for kname, which in (("entry", P.PROF_ENTRY), ("qkv", P.PROF_QKV), ("attention", P.PROF_ATTN),
+                         ("attn_out", P.PROF_ATTN_OUT), ("ln1", P.PROF_LN1), ("ffn1", P.PROF_FFN1),
+                         ("ffn2", P.PROF_FFN2), ("ln2", P.PROF_LN2)):
+        enc.profile(which)
+        n_pass = min(steps, 20)
+        for _ in range(n_pass):
+            enc.forward(hid, mask, out)
+        torch.cuda.synchronize()
+        kms, launches = enc.profile_read()
+        enc.profile(P.PROF_OFF)
+        if launches == 0:
+            continue
+        tot_s = kms * 1e-3 * launches / n_pass          # summed duration of the class in one forward
+        ops_f, bytes_f = work[kname]
+        ent = {"mean_launch_us": round(kms * 1e3, 2), "launches_per_step": launches / n_pass,
+               "GB/s": round(bytes_f / tot_s / 1e9, 1), "frac_hbm": round(bytes_f / tot_s / 1e9 / HBM_PEAK_GBS, 4)}
+        if kname in ("qkv", "attn_out", "ffn1", "ffn2") and (all_i8 or all_f16):
+            peak = INT8_PEAK_TOPS if all_i8 else FP16_PEAK_TFLOPS
+            ent["TOP/s" if all_i8 else "TFLOP/s"] = round(ops_f / tot_s / 1e12, 1)
+            ent["frac_mfma"] = round(ops_f / tot_s / 1e12 / peak, 4)
+        kernels[kname] = ent
+    return kernels
+
+
+def measure_peaks(P):
+    pk = {}
+    for name, f16 in (("int8", False), ("fp16", True)):
+        unit = 1e12
+        pk[f"mfma_{name}_constant_operands_T{'FL' if f16 else ''}OP/s"] = round(P.probe_mfma_rate(f16, False) / unit, 1)
+        pk[f"mfma_{name}_random_operands_T{'FL' if f16 else ''}OP/s"] = round(P.probe_mfma_rate(f16, True) / unit, 1)
+    pk["device_copy_GB/s"] = round(P.probe_copy_rate(1 << 30, 10) / 1e9, 1)
+    pk["note"] = ("issue rate of v_mfma_i32_32x32x32_i8 / v_mfma_f32_32x32x16_f16 from registers on all SIMDs; copy = bytes read + "
+                  "written of a 1 GiB device copy")
+    return pk
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--repeats", type=int, default=5, help="timed runs of --steps forwards each; the median is reported")
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--groups", type=int, default=0, help="batch groups run concurrently (0 = library default)")
-    ap.add_argument("--no-graph", action="store_true", help="plain launches instead of HIP graph replay")
+    ap.add_argument("--no-graph", action="store_true", help="headline from plain launches instead of HIP graph replay")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 256 MiB device copy (reference point for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--only-mode", default=None, help="time a single precision mode (FULL_INT8, FP16, ...)")
+    ap.add_argument("--peaks", action="store_true", help="only run the library's peak probes and print them")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the peak probes")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (sequences are independent, so more GPUs would each take a "
@@ -89,6 +169,11 @@ def main() -> int:
     P.lib()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    print(f"bench.py: host cores {os.cpu_count()}", file=sys.stderr, flush=True)
+
+    if a.peaks:
+        print(json.dumps({"peaks_measured": measure_peaks(P)}), flush=True)
+        return 0
 
     w0 = W.config(a.workload)
     cfg = (w0.layers, w0.hidden, w0.heads, w0.ffn, w0.ln_eps)
@@ -126,24 +211,26 @@ def main() -> int:
 
     results = {}
     roof = None
+    kernels = None
+    kernels_fp16 = None
     for name, mode in mode_list:
         modes = w0.modes if mode is None else (mode,) * w0.layers
         enc = enc16 if (mode == P.FP16) else P.Encoder(*cfg, modes, wts, scales, max_batch=w0.batch, max_seq=w0.seq)
         out = torch.empty_like(hid)
         enc.set_groups(a.groups)
-        if a.no_graph:
-            enc.set_graph(False)
-        for _ in range(a.warmup):
-            enc.forward(hid, mask, out)
+        per = {}
+        for label, graph in (("graph", True), ("eager", False)):
+            enc.set_graph(graph)
+            for _ in range(a.warmup):
+                enc.forward(hid, mask, out)
+            med, runs = timed(enc, hid, mask, out, a.steps, a.repeats, torch)
+            per[label] = med
+            per[label + "_runs"] = [round(r, 4) for r in runs]
+        enc.set_graph(not a.no_graph)
+        ms = per["eager"] if a.no_graph else per["graph"]
+        results[name] = {"ms_per_step": ms, "seq_per_s": w0.batch / (ms * 1e-3), "ms_per_step_graph": per["graph"],
+                         "ms_per_step_eager": per["eager"], "runs_graph_ms": per["graph_runs"], "runs_eager_ms": per["eager_runs"]}
         headline = name == mode_list[0][0]                # FULL_INT8 (or the workload's own mask), unless --only-mode
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(a.steps):
-            enc.forward(hid, mask, out)
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-        ms = dt / a.steps * 1e3
-        results[name] = {"ms_per_step": ms, "seq_per_s": w0.batch / (ms * 1e-3)}
         if headline:
             # The dominant kernel's launch duration: the same K steps once more with HIP events attached
             # to that kernel's dispatches (an event-carrying dispatch costs a few microseconds of queue
@@ -161,38 +248,17 @@ def main() -> int:
             ops = 2.0 * T * w0.ffn * w0.hidden * w0.layers / per_forward
             achieved = ops / (kms * 1e-3) / 1e12 if kms > 0 else 0.0
             peak = INT8_PEAK_TOPS if ffn_int8 else FP16_PEAK_TFLOPS
-            roof = {"kernel": "gemm_nt_kernel<I8,EpiGeluQuant> (FFN1 GEMM + bias + GELU + quantise)" if ffn_int8
-                    else "gemm_nt_kernel<F16,EpiF16> (FFN1)",
+            tokens_per_launch = int(round(T / (per_forward / w0.layers)))
+            roof = {"kernel": "FFN1 INT8 GEMM + bias + GELU (threshold table) + quantise" if ffn_int8 else "FFN1 FP16 GEMM + bias + GELU",
                     "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TOP/s" if ffn_int8 else "TFLOP/s",
                     "frac": achieved / peak,
-                    "traffic": MEASURED_TRAFFIC_BYTES.get((a.workload, name, int(round(T / (per_forward / w0.layers))))),
-                    "algorithmic_bytes": (T * w0.hidden + T * w0.ffn) / (per_forward / w0.layers) + w0.ffn * w0.hidden, "launches_timed": launches, "launches_per_step": per_forward,
+                    "traffic": measured_traffic(a.workload, name, "ffn1", tokens_per_launch),
+                    "algorithmic_bytes": (T * w0.hidden + T * w0.ffn) / (per_forward / w0.layers) + w0.ffn * w0.hidden,
+                    "launches_timed": launches, "launches_per_step": per_forward, "tokens_per_launch": tokens_per_launch,
                     "mean_launch_us": kms * 1e3, "ops_per_launch": ops}
-            # every kernel class, one pass each
-            work = algorithmic_work(w0, modes, lens)
-            all_i8 = all((m & 3) == P.FULL_INT8 for m in modes)
-            kernels = {}
-            for kname, which in (("entry", P.PROF_ENTRY), ("qkv", P.PROF_QKV), ("attention", P.PROF_ATTN),
-                                 ("attn_out", P.PROF_ATTN_OUT), ("ln1", P.PROF_LN1), ("ffn1", P.PROF_FFN1),
-                                 ("ffn2", P.PROF_FFN2), ("ln2", P.PROF_LN2)):
-                enc.profile(which)
-                n_pass = min(a.steps, 20)
-                for _ in range(n_pass):
-                    enc.forward(hid, mask, out)
-                torch.cuda.synchronize()
-                kms, launches = enc.profile_read()
-                enc.profile(P.PROF_OFF)
-                if launches == 0:
-                    continue
-                tot_s = kms * 1e-3 * launches / n_pass          # summed duration of the class in one forward
-                ops_f, bytes_f = work[kname]
-                ent = {"mean_launch_us": round(kms * 1e3, 2), "launches_per_step": launches / n_pass,
-                       "GB/s": round(bytes_f / tot_s / 1e9, 1), "frac_hbm": round(bytes_f / tot_s / 1e9 / HBM_PEAK_GBS, 4)}
-                if kname in ("qkv", "attn_out", "ffn1", "ffn2") and (all_i8 or all(m == P.FP16 for m in modes)):
-                    peak = INT8_PEAK_TOPS if all_i8 else FP16_PEAK_TFLOPS
-                    ent["TOP/s" if all_i8 else "TFLOP/s"] = round(ops_f / tot_s / 1e12, 1)
-                    ent["frac_mfma"] = round(ops_f / tot_s / 1e12 / peak, 4)
-                kernels[kname] = ent
+            kernels = kernel_table(P, enc, hid, mask, out, w0, modes, lens, a.steps, torch)
+        elif mode == P.FP16:
+            kernels_fp16 = kernel_table(P, enc, hid, mask, out, w0, modes, lens, a.steps, torch)
         if enc is not enc16:
             enc.close()
     enc16.close()
@@ -201,15 +267,20 @@ def main() -> int:
     line = {
         "metric": "sequences/sec BERT-base encoder b32xs128 per precision mode; % int8/fp16 MFMA peak",
         "value": results[head]["seq_per_s"], "unit": "sequences/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
-        "ms_per_step": results[head]["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int8" if head != "FP16" else "f16", "data": "synthetic",
+        "repeats": a.repeats, "ms_per_step": results[head]["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int8" if head != "FP16" else "f16", "data": "synthetic",
         "config": {"workload": f"{a.workload}: {w0.layers}-layer H{w0.hidden} F{w0.ffn} encoder, batch {w0.batch} x "
-                               f"seq {w0.seq}, mode {head}", "tokens": T, "headline_mode": head},
+                               f"seq {w0.seq}, mode {head}", "tokens": T, "headline_mode": head,
+                   "launch": "plain launches" if a.no_graph else "HIP graph replay"},
         "modes": results,
     }
     if roof:
         line["roofline"] = roof
         line["kernels"] = kernels
+    if kernels_fp16:
+        line["kernels_fp16"] = kernels_fp16
+    if not a.no_peaks:
+        line["peaks_measured"] = measure_peaks(P)
 
     if not a.no_cpu_baseline:
         import oracle

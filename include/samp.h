@@ -191,6 +191,16 @@ enum { SAMP_PROF_OFF = 0, SAMP_PROF_QKV = 1, SAMP_PROF_ATTN = 2, SAMP_PROF_ATTN_
 SAMP_API int samp_encoder_profile(samp_encoder_t *enc, int which);
 SAMP_API int samp_encoder_profile_read(samp_encoder_t *enc, double *mean_ms, int64_t *launches);
 
+/* Measured ceilings of the GPU the library runs on, for the benchmark's report next to the published peaks.
+ * samp_probe_mfma_rate: operations per second (2 per multiply-add) of the matrix instruction the INT8 (fp16 = 0)
+ * or FP16 (fp16 != 0) GEMMs are built from, issued from registers by every SIMD with no memory traffic; operands
+ * all equal (random_operands = 0) or pseudo-random (the clock under matrix load depends on how many bits toggle).
+ * dev_sink: 4 bytes of device memory.  samp_probe_copy_rate: bytes per second (read + written) of a plain device
+ * copy of `bytes` bytes, repeated `reps` times.  Both synchronise `stream`.                          */
+SAMP_API int samp_probe_mfma_rate(int32_t fp16, int32_t random_operands, int32_t iters, void *dev_sink, void *stream,
+                                  double *ops_per_s);
+SAMP_API int samp_probe_copy_rate(const void *src, void *dst, size_t bytes, int32_t reps, void *stream, double *bytes_per_s);
+
 /* Thread-local description of the last failure on this thread ("" if none).                       */
 SAMP_API const char *samp_last_error(void);
 

@@ -383,3 +383,20 @@ def pack_rows(hidden: torch.Tensor, mask: torch.Tensor, s_x: float = 0.0):
     row_map = torch.zeros(B * S, dtype=torch.int32, device=hidden.device)
     _check(lib().samp_pack_rows(_dp(hidden), _dp(mask), B, S, H, _f(s_x), _dp(packed), _dp(cu), _dp(row_map), _stream()))
     return packed, cu, row_map
+
+
+def probe_mfma_rate(fp16: bool, random_operands: bool, iters: int = 20000) -> float:
+    """samp_probe_mfma_rate: measured operations per second of the matrix instruction (2 per multiply-add)."""
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    out = C.c_double(0.0)
+    _check(lib().samp_probe_mfma_rate(int(fp16), int(random_operands), int(iters), _dp(sink), _stream(), C.byref(out)))
+    return out.value
+
+
+def probe_copy_rate(nbytes: int = 1 << 30, reps: int = 10) -> float:
+    """samp_probe_copy_rate: measured bytes per second (read + written) of a device copy."""
+    src = torch.ones(nbytes, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    out = C.c_double(0.0)
+    _check(lib().samp_probe_copy_rate(_dp(src), _dp(dst), C.c_size_t(nbytes), int(reps), _stream(), C.byref(out)))
+    return out.value

@@ -847,6 +847,23 @@ int samp_classify(const uint16_t *hidden, int32_t B, int32_t S, int32_t H, const
     return SAMP_OK;
 }
 
+int samp_probe_mfma_rate(int32_t fp16, int32_t random_operands, int32_t iters, void *dev_sink, void *stream, double *ops_per_s)
+{
+    if (!dev_sink || !ops_per_s) return fail(SAMP_ERR_ARG, "NULL pointer");
+    if (iters < 1 || iters > (1 << 20)) return fail(SAMP_ERR_ARG, "iters must be in [1, 2^20]");
+    HIP_TRY(probe_mfma_rate(fp16 != 0, random_operands != 0, iters, (int *)dev_sink, (hipStream_t)stream, ops_per_s));
+    return SAMP_OK;
+}
+
+int samp_probe_copy_rate(const void *src, void *dst, size_t bytes, int32_t reps, void *stream, double *bytes_per_s)
+{
+    if (!src || !dst || !bytes_per_s) return fail(SAMP_ERR_ARG, "NULL pointer");
+    if (bytes < 16 || bytes % 16 || reps < 1) return fail(SAMP_ERR_SHAPE, "bytes must be a positive multiple of 16, reps >= 1");
+    if (!aligned(src, 16) || !aligned(dst, 16)) return fail(SAMP_ERR_ARG, "buffers must be 16-byte aligned");
+    HIP_TRY(probe_copy_rate(src, dst, bytes, reps, (hipStream_t)stream, bytes_per_s));
+    return SAMP_OK;
+}
+
 int samp_code_histogram(const int8_t *codes, size_t n, uint64_t *hist, void *stream)
 {
     if (!codes || !hist) return fail(SAMP_ERR_ARG, "NULL pointer");

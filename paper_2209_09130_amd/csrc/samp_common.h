@@ -227,6 +227,10 @@ hipError_t launch_gelu_quant(const float *y, size_t n, float inv_s, int8_t *code
 hipError_t launch_classify(const __half *hidden, int B, int S, int H, const __half *w_pool, const float *b_pool,
                            const __half *w_cls, const float *b_cls, int C, float *logits, hipStream_t st);
 
+// measured ceilings (probe.hip); both synchronise the stream
+hipError_t probe_mfma_rate(bool f16, bool random_operands, int iters, int *sink, hipStream_t st, double *ops_per_s);
+hipError_t probe_copy_rate(const void *src, void *dst, size_t bytes, int reps, hipStream_t st, double *bytes_per_s);
+
 // host-side recommendation logic (allocator.hip)
 int allocate_decay_aware(const double *A, const double *L, int n);
 int recommend_settings(const double *A, const double *L, int n, double max_latency, double min_accuracy, int *out, int cap);
