@@ -134,6 +134,20 @@ SAMP_API size_t samp_encoder_workspace_bytes(const samp_encoder_t *enc, int32_t 
 SAMP_API int samp_encoder_forward(samp_encoder_t *enc, const void *hidden, const int32_t *mask, int32_t B, int32_t S,
                                   void *out, void *workspace, size_t workspace_bytes, void *stream);
 
+/* samp_encoder_forward for callers that cannot allocate (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the same kernels, run as ONE group with plain launches on `stream`, with the
+ * workspace in an array that is part of the library's device image (SAMP_NOALLOC_SCRATCH_BYTES per GPU, held
+ * until the process ends) instead of a caller-provided buffer.  The call allocates nothing on host or device,
+ * creates no stream, event or graph, and does not synchronise; the array's device address is looked up on the
+ * first call per device.  SAMP_ERR_SPACE if B x S needs more workspace than the array holds (BERT-base: up to
+ * about 1700 tokens; use samp_encoder_forward beyond).  All calls on one GPU share the array: calls that may
+ * overlap in time (different streams, different encoders) race on it -- keep them stream-ordered.  Nothing in
+ * the array needs to start at zero (every buffer in it is written before it is read within a call).
+ * Not available while samp_encoder_profile timing is on.                                            */
+#define SAMP_NOALLOC_SCRATCH_BYTES (32 << 20)
+SAMP_API int samp_encoder_forward_noalloc(samp_encoder_t *enc, const void *hidden, const int32_t *mask, int32_t B, int32_t S,
+                                          void *out, void *stream);
+
 /* Embedding module in front of the encoder (Section 3.1: the token, segment and position embeddings
  * are summed in ONE kernel; BERT's embedding ends with a LayerNorm, which is part of it; Section 3.2:
  * when layer 0's attention block is INT8 the kernel hands int8 to the encoder directly, quantising

@@ -178,6 +178,15 @@ class Encoder:
                                           C.c_size_t(ws.numel()), _stream()))
         return out
 
+    def forward_noalloc(self, hidden: torch.Tensor, mask: Optional[torch.Tensor], out: torch.Tensor) -> torch.Tensor:
+        """samp_encoder_forward_noalloc: the workspace is the library's built-in scratch array; nothing is allocated."""
+        assert hidden.dtype == torch.float16 and hidden.dim() == 3 and out.shape == hidden.shape and out.dtype == torch.float16
+        B, S, H = hidden.shape
+        if mask is not None:
+            assert mask.dtype == torch.int32 and tuple(mask.shape) == (B, S)
+        _check(lib().samp_encoder_forward_noalloc(self._h, _dp(hidden), _dp(mask), B, S, _dp(out), _stream()))
+        return out
+
     def forward_ids(self, emb: "Embedding", token_ids: torch.Tensor, segment_ids: Optional[torch.Tensor] = None,
                     mask: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
         """samp_encoder_forward_ids: the Embedding kernel feeds layer 0 directly."""

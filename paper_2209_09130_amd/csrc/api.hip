@@ -97,6 +97,35 @@ constexpr int MAX_EVENTS = 4096;
 
 }  // namespace
 
+// Workspace of samp_encoder_forward_noalloc: one array per GPU, living in the library's own device image for as
+// long as the process runs.  In host code the array's name is only a handle for hipGetSymbolAddress: the address
+// kernels can use is looked up once per device (noalloc_scratch) and used everywhere after that.
+static __device__ __align__(256) unsigned char scratch[SAMP_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int MAX_DEVICES = 64;
+std::atomic<void *> g_scratch_ptr[MAX_DEVICES];
+
+// Device address of `scratch` on the current device (looked up on the first call per device; concurrent first
+// calls look it up twice and store the same value).
+int noalloc_scratch(void **out)
+{
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(SAMP_ERR_ARG, "device index %d is outside [0, %d)", dev, MAX_DEVICES);
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || !aligned(p, ALIGN)) return fail(SAMP_ERR_HIP, "the scratch array has no usable device address");
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return SAMP_OK;
+}
+
+}  // namespace
+
 constexpr int MAX_GROUPS = 4;
 
 struct samp_encoder {
@@ -498,6 +527,26 @@ int samp_encoder_forward(samp_encoder_t *enc, const void *hidden, const int32_t 
     if (out == hidden) return fail(SAMP_ERR_ARG, "out must not alias hidden");
     if (!aligned(out, 16)) return fail(SAMP_ERR_ARG, "out must be 16-byte aligned");
     return forward_common(enc, hidden, nullptr, mask, B, S, out, workspace, static_cast<hipStream_t>(stream));
+}
+
+int samp_encoder_forward_noalloc(samp_encoder_t *enc, const void *hidden, const int32_t *mask, int32_t B, int32_t S, void *out,
+                                 void *stream)
+{
+    if (!enc || !hidden || !out) return fail(SAMP_ERR_ARG, "encoder, input or output is NULL");
+    if (B < 1 || S < 1) return fail(SAMP_ERR_SHAPE, "B and S must be >= 1");
+    if (B > enc->cfg.max_batch || S > enc->cfg.max_seq)
+        return fail(SAMP_ERR_SHAPE, "B=%d S=%d exceed max_batch=%d max_seq=%d", B, S, enc->cfg.max_batch, enc->cfg.max_seq);
+    if (!aligned(hidden, 16) || !aligned(out, 16)) return fail(SAMP_ERR_ARG, "hidden and out must be 16-byte aligned");
+    if (out == hidden) return fail(SAMP_ERR_ARG, "out must not alias hidden");
+    if (enc->prof_which != SAMP_PROF_OFF) return fail(SAMP_ERR_ARG, "kernel timing is on: it creates events, which this entry point must not");
+    const size_t need = carve(enc->cfg, B, S, nullptr).bytes;
+    if (need > (size_t)SAMP_NOALLOC_SCRATCH_BYTES)
+        return fail(SAMP_ERR_SPACE, "B=%d S=%d need %zu bytes of workspace, the built-in scratch array holds %d: use samp_encoder_forward",
+                    B, S, need, SAMP_NOALLOC_SCRATCH_BYTES);
+    void *ws = nullptr;
+    if (int rc = noalloc_scratch(&ws)) return rc;
+    // one group, plain launches on the caller's stream: no side streams, events or graphs are created on this path
+    return run(enc, hidden, nullptr, mask, B, S, out, ws, static_cast<hipStream_t>(stream), false);
 }
 
 static int check_embedding(const samp_embedding_t *e, int H, int S)
