@@ -152,6 +152,9 @@ def main() -> int:
     ap.add_argument("--only-mode", default=None, help="time a single precision mode (FULL_INT8, FP16, ...)")
     ap.add_argument("--peaks", action="store_true", help="only run the library's peak probes and print them")
     ap.add_argument("--no-peaks", action="store_true", help="skip the peak probes")
+    ap.add_argument("--kernel-passes-only", action="store_true",
+                    help="skip the throughput loops: only the per-kernel passes with isolated launches run (for profilers, "
+                         "whose per-kernel averages then cover exactly the launches the kernel tables are made from)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (sequences are independent, so more GPUs would each take a "
@@ -220,6 +223,9 @@ def main() -> int:
         enc.set_groups(a.groups)
         per = {}
         for label, graph in (("graph", True), ("eager", False)):
+            if a.kernel_passes_only:
+                per[label], per[label + "_runs"] = float("nan"), []
+                continue
             enc.set_graph(graph)
             for _ in range(a.warmup):
                 enc.forward(hid, mask, out)

@@ -639,6 +639,132 @@ hipError_t launch_big(const void *A, const void *W, void *out, const Epi &epi, R
     return hipGetLastError();
 }
 
+
+// ---- long operand rows on few tiles ------------------------------------------------------------------
+// FFN2 at small batch: 24 (FP16: 48) stages of 128 bytes, 64 x 96 tiles that no more than fill the chip once.  Such
+// a block is a chain of dependent stages whose pace is set by bytes in flight over load latency, and LDS for a
+// deeper ring is what the other batch group's kernels on the same CU need.  Here the stages in flight wait in
+// REGISTERS instead (a 32 x 32 tile per wave leaves most of them idle): every wave keeps DEPTH stages of its share
+// of the loads outstanding, writes the oldest one to one of two LDS buffers when it lands, and requests the stage
+// DEPTH ahead into the registers just freed.  One barrier per stage: a buffer is rewritten two stages after it
+// was read, and the barrier of the stage between lies between.  Deeper is faster for the kernel alone and slower
+// for the forward (the loads in flight compete with the other group's kernels), so the launcher takes DEPTH = 2:
+// what is won is the LDS (40 KB against 61 KB for the three-deep ring).
+template <class T, class Epi, int WGN, int DEPTH>
+__global__ __launch_bounds__(128 * WGN)
+void gemm_nt_longk_kernel(const char *__restrict__ A, const char *__restrict__ W, char *__restrict__ out, Epi epi, int host_rows,
+                          const int *__restrict__ dev_rows, int N, int Kbytes, int tiles_n)
+{
+    constexpr int BKB = 128, BM = 64, BN = 32 * WGN, NWAVES = 2 * WGN, NT = 64 * NWAVES;
+    constexpr int NPIECE = (BM + BN) / 8, NLD = (NPIECE + NWAVES - 1) / NWAVES;      // 1 KiB pieces of 8 rows; loads per wave and stage
+    constexpr int STAGE_BYTES = (BM + BN) * BKB, A_BYTES = BM * BKB;
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    float *tab = reinterpret_cast<float *>(lds + 2 * STAGE_BYTES);
+
+    const int M = dev_rows ? *dev_rows : host_rows;
+    const int tiles = ((M + BM - 1) / BM) * tiles_n;
+    if ((int)blockIdx.x >= tiles) return;
+    const int tile = xcd_contiguous(blockIdx.x, tiles);
+    const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave / WGN) * 32, wn = (wave % WGN) * 32;
+    const int r = lane & 31, g = lane >> 5;
+
+    // this wave's pieces: where they come from and where they go (a surplus slot repeats the last piece)
+    const char *src[NLD];
+    int dst[NLD];
+#pragma unroll
+    for (int j = 0; j < NLD; j++) {
+        const int piece = min(wave + NWAVES * j, NPIECE - 1);
+        const int srow = 8 * piece + (lane >> 3), chunk = lane & 7;
+        if (srow < BM) {
+            int am = m0 + srow; if (am > M - 1) am = M - 1;
+            src[j] = A + (size_t)am * Kbytes + chunk * 16;
+            dst[j] = srow * BKB + ((chunk ^ swz<BKB>(srow)) << 4);
+        } else {
+            const int row = srow - BM;
+            src[j] = W + (size_t)(n0 + row) * Kbytes + chunk * 16;
+            dst[j] = A_BYTES + row * BKB + ((chunk ^ swz<BKB>(row)) << 4);
+        }
+    }
+    const int KT = Kbytes / BKB;                                  // a multiple of DEPTH (the launcher checks)
+    // (scheduling fences keep the loads in stage order: the wait for a stage's registers counts the loads behind it)
+    v4i held[DEPTH][NLD];
+    epi.load_tables(tab, n0, BN, tid, NT);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int d = 0; d < DEPTH; d++) {
+#pragma unroll
+        for (int j = 0; j < NLD; j++) held[d][j] = *reinterpret_cast<const v4i *>(src[j] + (size_t)d * BKB);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+
+    typename T::acc_t acc;
+#pragma unroll
+    for (int e = 0; e < 16; e++) acc[e] = 0;
+    const int offa = (wm + r) * BKB, offw = A_BYTES + (wn + r) * BKB;
+    const int sa = swz<BKB>(wm + r), sw = swz<BKB>(wn + r);
+
+    auto stage = [&](int kt, int d, bool refill) {
+        char *buf = lds + (kt & 1) * STAGE_BYTES;
+#pragma unroll
+        for (int j = 0; j < NLD; j++) *reinterpret_cast<v4i *>(buf + dst[j]) = held[d][j];    // waits for these loads only
+        __builtin_amdgcn_sched_barrier(0);
+        if (refill) {
+#pragma unroll
+            for (int j = 0; j < NLD; j++) held[d][j] = *reinterpret_cast<const v4i *>(src[j] + (size_t)(kt + DEPTH) * BKB);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++) {
+            const v4i fa = *reinterpret_cast<const v4i *>(buf + offa + (((2 * ks + g) ^ sa) << 4));
+            const v4i fw = *reinterpret_cast<const v4i *>(buf + offw + (((2 * ks + g) ^ sw) << 4));
+            acc = T::mma(fw, fa, acc);
+        }
+    };
+    int kt = 0;
+    for (; kt + DEPTH < KT; kt += DEPTH)
+#pragma unroll
+        for (int d = 0; d < DEPTH; d++) stage(kt + d, d, true);
+#pragma unroll
+    for (int d = 0; d < DEPTH; d++) stage(kt + d, d, false);
+    __syncthreads();                                              // both buffers are idle from here on
+
+    constexpr int OB = Epi::OUT_BYTES;
+    constexpr int STRIDE = BN * OB + 16;
+    static_assert(BM * STRIDE <= 2 * STAGE_BYTES, "staging tile does not fit");
+    {
+        typename Epi::pack_t pk[4];
+        epi.tile(acc, tab, BN, wn, n0 + wn, g, pk);
+#pragma unroll
+        for (int q = 0; q < 4; q++)
+            *reinterpret_cast<typename Epi::pack_t *>(lds + (wm + r) * STRIDE + (wn + 8 * q + 4 * g) * OB) = pk[q];
+    }
+    __syncthreads();
+    constexpr int CHUNKS = BN * OB / 16;
+    for (int idx = tid; idx < BM * CHUNKS; idx += NT) {
+        const int lrow = idx / CHUNKS, ochunk = idx % CHUNKS;
+        if (m0 + lrow < M)
+            *reinterpret_cast<v4i *>(out + ((size_t)(m0 + lrow) * N + n0) * OB + ochunk * 16) =
+                *reinterpret_cast<const v4i *>(lds + lrow * STRIDE + ochunk * 16);
+    }
+}
+
+template <class T, class Epi, int WGN, int DEPTH>
+hipError_t launch_longk(const void *A, const void *W, void *out, const Epi &epi, Rows rows, int N, int K, hipStream_t st,
+                        const Timing *tm)
+{
+    constexpr int BN = 32 * WGN;
+    const int kbytes = K * T::ELEM;
+    if (N % BN || kbytes % (128 * DEPTH)) return hipErrorInvalidValue;
+    const size_t LDS = 2 * (size_t)(64 + BN) * 128 + (size_t)Epi::NTAB * BN * sizeof(float);
+    const int tiles_n = N / BN, tiles_m = (rows.host_rows + 63) / 64;
+    launch_kernel(gemm_nt_longk_kernel<T, Epi, WGN, DEPTH>, dim3(tiles_n * tiles_m), dim3(128 * WGN), LDS, st, tm,
+                  (const char *)A, (const char *)W, (char *)out, epi, rows.host_rows, rows.dev_rows, N, kbytes, tiles_n);
+    return hipGetLastError();
+}
+
 // Tile configuration per problem shape.  What bounds the main loop on this chip is the rate at which
 // a CU pulls operand stages out of L2 (about 37 bytes per clock per CU, whichever way they are loaded),
 // so small problems want many small tiles (more CUs pulling), large ones the larger tile (less traffic):
@@ -666,11 +792,11 @@ hipError_t launch(const void *A, const void *W, void *out, const Epi &epi, Rows 
         else {
             const long tiles = (long)(N / 128) * ((rows.host_rows + 127) / 128);
             cfg = tiles <= 640 ? 2 : 1;
-            // wide INT8 GEMMs (QKV, FFN1) from about a thousand tokens: 128 x 192 tiles, 64 x 96 per wave, two blocks
+            // wide GEMMs (QKV, FFN1) from about a thousand tokens: 128 x 192 tiles, 64 x 96 per wave, two blocks
             // per CU.  Measured in the BERT-base forward at 2 x 2048 tokens: -5 % with FFN1 (whose table-lookup epilogue
             // in the 64 x 128 configuration costs more than it saves: its table in LDS takes the third resident block
-            // away), another -1.4 % with QKV
-            if (std::is_same<T, I8>::value && N % 192 == 0 && N >= 2304 && rows.host_rows >= 1024) cfg = 6;
+            // away), another -1.4 % with QKV; the FP16 forward gains 2 %
+            if (N % 192 == 0 && N >= 2304 && rows.host_rows >= 1024) cfg = 6;
             // many tokens (INT8): wave tiles of 64 x 128 halve the LDS operand traffic per MFMA, two such blocks
             // per CU overlap one's epilogue with the other's main loop; long operand rows amortise the epilogue of a
             // 256 x 256 tile by themselves
@@ -696,8 +822,17 @@ hipError_t launch(const void *A, const void *W, void *out, const Epi &epi, Rows 
         // 64 x 96 tiles (six waves of 32 x 32) when they put the problem on more CUs without exceeding one block
         // per CU: the rate at which one CU pulls operands is what bounds these small problems
         if (!forced && N % 96 == 0 && (N / 96) * row_tiles <= 256) {
+            // (measured in the BERT-base forward at 2 x 2048 tokens: two stages held in registers -2 %, three +11 %,
+            // six +3 % against the three-deep LDS ring, although six is the fastest alone: 12.3 against 14.2 us)
+            if constexpr (Epi::STAGED && !std::is_same<Epi, EpiGeluTable>::value) {
+                if (long_k && kbytes % 256 == 0) return launch_longk<T, Epi, 3, 2>(A, W, out, epi, rows, N, K, st, tm);
+            }
             if (long_k) return launch_cfg<T, Epi, 1, 1, 128, 3, 2, 2, 3>(A, W, out, epi, rows, N, K, st, tm);
             return launch_cfg<T, Epi, 1, 1, 128, 2, 2, 2, 3>(A, W, out, epi, rows, N, K, st, tm);
+        }
+        if constexpr (Epi::STAGED && !std::is_same<Epi, EpiGeluTable>::value) {
+            if (!forced && long_k && kbytes % 256 == 0 && (N / 128) * row_tiles <= 256)
+                return launch_longk<T, Epi, 4, 2>(A, W, out, epi, rows, N, K, st, tm);
         }
         if (long_k && (N / 128) * row_tiles <= 256) return launch_cfg<T, Epi, 1, 2, 128, 3, 2>(A, W, out, epi, rows, N, K, st, tm);
         return launch_cfg<T, Epi, 1, 2, 128, 2, 2>(A, W, out, epi, rows, N, K, st, tm);
