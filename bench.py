@@ -199,13 +199,13 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    mode_list = [("FULL_INT8", P.FULL_INT8), ("FFN_INT8", P.FFN_INT8), ("MHA_INT8", P.MHA_INT8), ("FP16", P.FP16)]
-    if a.workload != "C2":
-        mode_list = [("CONFIG", None)]
+    uniform = [("FULL_INT8", P.FULL_INT8), ("FFN_INT8", P.FFN_INT8), ("MHA_INT8", P.MHA_INT8), ("FP16", P.FP16)]
+    # C2 is timed in every uniform mode; the other workloads in the per-layer mask their configuration names
+    mode_list = uniform if a.workload == "C2" else [("CONFIG", None)]
     if a.only_mode:
         # the softmax-output variants of the INT8 attention block are timed on request only
-        mode_list += [("FULL_INT8+PU", P.FULL_INT8 | P.P_UNSIGNED), ("FULL_INT8+P16", P.FULL_INT8 | P.P_FP16)]
-        mode_list = [m for m in mode_list if m[0] == a.only_mode]
+        named = uniform + [("CONFIG", None), ("FULL_INT8+PU", P.FULL_INT8 | P.P_UNSIGNED), ("FULL_INT8+P16", P.FULL_INT8 | P.P_FP16)]
+        mode_list = [m for m in named if m[0] == a.only_mode]
         if not mode_list:
             raise SystemExit(f"unknown mode {a.only_mode}")
         if mode_list[0][1] is not None and mode_list[0][1] & P.P_UNSIGNED:

@@ -69,7 +69,7 @@ enum {
     SAMP_ERR_SHAPE = -2,  /* shape outside the supported set or above max_batch / max_seq         */
     SAMP_ERR_SPACE = -3,  /* arena / workspace too small or misaligned (256 bytes)                */
     SAMP_ERR_HIP = -4,    /* a HIP call failed                                                    */
-    SAMP_ERR_SCALE = -5   /* a scale needed by an INT8 block is not finite or not positive        */
+    SAMP_ERR_SCALE = -5   /* a scale needed by an INT8 block is not finite, not positive or out of range */
 };
 
 /* Supported shapes: head size hidden/heads == 64; hidden % 128 == 0; ffn % 128 == 0;
@@ -309,7 +309,10 @@ SAMP_API int samp_gemm_f16(const uint16_t *A, const uint16_t *W, const float *bi
  * ignored and p_hist must be NULL.
  * p_hist: NULL, or dev uint64 [256] to which the kernel ADDS the number of times each code byte
  * (index = the code as an unsigned byte) occurs among the softmax codes of valid query/key pairs
- * (the caller zeroes it): the code-usage statistic of Appendix B.                                 */
+ * (the caller zeroes it): the code-usage statistic of Appendix B.
+ * s_q * s_k / 8 must not exceed 256 (SAMP_ERR_SCALE; samp_encoder_create applies the same bound to
+ * every INT8 attention block): beyond it a softmax is an argmax and the scores leave the range the
+ * exponential is evaluated on.                                                                     */
 SAMP_API int samp_attention_i8(const int8_t *qkv, const int32_t *cu_seqlens, int32_t B, int32_t max_len, int32_t hidden,
                                int32_t heads, float s_q, float s_k, float s_v, float s_p, float s_ctx, int32_t p_kind,
                                int8_t *ctx, uint64_t *p_hist, void *stream);

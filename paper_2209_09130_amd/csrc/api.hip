@@ -35,6 +35,10 @@ constexpr size_t ALIGN = 256;
 size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 bool good_scale(float s) { return std::isfinite(s) && s > 0.0f; }
+// An int8 score is at most 64 * 127 * 127 in magnitude, so with the multiplier bounded like this the argument of
+// the softmax exponential stays above -2^30, the range its integer exponent arithmetic is good for.
+constexpr float MAX_SCORE_MULTIPLIER = 256.0f;
+bool good_score_multiplier(float m) { return m > 0.0f && m <= MAX_SCORE_MULTIPLIER; }
 
 struct Layer {
     int mode;
@@ -423,6 +427,8 @@ int samp_encoder_create(const samp_config_t *cfg, const uint8_t *modes, const sa
                     HIP_TRY(launch_fold(nullptr, Y.s.x, s_w + part * H, Y.b_qkv + part * H, so[part], (int)H,
                                         Y.m_qkv + part * H, Y.bq_qkv + part * H, st));
                 Y.m_sc = (float)((double)Y.s.q * (double)Y.s.k / std::sqrt(64.0));
+                if (!good_score_multiplier(Y.m_sc))
+                    return fail(SAMP_ERR_SCALE, "layer %d: s_q * s_k / 8 must not exceed %g", l, (double)MAX_SCORE_MULTIPLIER);
                 Y.inv_sp = 1.0f / Y.s.p;
                 Y.m_ctx = (Y.mode & SAMP_P_FP16) ? (float)((double)Y.s.v / (double)Y.s.ctx)
                                                  : (float)((double)Y.s.p * (double)Y.s.v / (double)Y.s.ctx);
@@ -791,6 +797,7 @@ int samp_attention_i8(const int8_t *qkv, const int32_t *cu, int32_t B, int32_t m
     if (!(good_scale(s_q) && good_scale(s_k) && good_scale(s_v) && (p_kind == 2 || good_scale(s_p)) && good_scale(s_ctx)))
         return fail(SAMP_ERR_SCALE, "attention scales must be finite and positive");
     const float m_sc = (float)((double)s_q * (double)s_k / std::sqrt(64.0));
+    if (!good_score_multiplier(m_sc)) return fail(SAMP_ERR_SCALE, "s_q * s_k / 8 must not exceed %g", (double)MAX_SCORE_MULTIPLIER);
     if (p_kind == 2) {
         if (p_hist) return fail(SAMP_ERR_ARG, "a binary16 softmax output has no code histogram");
         HIP_TRY(launch_attention_i8_p16(qkv, cu, B, max_len, hidden, heads, m_sc, (float)((double)s_v / (double)s_ctx), ctx,

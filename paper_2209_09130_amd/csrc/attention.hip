@@ -30,9 +30,10 @@ constexpr int VT_STRIDE_F16 = 72;      // bytes per V^T row (32 keys + pad), fp1
 // of degree 11 in r (truncation below 2^-47), scaled by 2^k.  Its error is far below a binary32
 // ulp, so rounding the result to binary32 gives the correctly rounded exponential (up to ties
 // narrower than 2^-45), which is what the quantiser's decision is defined on.
-// The caller clamps x to [-746, 0] (in binary32; -inf of a masked key becomes a value whose
-// exponential rounds to 0).  k = rint(x / ln2) comes out of one fma with 1.5 * 2^52: the sum's low
-// dword is k as an integer, the sum minus the constant is k as a double.
+// x must be finite and above -2^30 (the host bounds the score multiplier accordingly): far below -746 the
+// scaling by 2^k underflows to 0 like the exponential itself.  The -inf of a masked key is clamped to
+// -746 by the caller.  k = rint(x / ln2) comes out of one fma with 1.5 * 2^52: the sum's low dword is k
+// as an integer, the sum minus the constant is k as a double.
 __device__ __forceinline__ double exp_nonpos(double x)
 {
     const double shifted = __builtin_fma(x, 1.44269504088896338700e+00, 6755399441055744.0);
@@ -55,6 +56,17 @@ __device__ __forceinline__ double exp_nonpos(double x)
     return __builtin_ldexp(p, ki);
 }
 
+// The wave's number inside its block, as a scalar: every test on it (does this wave own key tile j?) then is a
+// scalar branch instead of a lane mask with copies of the live registers where the paths join.
+__device__ __forceinline__ int wave_index() { return __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6); }
+
+__device__ __forceinline__ int opaque_zero()
+{
+    int z;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(z));
+    return z;
+}
+
 struct SeqInfo { int t0, n; };
 __device__ __forceinline__ SeqInfo seq_info(const int *cu, int b, int max_len)
 {
@@ -68,8 +80,10 @@ __device__ __forceinline__ SeqInfo seq_info(const int *cu, int b, int max_len)
 //     a row of ones; both are exact in int32.
 // HIST: also counts every softmax code of a valid (query, key) pair into p_hist[256] (a diagnostic:
 //     which of the 256 integers the softmax output uses, as Appendix B tabulates).
+// At least two waves per SIMD are asked for so that the register budget is one the matrix-core results fit
+// without the accumulation registers: the products then land where the vector ALU reads them.
 template <int NT, bool PU, bool HIST>
-__global__ __launch_bounds__(256) void attention_i8_kernel(const int8_t *__restrict__ qkv, const int *__restrict__ cu,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void attention_i8_kernel(const int8_t *__restrict__ qkv, const int *__restrict__ cu,
                                                            int max_len, int H, float m_sc, float inv_sp, float m_ctx,
                                                            int8_t *__restrict__ ctx, unsigned long long *__restrict__ p_hist)
 {
@@ -88,7 +102,7 @@ __global__ __launch_bounds__(256) void attention_i8_kernel(const int8_t *__restr
     const int q0 = (item % nqb) * QB;
     if (q0 >= sq.n) return;
     const int n = sq.n;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, g = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, w = wave_index(), r = lane & 31, g = lane >> 5;
     const unsigned ld = 3u * (unsigned)H;                          // row offsets inside a sequence fit 32 bits
     const int8_t *base = qkv + (size_t)sq.t0 * ld + head * 64;
     if (HIST) hist[tid] = 0;                                      // ordered before its use by the barriers below
@@ -155,26 +169,42 @@ __global__ __launch_bounds__(256) void attention_i8_kernel(const int8_t *__restr
     __syncthreads();
     mx = __builtin_fmaxf(__builtin_fmaxf(smax[0][r], smax[1][r]), __builtin_fmaxf(smax[2][r], smax[3][r]));
 
+    // tiles past the end are skipped here and below; only a ragged tile holds masked keys (score -inf), whose
+    // argument is clamped so that the exponential comes out as 0; in a full tile every argument is finite
     double part = 0.0;
 #pragma unroll
-    for (int i = 0; i < NT; i++)
+    for (int i = 0; i < NT; i++) {
+        const int j0 = (w + 4 * i) * 32;
+        if (j0 + 32 <= n) {
 #pragma unroll
-        for (int e = 0; e < 16; e++) {
-            const float ev = (float)exp_nonpos((double)__builtin_fmaxf(sc[i][e] - mx, -746.0f));   // 0 for masked keys (score -inf)
-            sc[i][e] = ev;
-            part += (double)ev;
+            for (int e = 0; e < 16; e++) {
+                const float ev = (float)exp_nonpos((double)(sc[i][e] - mx));
+                sc[i][e] = ev;
+                part += (double)ev;
+            }
+        } else if (j0 < n) {
+#pragma unroll
+            for (int e = 0; e < 16; e++) {
+                const float ev = (float)exp_nonpos((double)__builtin_fmaxf(sc[i][e] - mx, -746.0f));
+                sc[i][e] = ev;
+                part += (double)ev;
+            }
         }
+    }
     part += __shfl_xor(part, 32, 64);
     if (g == 0) ssum[w][r] = part;
     __syncthreads();
     const float S = (float)(((ssum[0][r] + ssum[1][r]) + ssum[2][r]) + ssum[3][r]);
     const float rS = __fdiv_rn(1.0f, S);
 
+    // Every accumulator register starts from a zero of its own that the compiler cannot see through: with literal
+    // zeros it gives the first product of each path registers of its own and copies all 32 accumulators where the
+    // paths join.
     v16i o[2], o1[PU ? 2 : 1];
 #pragma unroll
     for (int cb = 0; cb < 2; cb++)
 #pragma unroll
-        for (int e = 0; e < 16; e++) { o[cb][e] = 0; if (PU) o1[cb][e] = 0; }
+        for (int e = 0; e < 16; e++) { o[cb][e] = opaque_zero(); if (PU) o1[cb][e] = opaque_zero(); }
     const float lo = PU ? 0.0f : -127.0f, hi = PU ? 255.0f : 127.0f;
     const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
 #pragma unroll
@@ -253,7 +283,7 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const __half *__rest
     const int q0 = (item % nqb) * QB;
     if (q0 >= sq.n) return;
     const int n = sq.n;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, g = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, w = wave_index(), r = lane & 31, g = lane >> 5;
     const unsigned ld = 3u * (unsigned)H;
     const __half *base = qkv + (size_t)sq.t0 * ld + head * 64;
 
@@ -403,7 +433,7 @@ __global__ __launch_bounds__(256) void attention_i8_long_kernel(const int8_t *__
     const int q0 = (item % nqb) * QB;
     if (q0 >= sq.n) return;
     const int n = sq.n;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, g = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, w = wave_index(), r = lane & 31, g = lane >> 5;
     const unsigned ld = 3u * (unsigned)H;
     const int8_t *base = qkv + (size_t)sq.t0 * ld + head * 64;
     if (HIST) hist[tid] = 0;
@@ -573,7 +603,7 @@ __device__ __forceinline__ void p16_mfma(const v4i (&pf)[4], const int8_t *slab,
 __device__ __forceinline__ void p16_finish(const v16i (&o)[4], int cb, long long (&so)[4][QB][32], float m_ctx,
                                            int8_t *ctx_rows, int H, int rows_left, int tid)
 {
-    const int lane = tid & 63, w = tid >> 6, r = lane & 31, g = lane >> 5;
+    const int lane = tid & 63, w = wave_index(), r = lane & 31, g = lane >> 5;
     const int query = tid >> 3, c0 = (tid & 7) * 4;
     if (cb) __syncthreads();                                      // the previous block's partials have been read
 #pragma unroll
@@ -614,7 +644,7 @@ attention_i8_p16_kernel(const int8_t *__restrict__ qkv, const int *__restrict__ 
     const int q0 = (item % nqb) * QB;
     if (q0 >= sq.n) return;
     const int n = sq.n;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, g = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, w = wave_index(), r = lane & 31, g = lane >> 5;
     const unsigned ld = 3u * (unsigned)H;
     const int8_t *base = qkv + (size_t)sq.t0 * ld + head * 64;
     const int8_t *vp = base + 2 * H;
@@ -752,7 +782,7 @@ __global__ __launch_bounds__(256) void attention_f16_long_kernel(const __half *_
     const int q0 = (item % nqb) * QB;
     if (q0 >= sq.n) return;
     const int n = sq.n;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r = lane & 31, g = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, w = wave_index(), r = lane & 31, g = lane >> 5;
     const unsigned ld = 3u * (unsigned)H;
     const __half *base = qkv + (size_t)sq.t0 * ld + head * 64;
 

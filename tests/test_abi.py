@@ -98,3 +98,10 @@ def test_later_entry_points_reject_bad_arguments_on_the_host(L):
     assert L.samp_set_gemm_config(-1) == 0
     assert L.samp_attention_i8(None, None, 1, 16, 128, 2, C.c_float(1), C.c_float(1), C.c_float(1), C.c_float(1), C.c_float(1),
                                0, None, None, None) == -1
+    # a score multiplier s_q s_k / 8 above 256 is refused on the host (the softmax exponential's argument range)
+    aligned = (C.c_char * 4096)()
+    base = (C.addressof(aligned) + 255) & ~255
+    ptr, cu = C.c_void_p(base), C.c_void_p(base + 2048)
+    assert L.samp_attention_i8(ptr, cu, 1, 16, 128, 2, C.c_float(64), C.c_float(64), C.c_float(1), C.c_float(1), C.c_float(1),
+                               0, ptr, None, None) == -5
+    assert b"256" in L.samp_last_error()
