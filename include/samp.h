@@ -302,7 +302,7 @@ SAMP_API int samp_gemm_f16(const uint16_t *A, const uint16_t *W, const float *bi
 
 /* Softmax attention over packed rows.  qkv: dev [T,3H] (int8 or fp16), columns [0,H) Q, [H,2H) K,
  * [2H,3H) V.  cu_seqlens: dev int32 [B+1], sequence b owns rows cu[b]..cu[b+1); max_len >= every
- * length, <= SAMP_MAX_SEQ.  INT8 flavour (Section 4.2 / Appendix B: quantised softmax output):
+ * length, <= SAMP_MAX_SEQ.  cu_seqlens NULL: B sequences of exactly max_len rows each (T = B max_len).  INT8 flavour (Section 4.2 / Appendix B: quantised softmax output):
  * score = float(q.k) * (s_q s_k / 8); P = softmax; p_kind 0: Pq = rne(P / s_p) clamped to
  * [-127, 127]; p_kind 1: clamped to [0, 255]; ctx = rne(float(Pq.V) * s_p s_v / s_ctx).
  * p_kind 2: P is rounded to binary16 instead, ctx = rne(fl32(sum P16 V) * s_v / s_ctx), s_p is

@@ -281,16 +281,25 @@ def gemm_f16(A, W, bias, gelu: bool) -> torch.Tensor:
     return out
 
 
+def _batch_of(cu, T: int, max_len: int) -> int:
+    if cu is not None:
+        return cu.numel() - 1
+    assert T % max_len == 0, "without sequence offsets every sequence has max_len rows"
+    return T // max_len
+
+
 def attention_i8(qkv, cu, max_len: int, heads: int, s_q, s_k, s_v, s_p, s_ctx, p_unsigned: bool = False,
                  want_hist: bool = False, p_fp16: bool = False):
     """Returns ctx, or (ctx, hist) with hist = int64 [256] counts of the softmax codes (index = code byte).
-    p_fp16: the softmax output stays binary16 (s_p unused, no histogram)."""
+    p_fp16: the softmax output stays binary16 (s_p unused, no histogram).
+    cu None: qkv holds T / max_len sequences of exactly max_len rows each."""
     assert not (p_fp16 and (p_unsigned or want_hist))
     T, H3 = qkv.shape
     H = H3 // 3
+    B = _batch_of(cu, T, max_len)
     ctx = torch.zeros((T, H), dtype=torch.int8, device=qkv.device)
     hist = torch.zeros(256, dtype=torch.int64, device=qkv.device) if want_hist else None
-    _check(lib().samp_attention_i8(_dp(qkv), _dp(cu), cu.numel() - 1, max_len, H, heads, _f(s_q), _f(s_k), _f(s_v),
+    _check(lib().samp_attention_i8(_dp(qkv), _dp(cu), B, max_len, H, heads, _f(s_q), _f(s_k), _f(s_v),
                                    _f(s_p), _f(s_ctx), 2 if p_fp16 else int(bool(p_unsigned)), _dp(ctx), _dp(hist), _stream()))
     return (ctx, hist) if want_hist else ctx
 
@@ -316,7 +325,7 @@ def attention_f16(qkv, cu, max_len: int, heads: int) -> torch.Tensor:
     T, H3 = qkv.shape
     H = H3 // 3
     ctx = torch.zeros((T, H), dtype=torch.float16, device=qkv.device)
-    _check(lib().samp_attention_f16(_dp(qkv), _dp(cu), cu.numel() - 1, max_len, H, heads, _dp(ctx), _stream()))
+    _check(lib().samp_attention_f16(_dp(qkv), _dp(cu), _batch_of(cu, T, max_len), max_len, H, heads, _dp(ctx), _stream()))
     return ctx
 
 

@@ -781,7 +781,8 @@ int samp_gemm_f16(const uint16_t *A, const uint16_t *W, const float *bias, int32
 
 static int check_attention(const void *qkv, const int32_t *cu, int B, int max_len, int hidden, int heads, const void *ctx)
 {
-    if (!qkv || !cu || !ctx) return fail(SAMP_ERR_ARG, "NULL pointer");
+    (void)cu;                                                     // NULL: B sequences of exactly max_len rows
+    if (!qkv || !ctx) return fail(SAMP_ERR_ARG, "NULL pointer");
     if (B < 1 || max_len < 1 || max_len > SAMP_MAX_SEQ) return fail(SAMP_ERR_SHAPE, "B >= 1 and 1 <= max_len <= %d required", SAMP_MAX_SEQ);
     if (heads < 1 || hidden != heads * 64) return fail(SAMP_ERR_SHAPE, "head size must be 64");
     if (!aligned(qkv, 16) || !aligned(ctx, 16)) return fail(SAMP_ERR_ARG, "tensors must be 16-byte aligned");

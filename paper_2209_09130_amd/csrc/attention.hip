@@ -26,10 +26,14 @@ constexpr int ONE_PASS_MAX_LEN = 512;  // longest sequence whose score strip sta
 constexpr int VT_STRIDE_I8 = 36;       // bytes per V^T row (32 keys + pad), int8
 constexpr int VT_STRIDE_F16 = 72;      // bytes per V^T row (32 keys + pad), fp16
 
-// exp(x) for x <= 0 in binary64: x = k ln2 + r with |r| <= ln2 / 2 (two-part ln2), Taylor polynomial
-// of degree 11 in r (truncation below 2^-47), scaled by 2^k.  Its error is far below a binary32
-// ulp, so rounding the result to binary32 gives the correctly rounded exponential (up to ties
-// narrower than 2^-45), which is what the quantiser's decision is defined on.
+// exp(x) for x <= 0 in binary64: x = k ln2 + r with |r| <= ln2 / 2 (two-part ln2), then
+//     exp(r) = 1 + r (1 + r q(r)),
+// q a polynomial of degree 8 that interpolates (exp(r) - 1 - r) / r^2 at the nine Chebyshev nodes of
+// [-0.34665, 0.34665] (coefficients solved in rational arithmetic and rounded to binary64), scaled by 2^k.
+// Checked against a 60-digit exponential with every fused multiply-add emulated exactly: relative error
+// below 2^-49 over the whole argument range, far below a binary32 ulp, so rounding the result to binary32
+// gives the correctly rounded exponential (up to ties narrower than 2^-49), which is what the quantiser's
+// decision is defined on.  One operation shorter than the Taylor polynomial of the same accuracy.
 // x must be finite and above -2^30 (the host bounds the score multiplier accordingly): far below -746 the
 // scaling by 2^k underflows to 0 like the exponential itself.  The -inf of a masked key is clamped to
 // -746 by the caller.  k = rint(x / ln2) comes out of one fma with 1.5 * 2^52: the sum's low dword is k
@@ -41,16 +45,15 @@ __device__ __forceinline__ double exp_nonpos(double x)
     const double k = shifted - 6755399441055744.0;
     double r = __builtin_fma(k, -6.93147180369123816490e-01, x);
     r = __builtin_fma(k, -1.90821492927058770002e-10, r);
-    double p = 2.50521083854417187751e-08;               // 1/11!
-    p = __builtin_fma(p, r, 2.75573192239858906526e-07); // 1/10!
-    p = __builtin_fma(p, r, 2.75573192239858906526e-06); // 1/9!
-    p = __builtin_fma(p, r, 2.48015873015873015873e-05); // 1/8!
-    p = __builtin_fma(p, r, 1.98412698412698412698e-04); // 1/7!
-    p = __builtin_fma(p, r, 1.38888888888888888889e-03); // 1/6!
-    p = __builtin_fma(p, r, 8.33333333333333333333e-03); // 1/5!
-    p = __builtin_fma(p, r, 4.16666666666666666667e-02); // 1/4!
-    p = __builtin_fma(p, r, 1.66666666666666666667e-01); // 1/3!
-    p = __builtin_fma(p, r, 5.00000000000000000000e-01);
+    double p = 0x1.28804ab1d4135p-22;
+    p = __builtin_fma(p, r, 0x1.72c73b05aa600p-19);
+    p = __builtin_fma(p, r, 0x1.a019c99e7c005p-16);
+    p = __builtin_fma(p, r, 0x1.a019ad9901febp-13);
+    p = __builtin_fma(p, r, 0x1.6c16c17391579p-10);
+    p = __builtin_fma(p, r, 0x1.1111111c49a25p-7);
+    p = __builtin_fma(p, r, 0x1.5555555554cb5p-5);
+    p = __builtin_fma(p, r, 0x1.5555555553b71p-3);
+    p = __builtin_fma(p, r, 0.5);
     p = __builtin_fma(p, r, 1.0);
     p = __builtin_fma(p, r, 1.0);
     return __builtin_ldexp(p, ki);
@@ -88,8 +91,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
                                                            int8_t *__restrict__ ctx, unsigned long long *__restrict__ p_hist)
 {
     __shared__ unsigned hist[HIST ? 256 : 1];
-    __shared__ __attribute__((aligned(16))) int8_t vt[4][NT][64 * VT_STRIDE_I8];
-    __shared__ __attribute__((aligned(16))) int so[4][QB][64];
+    // One slab per wave: first its V^T tiles (written and read by that wave alone), then, once its last P.V
+    // product has read them, its partial context for the other waves; sharing the bytes lets a third block fit a CU.
+    constexpr int VT_TILE = 64 * VT_STRIDE_I8, SO_BYTES = QB * 64 * 4;
+    constexpr int SLAB = NT * VT_TILE > SO_BYTES ? NT * VT_TILE : SO_BYTES;
+    __shared__ __attribute__((aligned(16))) int8_t slab[4][SLAB];
+    auto so = [&](int wave) { return reinterpret_cast<int(*)[64]>(slab[wave]); };
     __shared__ float smax[4][QB];
     __shared__ double ssum[4][QB];
 
@@ -119,33 +126,49 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
     for (int i = 0; i < NT; i++) {
         const int j0 = (w + 4 * i) * 32;
         if (j0 < n) {                                           // wave-uniform
+            // the K rows are requested first, then the V rows: the first product then waits for the K rows only
             const int krow = min(j0 + r, n - 1);
             const int8_t *kp = base + (unsigned)krow * ld + H;
+            v4i kf[2];
+#pragma unroll
+            for (int ks = 0; ks < 2; ks++) kf[ks] = *reinterpret_cast<const v4i *>(kp + ks * 32 + g * 16);
+            // stage V^T of this key tile: a lane transposes two 4 keys x 4 channels byte blocks in
+            // registers (v_perm_b32) and stores them as dwords of 4 consecutive keys per channel
+            const int8_t *vp = base + 2 * H;
+            const bool full = j0 + 32 <= n;                      // wave-uniform
+            const int cq = lane & 15;
+            unsigned d[2][4];                                    // all eight loads are issued before the first is used
+            if (full) {                                          // four consecutive key rows: one address, three strides
+#pragma unroll
+                for (int u = 0; u < 2; u++) {
+                    const int8_t *p0 = vp + (unsigned)(j0 + 4 * ((lane >> 4) + 4 * u)) * ld + 4 * cq;
+#pragma unroll
+                    for (int t = 0; t < 4; t++) d[u][t] = *reinterpret_cast<const unsigned *>(p0 + t * ld);
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < 2; u++)
+#pragma unroll
+                    for (int t = 0; t < 4; t++)
+                        d[u][t] = *reinterpret_cast<const unsigned *>(vp + (unsigned)min(j0 + 4 * ((lane >> 4) + 4 * u) + t, n - 1) * ld + 4 * cq);
+            }
             v16i acc;
 #pragma unroll
             for (int e = 0; e < 16; e++) acc[e] = 0;
 #pragma unroll
-            for (int ks = 0; ks < 2; ks++)
-                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(*reinterpret_cast<const v4i *>(kp + ks * 32 + g * 16), qf[ks], acc, 0, 0, 0);
-            // stage V^T of this key tile: a lane transposes two 4 keys x 4 channels byte blocks in
-            // registers (v_perm_b32) and stores them as dwords of 4 consecutive keys per channel
-            const int8_t *vp = base + 2 * H;
+            for (int ks = 0; ks < 2; ks++) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf[ks], qf[ks], acc, 0, 0, 0);
 #pragma unroll
             for (int u = 0; u < 2; u++) {
-                const int cq = lane & 15, kq = (lane >> 4) + 4 * u;
-                unsigned d[4];
-#pragma unroll
-                for (int t = 0; t < 4; t++)
-                    d[t] = *reinterpret_cast<const unsigned *>(vp + (unsigned)min(j0 + 4 * kq + t, n - 1) * ld + 4 * cq);
-                const unsigned t01l = __builtin_amdgcn_perm(d[1], d[0], 0x05010400u), t23l = __builtin_amdgcn_perm(d[3], d[2], 0x05010400u);
-                const unsigned t01h = __builtin_amdgcn_perm(d[1], d[0], 0x07030602u), t23h = __builtin_amdgcn_perm(d[3], d[2], 0x07030602u);
-                unsigned *dst = reinterpret_cast<unsigned *>(&vt[w][i][(4 * cq) * VT_STRIDE_I8 + 4 * kq]);
+                const int kq = (lane >> 4) + 4 * u;
+                const unsigned t01l = __builtin_amdgcn_perm(d[u][1], d[u][0], 0x05010400u), t23l = __builtin_amdgcn_perm(d[u][3], d[u][2], 0x05010400u);
+                const unsigned t01h = __builtin_amdgcn_perm(d[u][1], d[u][0], 0x07030602u), t23h = __builtin_amdgcn_perm(d[u][3], d[u][2], 0x07030602u);
+                unsigned *dst = reinterpret_cast<unsigned *>(&slab[w][i * VT_TILE + (4 * cq) * VT_STRIDE_I8 + 4 * kq]);
                 dst[0 * (VT_STRIDE_I8 / 4)] = __builtin_amdgcn_perm(t23l, t01l, 0x05040100u);
                 dst[1 * (VT_STRIDE_I8 / 4)] = __builtin_amdgcn_perm(t23l, t01l, 0x07060302u);
                 dst[2 * (VT_STRIDE_I8 / 4)] = __builtin_amdgcn_perm(t23h, t01h, 0x05040100u);
                 dst[3 * (VT_STRIDE_I8 / 4)] = __builtin_amdgcn_perm(t23h, t01h, 0x07060302u);
             }
-            if (j0 + 32 <= n) {                                  // wave-uniform: a full tile needs no masking
+            if (full) {                                          // a full tile needs no masking
 #pragma unroll
                 for (int e = 0; e < 16; e++) {
                     sc[i][e] = (float)acc[e] * m_sc;
@@ -159,10 +182,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
                     mx = __builtin_fmaxf(mx, sc[i][e]);
                 }
             }
-        } else {
-#pragma unroll
-            for (int e = 0; e < 16; e++) sc[i][e] = -INFINITY;
-        }
+        }                                                        // the scores of a tile past the end are never read
     }
     mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32, 64));
     if (g == 0) smax[w][r] = mx;
@@ -229,7 +249,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
                 v4i vf;
 #pragma unroll
                 for (int q = 0; q < 4; q++)
-                    vf[q] = *reinterpret_cast<const int *>(&vt[w][i][(cb * 32 + r) * VT_STRIDE_I8 + 8 * q + 4 * g]);
+                    vf[q] = *reinterpret_cast<const int *>(&slab[w][i * VT_TILE + (cb * 32 + r) * VT_STRIDE_I8 + 8 * q + 4 * g]);
                 o[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(pf, vf, o[cb], 0, 0, 0);
                 if (PU) o1[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ones, vf, o1[cb], 0, 0, 0);
             }
@@ -245,7 +265,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
 #pragma unroll
     for (int cb = 0; cb < 2; cb++)
 #pragma unroll
-        for (int e = 0; e < 16; e++) so[w][8 * (e >> 2) + 4 * g + (e & 3)][cb * 32 + r] = o[cb][e];
+        for (int e = 0; e < 16; e++) so(w)[8 * (e >> 2) + 4 * g + (e & 3)][cb * 32 + r] = o[cb][e];
     __syncthreads();
 
     const int query = tid >> 3, c0 = (tid & 7) * 8;
@@ -253,7 +273,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
         int codes[8];
 #pragma unroll
         for (int e = 0; e < 8; e++) {
-            const int O = ((so[0][query][c0 + e] + so[1][query][c0 + e]) + so[2][query][c0 + e]) + so[3][query][c0 + e];
+            const int O = ((so(0)[query][c0 + e] + so(1)[query][c0 + e]) + so(2)[query][c0 + e]) + so(3)[query][c0 + e];
             codes[e] = qcode((float)O * m_ctx);
         }
         v2i pk = {pack4(codes[0], codes[1], codes[2], codes[3]), pack4(codes[4], codes[5], codes[6], codes[7])};
@@ -874,15 +894,17 @@ static void launch_attention_i8_variant(const int8_t *qkv, const int *cu, int B,
                                         float inv_sp, float m_ctx, int8_t *ctx, unsigned long long *p_hist, hipStream_t st,
                                         const Timing *tm)
 {
-    dim3 grid((unsigned)((max_len + QB - 1) / QB) * heads * B), block(256);
+    dim3 grid((unsigned)((max_len + QB - 1) / QB) * heads * B);
     if (max_len <= 128)
-        launch_kernel(attention_i8_kernel<1, PU, HIST>, grid, block, 0, st, tm, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx, p_hist);
+        launch_kernel(attention_i8_kernel<1, PU, HIST>, grid, dim3(256), 0, st, tm, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx, p_hist);
     else if (max_len <= 256)
-        launch_kernel(attention_i8_kernel<2, PU, HIST>, grid, block, 0, st, tm, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx, p_hist);
+        launch_kernel(attention_i8_kernel<2, PU, HIST>, grid, dim3(256), 0, st, tm, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx, p_hist);
+    else if (max_len <= 384)
+        launch_kernel(attention_i8_kernel<3, PU, HIST>, grid, dim3(256), 0, st, tm, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx, p_hist);
     else if (max_len <= ONE_PASS_MAX_LEN)
-        launch_kernel(attention_i8_kernel<4, PU, HIST>, grid, block, 0, st, tm, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx, p_hist);
+        launch_kernel(attention_i8_kernel<4, PU, HIST>, grid, dim3(256), 0, st, tm, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx, p_hist);
     else
-        launch_kernel(attention_i8_long_kernel<PU, HIST>, grid, block, 0, st, tm, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx, p_hist);
+        launch_kernel(attention_i8_long_kernel<PU, HIST>, grid, dim3(256), 0, st, tm, qkv, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx, p_hist);
 }
 
 hipError_t launch_attention_i8(const int8_t *qkv, const int *cu, int B, int max_len, int H, int heads, float m_sc,

@@ -279,6 +279,25 @@ def test_int8_attention_bit_exact(P, lens, heads):
     assert np.abs(want).max() > 20
 
 
+@pytest.mark.parametrize("S,B,heads,unsigned", [(128, 3, 2, False), (256, 2, 1, False), (384, 2, 1, False),
+                                                (512, 2, 1, False), (512, 1, 2, True), (96, 3, 1, False), (320, 2, 1, False)])
+def test_int8_attention_without_sequence_offsets_bit_exact(P, S, B, heads, unsigned):
+    """cu_seqlens NULL: B sequences of exactly S rows.  Lengths of 128, 256, 384 and 512 take the kernels that
+    carry no length tests at all; the others the general ones.  Same bytes as with explicit offsets, and the oracle's."""
+    rng = np.random.default_rng(S + B)
+    H = heads * 64
+    cu = _cu([S] * B)
+    qkv = np.clip(np.rint(rng.standard_normal((B * S, 3 * H)) * 26), -127, 127).astype(np.int8)
+    sc = (0.0209, 0.0249, 0.021, 0.0003 * (0.5 if unsigned else 1.0), 0.0021)
+    want = oracle.attention_i8(qkv, cu, heads, *sc, p_unsigned=unsigned)
+    got = host(P.attention_i8(dev(qkv), None, S, heads, *sc, p_unsigned=unsigned))
+    assert np.array_equal(got, want)
+    with_offsets = host(P.attention_i8(dev(qkv), dev(cu), S, heads, *sc, p_unsigned=unsigned))
+    assert np.array_equal(with_offsets, want)
+    half = host(P.attention_f16(dev(qkv.astype(np.float16)), None, S, heads))
+    assert np.array_equal(half, host(P.attention_f16(dev(qkv.astype(np.float16)), dev(cu), S, heads)))
+
+
 def test_int8_attention_peaked_softmax_bit_exact(P):
     # a large score step makes the softmax peaked: codes span 0..127 and clamp
     rng = np.random.default_rng(5)
