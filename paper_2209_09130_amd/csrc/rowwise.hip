@@ -64,7 +64,9 @@ template <bool I8> __device__ __forceinline__ void load16(const void *p, size_t 
 // Second half of a LayerNorm row held by 16 lanes (z: this lane's channels, sum: its partial sum):
 // binary64 mean and variance, binary32 normalisation, output as int8 codes or fp16 at element
 // offset obase, optional running absmax of the fp16 output.
-template <int NJ, bool OUT_I8>
+// WHOLE: H == 256 NJ, every lane owns NJ full sections and the tests against H fold away (with them the branches
+// that keep the compiler from requesting all sections of a row at once).
+template <int NJ, bool OUT_I8, bool WHOLE = false>
 __device__ __forceinline__ void ln_finish(const float (&z)[NJ][16], double sum, int H, int sub, const float *gamma,
                                           const float *beta, float eps, float s_out, void *out, size_t obase, float *absmax_out)
 {
@@ -72,9 +74,9 @@ __device__ __forceinline__ void ln_finish(const float (&z)[NJ][16], double sum, 
     double sq = 0.0;
 #pragma unroll
     for (int j = 0; j < NJ; j++) {
-        if (j * 256 + sub * 16 < H) {
+        if (WHOLE || j * 256 + sub * 16 < H) {
 #pragma unroll
-            for (int e = 0; e < 16; e++) { const double d = (double)z[j][e] - mu; sq += d * d; }
+            for (int e = 0; e < 16; e++) { const double d = (double)z[j][e] - mu; sq = __builtin_fma(d, d, sq); }
         }
     }
     const double var = row16_sum(sq) / (double)H;
@@ -85,7 +87,7 @@ __device__ __forceinline__ void ln_finish(const float (&z)[NJ][16], double sum, 
 #pragma unroll
     for (int j = 0; j < NJ; j++) {
         const int c = j * 256 + sub * 16;
-        if (c < H) {
+        if (WHOLE || c < H) {
             float y[16];
 #pragma unroll
             for (int q = 0; q < 4; q++) {
@@ -122,7 +124,7 @@ __device__ __forceinline__ void ln_finish(const float (&z)[NJ][16], double sum, 
     }
 }
 
-template <int NJ, bool IN_I8, bool RES_I8, bool OUT_I8>
+template <int NJ, bool IN_I8, bool RES_I8, bool OUT_I8, bool WHOLE>
 __global__ __launch_bounds__(16 * LN_ROWS) void add_ln_kernel(AddLnArgs a)
 {
     const int M = a.rows.dev_rows ? *a.rows.dev_rows : a.rows.host_rows;
@@ -132,13 +134,14 @@ __global__ __launch_bounds__(16 * LN_ROWS) void add_ln_kernel(AddLnArgs a)
     if (row >= M) return;                               // whole 16-lane rows leave together
     const int sub = threadIdx.x & 15, H = a.H;
     const size_t base = (size_t)row * H;
+    const int out_row = a.row_map ? a.row_map[row] : row;        // requested with the row's data, not after it
 
     float z[NJ][16];
     double sum = 0.0;
 #pragma unroll
     for (int j = 0; j < NJ; j++) {
         const int c = j * 256 + sub * 16;
-        if (c < H) {
+        if (WHOLE || c < H) {
             float x[16], r[16];
             load16<IN_I8>(a.in, base + c, x);
             load16<RES_I8>(a.res, base + c, r);
@@ -158,17 +161,21 @@ __global__ __launch_bounds__(16 * LN_ROWS) void add_ln_kernel(AddLnArgs a)
             for (int e = 0; e < 16; e++) z[j][e] = 0.0f;
         }
     }
-    ln_finish<NJ, OUT_I8>(z, sum, H, sub, a.gamma, a.beta, a.eps, a.s_out, a.out,
-                          (size_t)(a.row_map ? a.row_map[row] : row) * H, a.absmax_out);
+    ln_finish<NJ, OUT_I8, WHOLE>(z, sum, H, sub, a.gamma, a.beta, a.eps, a.s_out, a.out,
+                                 (size_t)out_row * H, a.absmax_out);
 }
 
 template <int NJ>
 hipError_t launch_add_ln_nj(const AddLnArgs &a, hipStream_t st, const Timing *tm)
 {
     dim3 grid((a.rows.host_rows + LN_ROWS - 1) / LN_ROWS), block(16 * LN_ROWS);
+    // width 768 has an instance without tests against H (at 1024 the requests of a whole row in flight take so many
+    // registers that the forward gets slower)
+    constexpr bool WHOLE_WIDTHS = NJ == 3;
 #define SAMP_LN_CASE(I, R, O)                                                                              \
     if (a.in_i8 == I && a.res_i8 == R && a.out_i8 == O) {                                                  \
-        launch_kernel(add_ln_kernel<NJ, I, R, O>, grid, block, 0, st, tm, a);                           \
+        if (WHOLE_WIDTHS && a.H == 256 * NJ) launch_kernel(add_ln_kernel<NJ, I, R, O, WHOLE_WIDTHS>, grid, block, 0, st, tm, a); \
+        else launch_kernel(add_ln_kernel<NJ, I, R, O, false>, grid, block, 0, st, tm, a);                  \
         return hipGetLastError();                                                                          \
     }
     SAMP_LN_CASE(true, true, true) SAMP_LN_CASE(true, true, false) SAMP_LN_CASE(false, false, true)
