@@ -132,8 +132,16 @@ def measure_peaks(P):
         pk[f"mfma_{name}_constant_operands_T{'FL' if f16 else ''}OP/s"] = round(P.probe_mfma_rate(f16, False) / unit, 1)
         pk[f"mfma_{name}_random_operands_T{'FL' if f16 else ''}OP/s"] = round(P.probe_mfma_rate(f16, True) / unit, 1)
     pk["device_copy_GB/s"] = round(P.probe_copy_rate(1 << 30, 10) / 1e9, 1)
+    # operand feed of the GEMM main loops without arithmetic: the QKV shape at 65536 tokens (all CUs busy for many tiles)
+    # and the FFN1 shape at 2048 tokens (one launch of the headline workload: 384 tiles)
+    big = P.probe_feed_rate(65536, 2304, 768)
+    small = P.probe_feed_rate(2048, 3072, 768)
+    pk["l2_to_lds_feed_TB/s"] = round(big / 1e12, 2)
+    pk["l2_to_lds_feed_bytes_per_ns_per_CU"] = round(big / 1e9 / 256, 1)
+    pk["l2_to_lds_feed_2048_tokens_TB/s"] = round(small / 1e12, 2)
     pk["note"] = ("issue rate of v_mfma_i32_32x32x32_i8 / v_mfma_f32_32x32x16_f16 from registers on all SIMDs; copy = bytes read + "
-                  "written of a 1 GiB device copy")
+                  "written of a 1 GiB device copy; feed = bytes per second that blocks streaming 128 x 128 tile operands "
+                  "(128-byte stages, direct loads into a 3-deep LDS ring, no matrix instruction) pull into LDS")
     return pk
 
 

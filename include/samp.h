@@ -210,10 +210,16 @@ SAMP_API int samp_encoder_profile_read(samp_encoder_t *enc, double *mean_ms, int
  * or FP16 (fp16 != 0) GEMMs are built from, issued from registers by every SIMD with no memory traffic; operands
  * all equal (random_operands = 0) or pseudo-random (the clock under matrix load depends on how many bits toggle).
  * dev_sink: 4 bytes of device memory.  samp_probe_copy_rate: bytes per second (read + written) of a plain device
- * copy of `bytes` bytes, repeated `reps` times.  Both synchronise `stream`.                          */
+ * copy of `bytes` bytes, repeated `reps` times.  samp_probe_feed_rate: bytes per second that the blocks of a
+ * rows x N GEMM with 128 x 128 tiles pull into LDS when they only stream their operand stages (direct loads, 3-deep
+ * ring of 128-byte stages, no matrix instruction): the operand-feed ceiling of the GEMM main loops.  operands: dev
+ * buffer of at least (rows + N) * kbytes bytes (contents irrelevant); rows, N, kbytes multiples of 128.
+ * All three synchronise `stream`.                                                                    */
 SAMP_API int samp_probe_mfma_rate(int32_t fp16, int32_t random_operands, int32_t iters, void *dev_sink, void *stream,
                                   double *ops_per_s);
 SAMP_API int samp_probe_copy_rate(const void *src, void *dst, size_t bytes, int32_t reps, void *stream, double *bytes_per_s);
+SAMP_API int samp_probe_feed_rate(const void *operands, size_t bytes, int32_t rows, int32_t N, int32_t kbytes, int32_t reps,
+                                  void *dev_sink, void *stream, double *bytes_per_s);
 
 /* Thread-local description of the last failure on this thread ("" if none).                       */
 SAMP_API const char *samp_last_error(void);

@@ -411,6 +411,17 @@ def probe_mfma_rate(fp16: bool, random_operands: bool, iters: int = 20000) -> fl
     return out.value
 
 
+def probe_feed_rate(rows: int, N: int, kbytes: int, reps: int = 20) -> float:
+    """samp_probe_feed_rate: bytes per second the blocks of a rows x N GEMM pull into LDS with no arithmetic."""
+    nbytes = (rows + N) * kbytes
+    buf = torch.ones(nbytes, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    out = C.c_double(0.0)
+    _check(lib().samp_probe_feed_rate(_dp(buf), C.c_size_t(nbytes), int(rows), int(N), int(kbytes), int(reps), _dp(sink),
+                                      _stream(), C.byref(out)))
+    return out.value
+
+
 def probe_copy_rate(nbytes: int = 1 << 30, reps: int = 10) -> float:
     """samp_probe_copy_rate: measured bytes per second (read + written) of a device copy."""
     src = torch.ones(nbytes, dtype=torch.uint8, device="cuda")

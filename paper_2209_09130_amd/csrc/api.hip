@@ -921,6 +921,21 @@ int samp_probe_copy_rate(const void *src, void *dst, size_t bytes, int32_t reps,
     return SAMP_OK;
 }
 
+int samp_probe_feed_rate(const void *operands, size_t bytes, int32_t rows, int32_t N, int32_t kbytes, int32_t reps,
+                         void *dev_sink, void *stream, double *bytes_per_s)
+{
+    if (!operands || !dev_sink || !bytes_per_s) return fail(SAMP_ERR_ARG, "NULL pointer");
+    if (rows < 128 || rows % 128 || N < 128 || N % 128 || kbytes < 128 || kbytes % 128 || reps < 1)
+        return fail(SAMP_ERR_SHAPE, "rows, N and kbytes must be positive multiples of 128, reps >= 1");
+    if ((long long)(rows / 128) * (N / 128) > (1 << 20)) return fail(SAMP_ERR_SHAPE, "too many tiles");
+    const size_t a_bytes = (size_t)rows * kbytes, w_bytes = (size_t)N * kbytes;
+    if (bytes < a_bytes + w_bytes) return fail(SAMP_ERR_SPACE, "the operand buffer must hold (rows + N) * kbytes bytes");
+    if (!aligned(operands, 16)) return fail(SAMP_ERR_ARG, "the operand buffer must be 16-byte aligned");
+    HIP_TRY(probe_feed_rate(operands, (const char *)operands + a_bytes, rows, N, kbytes, reps, (int *)dev_sink,
+                            (hipStream_t)stream, bytes_per_s));
+    return SAMP_OK;
+}
+
 int samp_code_histogram(const int8_t *codes, size_t n, uint64_t *hist, void *stream)
 {
     if (!codes || !hist) return fail(SAMP_ERR_ARG, "NULL pointer");

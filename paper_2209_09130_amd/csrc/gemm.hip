@@ -766,7 +766,7 @@ hipError_t launch_longk(const void *A, const void *W, void *out, const Epi &epi,
 }
 
 // Tile configuration per problem shape.  What bounds the main loop on this chip is the rate at which
-// a CU pulls operand stages out of L2 (about 37 bytes per clock per CU, whichever way they are loaded),
+// a CU pulls operand stages out of L2 (20 to 40 bytes per clock per CU, whichever way they are loaded),
 // so small problems want many small tiles (more CUs pulling), large ones the larger tile (less traffic):
 //   0: 128 x 128 tile, 64-byte stages, 4-deep ring  (any K that is a multiple of 64 bytes)
 //   1: 128 x 128 tile, 128-byte stages (whole cache lines per row), 2-deep ring, 2 blocks per CU

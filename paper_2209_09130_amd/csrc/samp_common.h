@@ -230,6 +230,8 @@ hipError_t launch_classify(const __half *hidden, int B, int S, int H, const __ha
 // measured ceilings (probe.hip); both synchronise the stream
 hipError_t probe_mfma_rate(bool f16, bool random_operands, int iters, int *sink, hipStream_t st, double *ops_per_s);
 hipError_t probe_copy_rate(const void *src, void *dst, size_t bytes, int reps, hipStream_t st, double *bytes_per_s);
+hipError_t probe_feed_rate(const void *A, const void *W, int rows, int N, int kbytes, int reps, int *sink, hipStream_t st,
+                           double *bytes_per_s);
 
 // host-side recommendation logic (allocator.hip)
 int allocate_decay_aware(const double *A, const double *L, int n);

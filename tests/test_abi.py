@@ -98,6 +98,8 @@ def test_later_entry_points_reject_bad_arguments_on_the_host(L):
     assert L.samp_set_gemm_config(-1) == 0
     assert L.samp_attention_i8(None, None, 1, 16, 128, 2, C.c_float(1), C.c_float(1), C.c_float(1), C.c_float(1), C.c_float(1),
                                0, None, None, None) == -1
+    assert L.samp_probe_feed_rate(buf, C.c_size_t(256), 100, 128, 128, 1, buf, None, C.byref(C.c_double())) == -2
+    assert L.samp_probe_feed_rate(buf, C.c_size_t(256), 128, 128, 128, 1, buf, None, C.byref(C.c_double())) == -3   # buffer too small
     # a score multiplier s_q s_k / 8 above 256 is refused on the host (the softmax exponential's argument range)
     aligned = (C.c_char * 4096)()
     base = (C.addressof(aligned) + 255) & ~255

@@ -569,3 +569,14 @@ def test_a_sequence_with_an_all_zero_mask_row_is_inert(P):
     assert np.array_equal(out[keep], out3)
     for b in range(4):
         assert not out[b, lens[b]:].any()
+
+
+# ------------------------------------------------------------------ measured ceilings
+def test_peak_probes_return_plausible_rates(P):
+    """The probes behind bench.py's `peaks_measured`: matrix-instruction issue rate, device copy, operand feed.
+    Loose sanity ranges only (an MI355X is far above the lower ends); random operands never beat constant ones by much."""
+    const_i8, rand_i8 = P.probe_mfma_rate(False, False, 4000), P.probe_mfma_rate(False, True, 4000)
+    assert 5e14 < rand_i8 < 6e15 and 5e14 < const_i8 < 6e15 and rand_i8 < 1.1 * const_i8
+    assert 2e14 < P.probe_mfma_rate(True, True, 4000) < 3e15
+    assert 5e11 < P.probe_copy_rate(1 << 28, 3) < 1e13
+    assert 1e12 < P.probe_feed_rate(4096, 768, 768, 5) < 2e14
