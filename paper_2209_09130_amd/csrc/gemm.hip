@@ -54,13 +54,18 @@ struct F16 {
 // n_tile + 8q + 4g + t (g = lane >> 5) of the lane's token row.  tile() turns them into the four
 // packed output groups of the lane (q = 0..3).  The per-channel tables of the block's BN channels
 // are copied into LDS when the block starts (load_tables), so that their memory latency is hidden
-// behind the main loop; tile() reads them from there (tab, indexed by the channel inside the block).
+// behind the main loop.  load_tab() fetches the table entries of one 32-channel tile from there into registers
+// (a Tab) and tile() works from those: the kernels request the Tab of the next tile before they work on the
+// current one, because a wave that waits for every LDS read where it needs it spends more time in the
+// epilogue of a small problem than in its main loop.
 struct EpiRawI32 {                                // test hook: the exact int32 accumulators
     int32_t *out; int N;
     static constexpr int OUT_BYTES = 4;
     static constexpr bool STAGED = false;
     static constexpr int NTAB = 0;
+    struct Tab {};
     __device__ __forceinline__ void load_tables(float *, int, int, int, int) const {}
+    __device__ __forceinline__ Tab load_tab(const float *, int, int, int) const { return {}; }
     __device__ __forceinline__ void direct(int row, int n, int a0, int a1, int a2, int a3) const
     { *reinterpret_cast<v4i *>(out + (size_t)row * N + n) = v4i{a0, a1, a2, a3}; }
 };
@@ -71,6 +76,19 @@ __device__ __forceinline__ void copy_table(float *dst, const float *src, int n0,
         *reinterpret_cast<v4f *>(dst + c) = src ? *reinterpret_cast<const v4f *>(src + n0 + c) : v4f{0.f, 0.f, 0.f, 0.f};
 }
 
+// the multiplier and offset vectors of one 32-channel tile: group q holds channels n_loc + 8q + 4g .. + 3
+template <class Tab> __device__ __forceinline__ Tab load_tab_mb(const float *tab, int bn, int n_loc, int g)
+{
+    Tab t;
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+        const int n = n_loc + 8 * q + 4 * g;
+        t.m[q] = *reinterpret_cast<const v4f *>(tab + n);
+        t.b[q] = *reinterpret_cast<const v4f *>(tab + bn + n);
+    }
+    return t;
+}
+
 struct EpiRequant {                               // code = rne(fmaf(acc, m[n], b[n]))
     const float *m, *b;
     static constexpr int OUT_BYTES = 1;
@@ -79,13 +97,13 @@ struct EpiRequant {                               // code = rne(fmaf(acc, m[n], 
     typedef int pack_t;
     __device__ __forceinline__ void load_tables(float *tab, int n0, int bn, int tid, int nthreads) const
     { copy_table(tab, m, n0, bn, tid, nthreads); copy_table(tab + bn, b, n0, bn, tid, nthreads); }
-    __device__ __forceinline__ void tile(const v16i &acc, const float *tab, int bn, int n_loc, int n_glob, int g, int (&pk)[4]) const
+    struct Tab { v4f m[4], b[4]; };
+    __device__ __forceinline__ Tab load_tab(const float *tab, int bn, int n_loc, int g) const { return load_tab_mb<Tab>(tab, bn, n_loc, g); }
+    __device__ __forceinline__ void tile(const v16i &acc, const Tab &t, const float *tab, int bn, int n_loc, int g, int (&pk)[4]) const
     {
 #pragma unroll
         for (int q = 0; q < 4; q++) {
-            const int n = n_loc + 8 * q + 4 * g;
-            const v4f mm = *reinterpret_cast<const v4f *>(tab + n);
-            const v4f bb = *reinterpret_cast<const v4f *>(tab + bn + n);
+            const v4f mm = t.m[q], bb = t.b[q];
             pk[q] = pack_codes(code_bits(__builtin_fmaf((float)acc[4 * q + 0], mm.x, bb.x)),
                                code_bits(__builtin_fmaf((float)acc[4 * q + 1], mm.y, bb.y)),
                                code_bits(__builtin_fmaf((float)acc[4 * q + 2], mm.z, bb.z)),
@@ -107,14 +125,14 @@ struct EpiGeluQuant {
     typedef int pack_t;
     __device__ __forceinline__ void load_tables(float *tab, int n0, int bn, int tid, int nthreads) const
     { copy_table(tab, m, n0, bn, tid, nthreads); copy_table(tab + bn, bias, n0, bn, tid, nthreads); }
-    __device__ __forceinline__ void tile(const v16i &acc, const float *tab, int bn, int n_loc, int n_glob, int g, int (&pk)[4]) const
+    struct Tab { v4f m[4], b[4]; };
+    __device__ __forceinline__ Tab load_tab(const float *tab, int bn, int n_loc, int g) const { return load_tab_mb<Tab>(tab, bn, n_loc, g); }
+    __device__ __forceinline__ void tile(const v16i &acc, const Tab &tb, const float *tab, int bn, int n_loc, int g, int (&pk)[4]) const
     {
         unsigned long long tie[16], any = 0;
 #pragma unroll
         for (int q = 0; q < 4; q++) {
-            const int n = n_loc + 8 * q + 4 * g;
-            const v4f mm = *reinterpret_cast<const v4f *>(tab + n);
-            const v4f bb = *reinterpret_cast<const v4f *>(tab + bn + n);
+            const v4f mm = tb.m[q], bb = tb.b[q];
             float f[4];
 #pragma unroll
             for (int t = 0; t < 4; t++) {
@@ -169,22 +187,30 @@ struct EpiGeluTable {
         v2i *lut = reinterpret_cast<v2i *>(tab + 2 * bn);
         for (int i = tid; i < bins; i += nthreads) lut[i] = reinterpret_cast<const v2i *>(entries)[i];
     }
-    __device__ __forceinline__ void tile(const v16i &acc, const float *tab, int bn, int n_loc, int n_glob, int g, int (&pk)[4]) const
+    struct Tab { v4f m[4], b[4]; };
+    __device__ __forceinline__ Tab load_tab(const float *tab, int bn, int n_loc, int g) const { return load_tab_mb<Tab>(tab, bn, n_loc, g); }
+    __device__ __forceinline__ void tile(const v16i &acc, const Tab &t, const float *tab, int bn, int n_loc, int g, int (&pk)[4]) const
     {
         const v2i *lut = reinterpret_cast<const v2i *>(tab + 2 * bn);
+        // all sixteen bins first, then the sixteen table reads, then the comparisons: one wait instead of sixteen
+        float y[16];
+        unsigned bin[16];
+        v2i e[16];
+#pragma unroll
+        for (int k = 0; k < 16; k++) {
+            y[k] = __builtin_fmaf((float)acc[k], t.m[k >> 2][k & 3], t.b[k >> 2][k & 3]);
+            bin[k] = __float_as_uint(__builtin_amdgcn_fmed3f(__builtin_fmaf(y[k], rate, offset), 8388608.0f, t_max)) - 0x4B000000u;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int k = 0; k < 16; k++) e[k] = lut[bin[k]];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int q = 0; q < 4; q++) {
-            const int n = n_loc + 8 * q + 4 * g;
-            const v4f mm = *reinterpret_cast<const v4f *>(tab + n);
-            const v4f bb = *reinterpret_cast<const v4f *>(tab + bn + n);
             unsigned c[4];
 #pragma unroll
-            for (int t = 0; t < 4; t++) {
-                const float y = __builtin_fmaf((float)acc[4 * q + t], mm[t], bb[t]);
-                const float pos = __builtin_amdgcn_fmed3f(__builtin_fmaf(y, rate, offset), 8388608.0f, t_max);
-                const v2i e = lut[__float_as_uint(pos) - 0x4B000000u];
-                c[t] = y >= __int_as_float(e.x) ? (unsigned)e.y >> 8 : (unsigned)e.y;
-            }
+            for (int k = 0; k < 4; k++)
+                c[k] = y[4 * q + k] >= __int_as_float(e[4 * q + k].x) ? (unsigned)e[4 * q + k].y >> 8 : (unsigned)e[4 * q + k].y;
             const unsigned lo = __builtin_amdgcn_perm(c[1], c[0], 0x0c0c0400u), hi = __builtin_amdgcn_perm(c[3], c[2], 0x0c0c0400u);
             pk[q] = (int)__builtin_amdgcn_perm(hi, lo, 0x05040100u);
         }
@@ -199,11 +225,19 @@ struct EpiF16 {                                   // fp16(act(acc + bias[n]))
     typedef v2i pack_t;
     __device__ __forceinline__ void load_tables(float *tab, int n0, int bn, int tid, int nthreads) const
     { copy_table(tab, bias, n0, bn, tid, nthreads); }
-    __device__ __forceinline__ void tile(const v16f &acc, const float *tab, int bn, int n_loc, int n_glob, int g, v2i (&pk)[4]) const
+    struct Tab { v4f b[4]; };
+    __device__ __forceinline__ Tab load_tab(const float *tab, int bn, int n_loc, int g) const
+    {
+        Tab t;
+#pragma unroll
+        for (int q = 0; q < 4; q++) t.b[q] = *reinterpret_cast<const v4f *>(tab + n_loc + 8 * q + 4 * g);
+        return t;
+    }
+    __device__ __forceinline__ void tile(const v16f &acc, const Tab &t, const float *tab, int bn, int n_loc, int g, v2i (&pk)[4]) const
     {
 #pragma unroll
         for (int q = 0; q < 4; q++) {
-            const v4f bb = *reinterpret_cast<const v4f *>(tab + n_loc + 8 * q + 4 * g);
+            const v4f bb = t.b[q];
             float a0 = acc[4 * q] + bb.x, a1 = acc[4 * q + 1] + bb.y, a2 = acc[4 * q + 2] + bb.z, a3 = acc[4 * q + 3] + bb.w;
             if (gelu) { a0 = gelu_fast(a0); a1 = gelu_fast(a1); a2 = gelu_fast(a2); a3 = gelu_fast(a3); }
             const v4h h = {to_half(a0), to_half(a1), to_half(a2), to_half(a3)};
@@ -325,6 +359,9 @@ void gemm_nt_kernel(const char *__restrict__ A, const char *__restrict__ W, char
                 for (int j = 0; j < TM; j++) acc[i][j] = T::mma(fw[i], fa[j], acc[i][j]);
         }
     }
+    typename Epi::Tab tabs[TN];                                   // the epilogue's table entries arrive while the waves gather
+#pragma unroll
+    for (int io = 0; io < TN; io++) tabs[io] = epi.load_tab(tab, BN, wn + io * 32, g);
     wait_vm_and_barrier<0>();                                     // the ring is idle from here on
 
     if constexpr (!Epi::STAGED) {
@@ -353,7 +390,7 @@ void gemm_nt_kernel(const char *__restrict__ A, const char *__restrict__ W, char
                 typename Epi::pack_t pk[4];
                 const int lrow = wm + j * 32 + r;
                 const int nl = wn + io * 32;
-                epi.tile(acc[io][j], tab, BN, nl, n0 + nl, g, pk);
+                epi.tile(acc[io][j], tabs[io], tab, BN, nl, g, pk);
 #pragma unroll
                 for (int q = 0; q < 4; q++)
                     *reinterpret_cast<typename Epi::pack_t *>(lds + lrow * STRIDE + (nl + 8 * q + 4 * g) * OB) = pk[q];
@@ -566,6 +603,7 @@ void gemm_nt_big_kernel(const char *__restrict__ A, const char *__restrict__ W, 
         for (int ks = 0; ks < KS; ks++) step(ks, false, true, std::integral_constant<int, 0>());
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) step(ks, false, false, std::integral_constant<int, 0>());
+    typename Epi::Tab first_tab = epi.load_tab(tab, BN, wn, g);    // arrives while the waves gather
     wait_vm_and_barrier<0>();                                     // the ring is idle from here on
 
     if constexpr (!Epi::STAGED) {
@@ -593,25 +631,34 @@ void gemm_nt_big_kernel(const char *__restrict__ A, const char *__restrict__ W, 
         for (int j = 0; j < TM; j++) {
             char *slab = lds + (j & 1) * 64 * STRIDE;             // alternate slabs: one barrier per pass
             const int lrow = (wave >> 1) * 32 + r;
+            typename Epi::Tab cur = j == 0 ? first_tab : epi.load_tab(tab, BN, wn, g);
 #pragma unroll
             for (int io = 0; io < TN; io++) {
                 typename Epi::pack_t pk[4];
                 const int nl = wn + io * 32;
-                epi.tile(acc[io][j], tab, BN, nl, n0 + nl, g, pk);
+                typename Epi::Tab nxt;                            // the next tile's entries travel while this tile is worked on
+                if (io + 1 < TN) nxt = epi.load_tab(tab, BN, nl + 32, g);
+                __builtin_amdgcn_sched_barrier(0);
+                epi.tile(acc[io][j], cur, tab, BN, nl, g, pk);
 #pragma unroll
                 for (int q = 0; q < 4; q++)
                     *reinterpret_cast<typename Epi::pack_t *>(slab + lrow * STRIDE + (nl + 8 * q + 4 * g) * OB) = pk[q];
+                if (io + 1 < TN) cur = nxt;
             }
             __syncthreads();
+            constexpr int PASSES = 64 * CHUNKS / NT;
+            v4i v[PASSES];                                        // all reads of the pass, then the stores
 #pragma unroll
-            for (int p = 0; p < 64 * CHUNKS / NT; p++) {
+            for (int p = 0; p < PASSES; p++) {
+                const int idx = p * NT + tid;
+                v[p] = *reinterpret_cast<const v4i *>(slab + (idx / CHUNKS) * STRIDE + (idx % CHUNKS) * 16);
+            }
+#pragma unroll
+            for (int p = 0; p < PASSES; p++) {
                 const int idx = p * NT + tid;
                 const int srow = idx / CHUNKS, ochunk = idx % CHUNKS;
                 const int grow = m0 + (srow >> 5) * 32 * TM + j * 32 + (srow & 31);
-                if (grow < M) {
-                    const v4i v = *reinterpret_cast<const v4i *>(slab + srow * STRIDE + ochunk * 16);
-                    *reinterpret_cast<v4i *>(out + ((size_t)grow * N + n0) * OB + ochunk * 16) = v;
-                }
+                if (grow < M) *reinterpret_cast<v4i *>(out + ((size_t)grow * N + n0) * OB + ochunk * 16) = v[p];
             }
         }
     }
@@ -729,6 +776,7 @@ void gemm_nt_longk_kernel(const char *__restrict__ A, const char *__restrict__ W
         for (int d = 0; d < DEPTH; d++) stage(kt + d, d, true);
 #pragma unroll
     for (int d = 0; d < DEPTH; d++) stage(kt + d, d, false);
+    const typename Epi::Tab tb = epi.load_tab(tab, BN, wn, g);     // arrives while the waves gather
     __syncthreads();                                              // both buffers are idle from here on
 
     constexpr int OB = Epi::OUT_BYTES;
@@ -736,7 +784,7 @@ void gemm_nt_longk_kernel(const char *__restrict__ A, const char *__restrict__ W
     static_assert(BM * STRIDE <= 2 * STAGE_BYTES, "staging tile does not fit");
     {
         typename Epi::pack_t pk[4];
-        epi.tile(acc, tab, BN, wn, n0 + wn, g, pk);
+        epi.tile(acc, tb, tab, BN, wn, g, pk);
 #pragma unroll
         for (int q = 0; q < 4; q++)
             *reinterpret_cast<typename Epi::pack_t *>(lds + (wm + r) * STRIDE + (wn + 8 * q + 4 * g) * OB) = pk[q];
