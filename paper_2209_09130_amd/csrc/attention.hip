@@ -289,8 +289,11 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const __half *__rest
                                                             int max_len, int H, float scale, __half *__restrict__ ctx,
                                                             float *__restrict__ p_absmax)
 {
-    __shared__ __attribute__((aligned(16))) char vt[4][NT][64 * VT_STRIDE_F16];
-    __shared__ __attribute__((aligned(16))) float so[4][QB][64];
+    // one slab per wave, as in the INT8 kernel: first its V^T tiles, then its partial context for the other waves
+    constexpr int VT_TILE = 64 * VT_STRIDE_F16, SO_BYTES = QB * 64 * 4;
+    constexpr int SLAB = NT * VT_TILE > SO_BYTES ? NT * VT_TILE : SO_BYTES;
+    __shared__ __attribute__((aligned(16))) char slab[4][SLAB];
+    auto so = [&](int wave) { return reinterpret_cast<float(*)[64]>(slab[wave]); };
     __shared__ float smax[4][QB];
     __shared__ float ssum[4][QB];
 
@@ -334,7 +337,7 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const __half *__rest
                 const v8h v = *reinterpret_cast<const v8h *>(vp + (unsigned)min(j0 + key, n - 1) * ld + c0);
 #pragma unroll
                 for (int e = 0; e < 8; e++)
-                    *reinterpret_cast<_Float16 *>(&vt[w][i][(c0 + e) * VT_STRIDE_F16 + key * 2]) = v[e];
+                    *reinterpret_cast<_Float16 *>(&slab[w][i * VT_TILE + (c0 + e) * VT_STRIDE_F16 + key * 2]) = v[e];
             }
 #pragma unroll
             for (int e = 0; e < 16; e++) {
@@ -384,7 +387,7 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const __half *__rest
                 for (int e = 0; e < 8; e++) pf[e] = to_half(sc[i][8 * hf + e] * rS);
 #pragma unroll
                 for (int cb = 0; cb < 2; cb++) {
-                    const char *rowp = &vt[w][i][(cb * 32 + r) * VT_STRIDE_F16];
+                    const char *rowp = &slab[w][i * VT_TILE + (cb * 32 + r) * VT_STRIDE_F16];
                     const v4h lo = *reinterpret_cast<const v4h *>(rowp + (16 * hf + 4 * g) * 2);
                     const v4h hi = *reinterpret_cast<const v4h *>(rowp + (16 * hf + 8 + 4 * g) * 2);
                     const v8h vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
@@ -396,7 +399,7 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const __half *__rest
 #pragma unroll
     for (int cb = 0; cb < 2; cb++)
 #pragma unroll
-        for (int e = 0; e < 16; e++) so[w][8 * (e >> 2) + 4 * g + (e & 3)][cb * 32 + r] = o[cb][e];
+        for (int e = 0; e < 16; e++) so(w)[8 * (e >> 2) + 4 * g + (e & 3)][cb * 32 + r] = o[cb][e];
     __syncthreads();
 
     const int query = tid >> 3, c0 = (tid & 7) * 8;
@@ -404,7 +407,7 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const __half *__rest
         v8h outv;
 #pragma unroll
         for (int e = 0; e < 8; e++)
-            outv[e] = to_half(((so[0][query][c0 + e] + so[1][query][c0 + e]) + so[2][query][c0 + e]) + so[3][query][c0 + e]);
+            outv[e] = to_half(((so(0)[query][c0 + e] + so(1)[query][c0 + e]) + so(2)[query][c0 + e]) + so(3)[query][c0 + e]);
         *reinterpret_cast<v8h *>(ctx + (size_t)(sq.t0 + q0 + query) * H + head * 64 + c0) = outv;
     }
 }
