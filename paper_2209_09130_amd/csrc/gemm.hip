@@ -845,6 +845,9 @@ hipError_t launch(const void *A, const void *W, void *out, const Epi &epi, Rows 
             // in the 64 x 128 configuration costs more than it saves: its table in LDS takes the third resident block
             // away), another -1.4 % with QKV; the FP16 forward gains 2 %
             if (N % 192 == 0 && N >= 2304 && rows.host_rows >= 1024) cfg = 6;
+            // widths that 192 does not divide (FFN1 of BERT-large, 4096): 128 x 256 tiles (-3.5 % on that forward
+            // at 2 x 4096 tokens against 128 x 128; 256 x 128 -0.5 %, 64 x 128 +5.5 %)
+            else if (N % 256 == 0 && N >= 2304 && rows.host_rows >= 1024) cfg = 4;
             // many tokens (INT8): wave tiles of 64 x 128 halve the LDS operand traffic per MFMA, two such blocks
             // per CU overlap one's epilogue with the other's main loop; long operand rows amortise the epilogue of a
             // 256 x 256 tile by themselves
