@@ -839,7 +839,9 @@ hipError_t launch(const void *A, const void *W, void *out, const Epi &epi, Rows 
         if (kbytes % 128) cfg = 0;
         else {
             const long tiles = (long)(N / 128) * ((rows.host_rows + 127) / 128);
-            cfg = tiles <= 640 ? 2 : 1;
+            // fewer 128 x 128 tiles than CUs: the smaller tiles of configuration 2 (BERT-large's 1024-wide GEMMs at
+            // 4096 tokens, 256 tiles, measured -4.4 % on that forward with 128 x 128 against 64 x 128)
+            cfg = tiles < 256 ? 2 : 1;
             // wide GEMMs (QKV, FFN1) from about a thousand tokens: 128 x 192 tiles, 64 x 96 per wave, two blocks
             // per CU.  Measured in the BERT-base forward at 2 x 2048 tokens: -5 % with FFN1 (whose table-lookup epilogue
             // in the 64 x 128 configuration costs more than it saves: its table in LDS takes the third resident block
