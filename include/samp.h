@@ -169,10 +169,10 @@ SAMP_API int samp_encoder_forward_ids(samp_encoder_t *enc, const samp_embedding_
                                       const int32_t *segment_ids, const int32_t *mask, int32_t B, int32_t S, void *out,
                                       void *workspace, size_t workspace_bytes, void *stream);
 
-/* Sequences are independent (all scales are static, Appendix B), so a forward may cut a small batch
+/* Sequences are independent (all scales are static, Appendix B), so a forward may cut a batch
  * into up to 4 groups of sequences that run concurrently on streams owned by the encoder, forked
  * from and joined back into the caller's stream; results do not depend on the split.  groups = 0
- * (default) chooses by size, 1 disables the split, 2..4 force it.                                  */
+ * (default) chooses by size (two groups from 2560 token rows on), 1 disables the split, 2..4 force it. */
 SAMP_API int samp_encoder_set_groups(samp_encoder_t *enc, int32_t groups);
 
 /* A forward is a few hundred short kernels, so by default the library records them once per distinct
