@@ -58,24 +58,26 @@ def measured_traffic(workload: str, mode: str, kernel: str, tokens_per_launch: i
     return None
 
 
-def algorithmic_work(w, modes, lens):
+def algorithmic_work(w, modes, lens, fused=False):
     """Per kernel class, summed over one forward: (ops, bytes) that the method itself needs - operands read once,
-    results written once, weights once per layer."""
+    results written once, weights once per layer.  fused: INT8 attention blocks with symmetric softmax codes run the QKV
+    GEMM and the attention as one kernel (class qkv_attention: the q, k, v codes are not traffic any more)."""
     T = int(lens.sum())
     H, F = w.hidden, w.ffn
     att = float((lens.astype("float64") ** 2).sum()) * 4 * H
-    work = {k: [0.0, 0.0] for k in ("qkv", "attention", "attn_out", "ln1", "ffn1", "ffn2", "ln2")}
+    work = {k: [0.0, 0.0] for k in ("qkv", "attention", "qkv_attention", "attn_out", "ln1", "ffn1", "ffn2", "ln2")}
     for i, m in enumerate(modes):
         em = 1 if m & 1 else 2
         ef = 1 if m & 2 else 2
         en = 2 if i + 1 == len(modes) else (1 if modes[i + 1] & 1 else 2)
-        for k, ops, byts in (("qkv", 2.0 * T * 3 * H * H, (T * 4 * H + 3 * H * H) * em),
-                             ("attention", att, T * 4 * H * em),
-                             ("attn_out", 2.0 * T * H * H, (T * 2 * H + H * H) * em),
-                             ("ln1", 10.0 * T * H, T * H * (2 * em + ef)),
-                             ("ffn1", 2.0 * T * H * F, (T * (H + F) + H * F) * ef),
-                             ("ffn2", 2.0 * T * H * F, (T * (H + F) + H * F) * ef),
-                             ("ln2", 10.0 * T * H, T * H * (2 * ef + en))):
+        one_kernel = fused and (m & 1) and not (m & ~3)
+        front = ((("qkv_attention", 2.0 * T * 3 * H * H + att, T * 2 * H + 3 * H * H),) if one_kernel else
+                 (("qkv", 2.0 * T * 3 * H * H, (T * 4 * H + 3 * H * H) * em), ("attention", att, T * 4 * H * em)))
+        for k, ops, byts in front + (("attn_out", 2.0 * T * H * H, (T * 2 * H + H * H) * em),
+                                     ("ln1", 10.0 * T * H, T * H * (2 * em + ef)),
+                                     ("ffn1", 2.0 * T * H * F, (T * (H + F) + H * F) * ef),
+                                     ("ffn2", 2.0 * T * H * F, (T * (H + F) + H * F) * ef),
+                                     ("ln2", 10.0 * T * H, T * H * (2 * ef + en))):
             work[k][0] += ops
             work[k][1] += byts
     work["entry"] = [0.0, T * H * (2 + (1 if modes[0] & 1 else 2))]
@@ -97,27 +99,29 @@ def timed(enc, hid, mask, out, steps, repeats, torch):
 
 def kernel_table(P, enc, hid, mask, out, w0, modes, lens, steps, torch):
     """Every kernel class, one pass each, HIP events on the dispatches (groups run one after another meanwhile)."""
-    work = algorithmic_work(w0, modes, lens)
     all_i8 = all((m & 3) == P.FULL_INT8 for m in modes)
     all_f16 = all(m == P.FP16 for m in modes)
-    kernels = {}
-    for kname, which in (("entry", P.PROF_ENTRY), ("qkv", P.PROF_QKV), ("attention", P.PROF_ATTN),
+    measured = {}
+    n_pass = min(steps, 20)
+    for kname, which in (("entry", P.PROF_ENTRY), ("qkv", P.PROF_QKV), ("attention", P.PROF_ATTN), ("qkv_attention", P.PROF_QKV_ATTN),
                          ("attn_out", P.PROF_ATTN_OUT), ("ln1", P.PROF_LN1), ("ffn1", P.PROF_FFN1),
                          ("ffn2", P.PROF_FFN2), ("ln2", P.PROF_LN2)):
         enc.profile(which)
-        n_pass = min(steps, 20)
         for _ in range(n_pass):
             enc.forward(hid, mask, out)
         torch.cuda.synchronize()
-        kms, launches = enc.profile_read()
+        measured[kname] = enc.profile_read()
         enc.profile(P.PROF_OFF)
+    work = algorithmic_work(w0, modes, lens, fused=measured["qkv_attention"][1] > 0)
+    kernels = {}
+    for kname, (kms, launches) in measured.items():
         if launches == 0:
             continue
         tot_s = kms * 1e-3 * launches / n_pass          # summed duration of the class in one forward
         ops_f, bytes_f = work[kname]
         ent = {"mean_launch_us": round(kms * 1e3, 2), "launches_per_step": launches / n_pass,
                "GB/s": round(bytes_f / tot_s / 1e9, 1), "frac_hbm": round(bytes_f / tot_s / 1e9 / HBM_PEAK_GBS, 4)}
-        if kname in ("qkv", "attn_out", "ffn1", "ffn2") and (all_i8 or all_f16):
+        if kname in ("qkv", "qkv_attention", "attn_out", "ffn1", "ffn2") and (all_i8 or all_f16):
             peak = INT8_PEAK_TOPS if all_i8 else FP16_PEAK_TFLOPS
             ent["TOP/s" if all_i8 else "TFLOP/s"] = round(ops_f / tot_s / 1e12, 1)
             ent["frac_mfma"] = round(ops_f / tot_s / 1e12 / peak, 4)

@@ -175,6 +175,13 @@ SAMP_API int samp_encoder_forward_ids(samp_encoder_t *enc, const samp_embedding_
  * (default) chooses by size (two groups from 2560 token rows on), 1 disables the split, 2..4 force it. */
 SAMP_API int samp_encoder_set_groups(samp_encoder_t *enc, int32_t groups);
 
+/* Section 3.2 hands the QKV GEMM's requantised int8 output straight to the attention; for sequences of at
+ * most 128 tokens one kernel can do both per (sequence, head), so that the q, k, v codes never reach memory and
+ * a layer has one launch less (symmetric int8 softmax codes only).  mode 0 (default): used where it measured
+ * faster (at least 128 (sequence, head) pairs per launch); 1: never; 2: whenever the shape allows.  The
+ * context codes are the same bytes either way.                                                            */
+SAMP_API int samp_encoder_set_qkv_fusion(samp_encoder_t *enc, int32_t mode);
+
 /* A forward is a few hundred short kernels, so by default the library records them once per distinct
  * argument set (pointers, B, S) into a HIP graph -- on the second call with those arguments, on a
  * stream of its own -- and replays that graph on the caller's stream afterwards.  enabled = 0 keeps
@@ -201,7 +208,8 @@ SAMP_API int samp_encoder_destroy(samp_encoder_t *enc);
  * samp_encoder_profile_read synchronises the events recorded so far, returns their mean duration
  * in milliseconds and their number, and clears them.                                             */
 enum { SAMP_PROF_OFF = 0, SAMP_PROF_QKV = 1, SAMP_PROF_ATTN = 2, SAMP_PROF_ATTN_OUT = 3, SAMP_PROF_LN1 = 4,
-       SAMP_PROF_FFN1 = 5, SAMP_PROF_FFN2 = 6, SAMP_PROF_LN2 = 7, SAMP_PROF_ENTRY = 8 };
+       SAMP_PROF_FFN1 = 5, SAMP_PROF_FFN2 = 6, SAMP_PROF_LN2 = 7, SAMP_PROF_ENTRY = 8,
+       SAMP_PROF_QKV_ATTN = 9 /* the QKV GEMM and attention in one kernel, where a forward uses it */ };
 SAMP_API int samp_encoder_profile(samp_encoder_t *enc, int which);
 SAMP_API int samp_encoder_profile_read(samp_encoder_t *enc, double *mean_ms, int64_t *launches);
 
@@ -322,6 +330,14 @@ SAMP_API int samp_gemm_f16(const uint16_t *A, const uint16_t *W, const float *bi
 SAMP_API int samp_attention_i8(const int8_t *qkv, const int32_t *cu_seqlens, int32_t B, int32_t max_len, int32_t hidden,
                                int32_t heads, float s_q, float s_k, float s_v, float s_p, float s_ctx, int32_t p_kind,
                                int8_t *ctx, uint64_t *p_hist, void *stream);
+/* QKV GEMM, its requantisation and the INT8 attention (p_kind 0) of sequences of at most 128 tokens in one kernel
+ * (Section 3.2: the same two steps, the q, k, v codes staying on chip): x dev int8 [T,hidden] packed rows,
+ * w_qkv dev int8 [3 hidden, hidden] (rows [0,H) Q, [H,2H) K, [2H,3H) V), m and b dev float [3 hidden] as in
+ * samp_gemm_i8_requant (b NULL = zeros); cu_seqlens, B, max_len <= 128, scales and ctx as in samp_attention_i8.
+ * ctx equals samp_gemm_i8_requant followed by samp_attention_i8 byte for byte.                              */
+SAMP_API int samp_qkv_attention_i8(const int8_t *x, const int8_t *w_qkv, const float *m, const float *b,
+                                   const int32_t *cu_seqlens, int32_t B, int32_t max_len, int32_t hidden, int32_t heads,
+                                   float s_q, float s_k, float s_v, float s_p, float s_ctx, int8_t *ctx, void *stream);
 SAMP_API int samp_attention_f16(const uint16_t *qkv, const int32_t *cu_seqlens, int32_t B, int32_t max_len, int32_t hidden,
                                 int32_t heads, uint16_t *ctx, void *stream);
 

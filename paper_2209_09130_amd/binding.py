@@ -11,7 +11,7 @@ import torch
 FP16, MHA_INT8, FFN_INT8, FULL_INT8 = 0, 1, 2, 3
 P_UNSIGNED = 4
 P_FP16 = 8
-(PROF_OFF, PROF_QKV, PROF_ATTN, PROF_ATTN_OUT, PROF_LN1, PROF_FFN1, PROF_FFN2, PROF_LN2, PROF_ENTRY) = range(9)
+(PROF_OFF, PROF_QKV, PROF_ATTN, PROF_ATTN_OUT, PROF_LN1, PROF_FFN1, PROF_FFN2, PROF_LN2, PROF_ENTRY, PROF_QKV_ATTN) = range(10)
 SCALE_FIELDS = ("x", "q", "k", "v", "p", "ctx", "attn_out", "ffn_in", "ffn_mid", "ffn_out")
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -210,6 +210,10 @@ class Encoder:
     def set_groups(self, groups: int):
         _check(lib().samp_encoder_set_groups(self._h, int(groups)))
 
+    def set_qkv_fusion(self, mode: int):
+        """0: QKV GEMM + attention in one kernel where it is faster, 1: never, 2: whenever the shape allows."""
+        _check(lib().samp_encoder_set_qkv_fusion(self._h, int(mode)))
+
     def set_graph(self, enabled: bool):
         _check(lib().samp_encoder_set_graph(self._h, int(bool(enabled))))
 
@@ -302,6 +306,16 @@ def attention_i8(qkv, cu, max_len: int, heads: int, s_q, s_k, s_v, s_p, s_ctx, p
     _check(lib().samp_attention_i8(_dp(qkv), _dp(cu), B, max_len, H, heads, _f(s_q), _f(s_k), _f(s_v),
                                    _f(s_p), _f(s_ctx), 2 if p_fp16 else int(bool(p_unsigned)), _dp(ctx), _dp(hist), _stream()))
     return (ctx, hist) if want_hist else ctx
+
+
+def qkv_attention_i8(x, w_qkv, m, b, cu, max_len: int, heads: int, s_q, s_k, s_v, s_p, s_ctx):
+    """samp_qkv_attention_i8: ctx [T, H] int8 from packed int8 rows x [T, H] and the int8 QKV weights [3H, H]."""
+    T, H = x.shape
+    B = _batch_of(cu, T, max_len)
+    ctx = torch.zeros((T, H), dtype=torch.int8, device=x.device)
+    _check(lib().samp_qkv_attention_i8(_dp(x), _dp(w_qkv), _dp(m), _dp(b), _dp(cu), B, max_len, H, heads, _f(s_q), _f(s_k),
+                                       _f(s_v), _f(s_p), _f(s_ctx), _dp(ctx), _stream()))
+    return ctx
 
 
 def classify(hidden: torch.Tensor, w_pool, b_pool, w_cls, b_cls) -> torch.Tensor:

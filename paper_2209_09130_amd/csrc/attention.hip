@@ -16,6 +16,7 @@
 // Every floating-point value that decides an int8 code follows one fixed sequence of binary32
 // operations; exp and the row sum are evaluated in binary64 and rounded once.
 #include "samp_common.h"
+#include "mfma_tile.h"
 #include <hip/hip_ext.h>
 
 namespace samp {
@@ -280,6 +281,289 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
         *reinterpret_cast<v2i *>(ctx + (size_t)(sq.t0 + q0 + query) * H + head * 64 + c0) = pk;
     }
     if (HIST && hist[tid]) atomicAdd(&p_hist[tid], (unsigned long long)hist[tid]);   // after the barrier above
+}
+
+// ---- QKV GEMM and attention of one (sequence, head) in one kernel ------------------------------------------
+// For sequences of at most 128 tokens the QKV tile of one (sequence, head) -- the sequence's token rows times the
+// head's 64 query, 64 key and 64 value channels -- is exactly one 128 x 192 block tile of the large-tile GEMM, and it
+// is all that head's attention needs (Section 3.2: the QKV GEMM's requantised int8 output is the attention's only
+// input).  The block therefore runs that GEMM's main loop (three-deep ring of 64-byte stages, direct global->LDS
+// loads, wave tiles of 64 x 96), requantises q, k, v into LDS where the ring was, and goes on as the attention
+// kernel above does, one wave per 32 queries over all keys: the q, k, v codes never reach memory and one launch per
+// layer is gone.  Every value is produced by the same operations in the same order as in the two separate kernels
+// (the row sums are added tile by tile as the four waves' partial sums are there), so the context codes are the same
+// bytes.
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void qkv_attention_i8_kernel(const char *__restrict__ X, const char *__restrict__ W, const float *__restrict__ m_tab,
+                             const float *__restrict__ b_tab, const int *__restrict__ cu, int max_len, int H, float m_sc,
+                             float inv_sp, float m_ctx, int8_t *__restrict__ ctx)
+{
+    constexpr int TM = 2, TN = 3, BKB = 64, NSTAGE = 3, NWAVES = 4, CH = 4, RPI = 16, KS = 2;
+    constexpr int BM = 128, BN = 192;
+    constexpr int A_BYTES = BM * BKB, STAGE_BYTES = (BM + BN) * BKB, RING_BYTES = NSTAGE * STAGE_BYTES;
+    constexpr int NLD = (BM + BN) / RPI / NWAVES;                 // 1 KiB pieces per wave and stage
+    constexpr int QK_STRIDE = 80, VT_STRIDE = 132;                // bytes per token row of q / k, per channel row of V^T
+    constexpr int Q_OFF = 0, K_OFF = BM * QK_STRIDE, VT_OFF = 2 * BM * QK_STRIDE;
+    static_assert(VT_OFF + 64 * VT_STRIDE <= RING_BYTES, "q, k and V^T take the place of the ring");
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    float *tab = reinterpret_cast<float *>(lds + RING_BYTES);     // multipliers, then offsets, of the 192 columns
+
+    const int heads = H >> 6;
+    const int item = xcd_contiguous(blockIdx.x, gridDim.x);       // sequences outermost, as in the attention kernel
+    const int seq = item / heads, head = item % heads;
+    const SeqInfo sq = seq_info(cu, seq, max_len);
+    const int n = sq.n;
+    if (n <= 0) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
+    const int wm = (wave >> 1) * 32 * TM, wn = (wave & 1) * 32 * TN;
+    const int r = lane & 31, g = lane >> 5;
+    const int Kbytes = H;
+
+    // operand rows: the sequence's tokens (rows past its end repeat the last one), and the head's 64 rows of each of
+    // the query, key and value thirds of the weight matrix
+    const char *src[NLD];
+#pragma unroll
+    for (int j = 0; j < NLD; j++) {
+        const int srow = RPI * (wave + NWAVES * j) + lane / CH;
+        if (srow < BM) {
+            const int am = min(srow, n - 1);
+            src[j] = X + (size_t)(sq.t0 + am) * Kbytes + (((lane % CH) ^ swz<BKB>(srow)) << 4);
+        } else {
+            const int row = srow - BM;
+            src[j] = W + (size_t)((row >> 6) * H + head * 64 + (row & 63)) * Kbytes + (((lane % CH) ^ swz<BKB>(row)) << 4);
+        }
+    }
+    const int KT = Kbytes / BKB;
+    int fill_slot = 0, fill_kt = 0;
+    auto issue = [&]() {
+        char *st = lds + fill_slot * STAGE_BYTES;
+#pragma unroll
+        for (int j = 0; j < NLD; j++)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[j] + (size_t)fill_kt * BKB),
+                                             (__attribute__((address_space(3))) void *)(st + (wave + NWAVES * j) * 1024), 16, 0, 0);
+        fill_kt++;
+        fill_slot = fill_slot + 1 == NSTAGE ? 0 : fill_slot + 1;
+    };
+    const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
+    unsigned offa[KS], offw[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) {
+        offa[ks] = lds_base + (wm + r) * BKB + (((2 * ks + g) ^ swz<BKB>(wm + r)) << 4);
+        offw[ks] = lds_base + A_BYTES + (wn + r) * BKB + (((2 * ks + g) ^ swz<BKB>(wn + r)) << 4);
+    }
+    auto fetch = [&](int slot_bytes, int ks, v4i (&fa)[TM], v4i (&fw)[TN]) {
+        lds_read_frags<32 * BKB>(offa[ks] + slot_bytes, fa, std::make_integer_sequence<int, TM>());
+        lds_read_frags<32 * BKB>(offw[ks] + slot_bytes, fw, std::make_integer_sequence<int, TN>());
+    };
+    auto ready = [&](v4i (&fa)[TM], v4i (&fw)[TN]) {
+        tie(fa, std::make_integer_sequence<int, TM>());
+        tie(fw, std::make_integer_sequence<int, TN>());
+    };
+
+#pragma unroll
+    for (int s = 0; s < NSTAGE - 1; s++)
+        if (s < KT) issue();
+    for (int c = tid; c < BN; c += 256) {
+        const int col = (c >> 6) * H + head * 64 + (c & 63);
+        tab[c] = m_tab[col];
+        tab[BN + c] = b_tab ? b_tab[col] : 0.0f;
+    }
+
+    v16i acc[TN][TM];
+#pragma unroll
+    for (int i = 0; i < TN; i++)
+#pragma unroll
+        for (int j = 0; j < TM; j++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) acc[i][j][e] = 0;
+    const bool rows_live[TM] = {wm < n, wm + 32 < n};             // wave-uniform: token tiles past the sequence's end are not multiplied
+    auto multiply = [&](const v4i (&fa)[TM], const v4i (&fw)[TN]) {
+#pragma unroll
+        for (int j = 0; j < TM; j++)
+            if (rows_live[j]) {
+#pragma unroll
+                for (int i = 0; i < TN; i++) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[i], fa[j], acc[i][j], 0, 0, 0);
+            }
+    };
+
+    // the main loop of the large-tile GEMM kernel (same ring, same waits)
+    v4i fa[2][TM], fw[2][TN];
+    if (KT > NSTAGE - 2) wait_vm_and_barrier<(NSTAGE - 2) * NLD>(); else wait_vm_and_barrier<0>();
+    fetch(0, 0, fa[0], fw[0]);
+    int slot_bytes = 0;
+    auto next_slot = [&]() { slot_bytes = slot_bytes + STAGE_BYTES == RING_BYTES ? 0 : slot_bytes + STAGE_BYTES; };
+    auto step = [&](int ks, bool refill, bool more, auto vm_tag) {
+        constexpr int VM = decltype(vm_tag)::value;
+        if (ks + 1 < KS) {
+            fetch(slot_bytes, ks + 1, fa[(ks + 1) & 1], fw[(ks + 1) & 1]);
+            wait_lds_reads<TM + TN>();
+        } else if (more) {
+            wait_vm_and_barrier<VM>();
+            next_slot();
+            fetch(slot_bytes, 0, fa[0], fw[0]);
+        } else {
+            wait_lds_reads<0>();
+        }
+        ready(fa[ks & 1], fw[ks & 1]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (refill && ks == 0) issue();
+        multiply(fa[ks & 1], fw[ks & 1]);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    int kt = 0;
+    for (; kt + NSTAGE - 1 < KT; kt++)
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++) step(ks, true, true, std::integral_constant<int, (NSTAGE - 2) * NLD>());
+    for (; kt + 1 < KT; kt++)
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++) step(ks, false, true, std::integral_constant<int, 0>());
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) step(ks, false, false, std::integral_constant<int, 0>());
+    wait_vm_and_barrier<0>();                                     // the ring is idle from here on
+
+    // requantise into LDS: q and k as token rows of 64 codes, v transposed (a channel's codes of all keys in a row).
+    // A lane holds one token and groups of four consecutive channels.
+#pragma unroll
+    for (int io = 0; io < TN; io++) {
+        const int nl = wn + io * 32;                              // first of the tile's 32 columns among the block's 192 (scalar)
+        const int part = nl >> 6, c0 = nl & 63;                   // 0 query, 1 key, 2 value
+        v4f mm[4], bb[4];
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+            mm[q] = *reinterpret_cast<const v4f *>(tab + nl + 8 * q + 4 * g);
+            bb[q] = *reinterpret_cast<const v4f *>(tab + BN + nl + 8 * q + 4 * g);
+        }
+#pragma unroll
+        for (int j = 0; j < TM; j++) {
+            const int row = wm + 32 * j + r;
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                const v16i &a = acc[io][j];
+                const int pk = pack_codes(code_bits(__builtin_fmaf((float)a[4 * q + 0], mm[q].x, bb[q].x)),
+                                          code_bits(__builtin_fmaf((float)a[4 * q + 1], mm[q].y, bb[q].y)),
+                                          code_bits(__builtin_fmaf((float)a[4 * q + 2], mm[q].z, bb[q].z)),
+                                          code_bits(__builtin_fmaf((float)a[4 * q + 3], mm[q].w, bb[q].w)));
+                const int c = c0 + 8 * q + 4 * g;
+                if (part < 2) {
+                    *reinterpret_cast<int *>(lds + (part ? K_OFF : Q_OFF) + row * QK_STRIDE + c) = pk;
+                } else {
+#pragma unroll
+                    for (int t = 0; t < 4; t++) lds[VT_OFF + (c + t) * VT_STRIDE + row] = (char)(pk >> (8 * t));
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    // attention: this wave's 32 queries against all keys
+    const int q0 = wave * QB;
+    if (q0 >= n) return;                                          // no barrier below
+    v4i qf[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ks++) qf[ks] = *reinterpret_cast<const v4i *>(lds + Q_OFF + (q0 + r) * QK_STRIDE + ks * 32 + g * 16);
+    float sc[4][16];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const int j0 = 32 * i;
+        if (j0 < n) {                                            // wave-uniform
+            v4i kf[2];
+#pragma unroll
+            for (int ks = 0; ks < 2; ks++) kf[ks] = *reinterpret_cast<const v4i *>(lds + K_OFF + (j0 + r) * QK_STRIDE + ks * 32 + g * 16);
+            v16i s;
+#pragma unroll
+            for (int e = 0; e < 16; e++) s[e] = 0;
+#pragma unroll
+            for (int ks = 0; ks < 2; ks++) s = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf[ks], qf[ks], s, 0, 0, 0);
+            if (j0 + 32 <= n) {
+#pragma unroll
+                for (int e = 0; e < 16; e++) {
+                    sc[i][e] = (float)s[e] * m_sc;
+                    mx = __builtin_fmaxf(mx, sc[i][e]);
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; e++) {
+                    const int key = j0 + 8 * (e >> 2) + 4 * g + (e & 3);
+                    sc[i][e] = key < n ? (float)s[e] * m_sc : -INFINITY;
+                    mx = __builtin_fmaxf(mx, sc[i][e]);
+                }
+            }
+        }
+    }
+    mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32, 64));
+
+    double tile_sum[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const int j0 = 32 * i;
+        double part = 0.0;
+        if (j0 + 32 <= n) {
+#pragma unroll
+            for (int e = 0; e < 16; e++) {
+                const float ev = (float)exp_nonpos((double)(sc[i][e] - mx));
+                sc[i][e] = ev;
+                part += (double)ev;
+            }
+        } else if (j0 < n) {
+#pragma unroll
+            for (int e = 0; e < 16; e++) {
+                const float ev = (float)exp_nonpos((double)__builtin_fmaxf(sc[i][e] - mx, -746.0f));
+                sc[i][e] = ev;
+                part += (double)ev;
+            }
+        }
+        tile_sum[i] = part + __shfl_xor(part, 32, 64);
+    }
+    const float S = (float)(((tile_sum[0] + tile_sum[1]) + tile_sum[2]) + tile_sum[3]);
+    const float rS = __fdiv_rn(1.0f, S);
+
+    v16i o[2];
+#pragma unroll
+    for (int cb = 0; cb < 2; cb++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) o[cb][e] = opaque_zero();
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const int j0 = 32 * i;
+        if (j0 < n) {
+            v4i pf;
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                float f[4];
+#pragma unroll
+                for (int t = 0; t < 4; t++) f[t] = __builtin_amdgcn_fmed3f((sc[i][4 * q + t] * rS) * inv_sp, -127.0f, 127.0f) + SAMP_RNE_MAGIC;
+                pf[q] = pack_codes(f[0], f[1], f[2], f[3]);
+            }
+#pragma unroll
+            for (int cb = 0; cb < 2; cb++) {
+                v4i vf;
+#pragma unroll
+                for (int q = 0; q < 4; q++)
+                    vf[q] = *reinterpret_cast<const int *>(lds + VT_OFF + (cb * 32 + r) * VT_STRIDE + j0 + 8 * q + 4 * g);
+                o[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(pf, vf, o[cb], 0, 0, 0);
+            }
+        }
+    }
+
+    // context codes: a lane holds channel cb*32 + r of queries 8q + 4g + t; they change places through the wave's own
+    // query rows in LDS (read into qf above, read by no other wave) and leave as 32 bytes per lane
+    char *slab = lds + Q_OFF + q0 * QK_STRIDE;
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int cb = 0; cb < 2; cb++)
+#pragma unroll
+        for (int e = 0; e < 16; e++)
+            slab[(8 * (e >> 2) + 4 * g + (e & 3)) * QK_STRIDE + cb * 32 + r] = (char)qcode((float)o[cb][e] * m_ctx);
+    __builtin_amdgcn_wave_barrier();
+    const int query = lane >> 1, half = lane & 1;
+    if (q0 + query < n) {
+        const v4i lo = *reinterpret_cast<const v4i *>(slab + query * QK_STRIDE + half * 32);
+        const v4i hi = *reinterpret_cast<const v4i *>(slab + query * QK_STRIDE + half * 32 + 16);
+        int8_t *dst = ctx + (size_t)(sq.t0 + q0 + query) * H + head * 64 + half * 32;
+        *reinterpret_cast<v4i *>(dst) = lo;
+        *reinterpret_cast<v4i *>(dst + 16) = hi;
+    }
 }
 
 // FP16 flavour: fp16 q, k, v; binary32 scores, fast exp; P rounded to fp16 before P.V; binary32
@@ -921,6 +1205,17 @@ hipError_t launch_attention_i8(const int8_t *qkv, const int *cu, int B, int max_
         if (p_hist) launch_attention_i8_variant<false, true>(qkv, cu, B, max_len, H, heads, m_sc, inv_sp, m_ctx, ctx, p_hist, st, tm);
         else launch_attention_i8_variant<false, false>(qkv, cu, B, max_len, H, heads, m_sc, inv_sp, m_ctx, ctx, p_hist, st, tm);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_qkv_attention_i8(const int8_t *x, const int8_t *w_qkv, const float *m, const float *b, const int *cu, int B,
+                                   int max_len, int H, float m_sc, float inv_sp, float m_ctx, int8_t *ctx, hipStream_t st,
+                                   const Timing *tm)
+{
+    if (max_len > 128 || H % 64 || B <= 0) return hipErrorInvalidValue;
+    const size_t lds = 3 * (128 + 192) * 64 + 2 * 192 * sizeof(float);
+    launch_kernel(qkv_attention_i8_kernel, dim3((unsigned)(B * (H / 64))), dim3(256), lds, st, tm, (const char *)x,
+                  (const char *)w_qkv, m, b, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx);
     return hipGetLastError();
 }
 

@@ -29,6 +29,12 @@ def test_algorithmic_work_of_a_bert_base_forward():
     per_launch = (2048 * (H + F) + H * F)                     # int8: one byte per element
     assert abs(per_launch - 10.22e6) < 0.01e6
     assert work["ffn1"][1] == (T * (H + F) + H * F) * L        # weights once per layer, activations once
+    # with the QKV GEMM and the attention in one kernel, their operations add up and the q, k, v codes are no traffic
+    one = b.algorithmic_work(w, w.modes, lens, fused=True)
+    assert one["qkv"] == [0.0, 0.0] and one["attention"] == [0.0, 0.0]
+    assert one["qkv_attention"][0] == work["qkv"][0] + work["attention"][0]
+    assert one["qkv_attention"][1] == (2 * T * H + 3 * H * H) * L
+    assert one["ffn1"] == work["ffn1"] and work["qkv_attention"] == [0.0, 0.0]
     # an FP16 stack moves two bytes per element in every kernel
     fp16 = b.algorithmic_work(w, (0,) * L, lens)
     assert fp16["ffn1"][1] == 2 * work["ffn1"][1] and fp16["ln1"][1] == 2 * work["ln1"][1]

@@ -45,9 +45,10 @@ def args(w):
     return (w.layers, w.hidden, w.heads, w.ffn, w.ln_eps)
 
 
-def run_gpu(P, w, wts, sc, hid, mask):
+def run_gpu(P, w, wts, sc, hid, mask, fusion=0):
     import torch
     enc = P.Encoder(*args(w), w.modes, wts, sc, max_batch=hid.shape[0], max_seq=hid.shape[1])
+    enc.set_qkv_fusion(fusion)                  # 0: by size, 1: never, 2: QKV GEMM + attention in one kernel where possible
     h = torch.from_numpy(hid).cuda()
     m = None if mask is None else torch.from_numpy(mask).cuda()
     res = torch.empty_like(h)
@@ -151,6 +152,26 @@ def test_small_encoder_every_mode(P, mode, varlen):
     if mode == FULL_INT8:
         # every decision on this path is reproducible: the fp16 outputs are bit-identical
         assert (d == 0).all()
+
+
+@pytest.mark.parametrize("modes", [(FULL_INT8,) * 3, (MHA_INT8, FULL_INT8, FP16), (FULL_INT8 | P_UNSIGNED, FULL_INT8, FULL_INT8 | P_FP16)])
+@pytest.mark.parametrize("varlen", [False, True])
+def test_small_encoder_with_qkv_gemm_and_attention_in_one_kernel(P, modes, varlen):
+    """Forcing the kernel that does the QKV GEMM and the attention at once (small batches do not take it by themselves)
+    changes no byte of the output, on sequences of 1 to 128 tokens, and the Fully-Quant stack stays the oracle's."""
+    w = small(modes, batch=7, seq=128, varlen=varlen)
+    wts = W.make_weights(w)
+    hid, lens, mask = W.make_hidden(w)
+    sc = oracle.calibrate(*args(w), wts, W.make_calibration_batch(w))
+    for l, m in enumerate(modes):
+        if m & P_UNSIGNED:
+            sc[l, 4] = np.float32(sc[l, 4] * np.float32(127.0 / 255.0))
+    fused = run_gpu(P, w, wts, sc, hid, mask if varlen else None, fusion=2)
+    apart = run_gpu(P, w, wts, sc, hid, mask if varlen else None, fusion=1)
+    assert np.array_equal(fused, apart)
+    if all((m & 3) == FULL_INT8 for m in modes):
+        want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid, lens)
+        assert (compare(fused, want, lens, True, f"fused {modes} varlen={varlen}") == 0).all()
 
 
 @pytest.mark.parametrize("modes", [(FULL_INT8, FP16, FULL_INT8, FFN_INT8), (FP16, MHA_INT8, FFN_INT8, FULL_INT8),
@@ -441,7 +462,7 @@ def test_random_small_configurations(P, seed):
         if m & P_UNSIGNED:
             sc[l, 4] = np.float32(sc[l, 4] * np.float32(127.0 / 255.0))
     want = oracle.Encoder(*args(w), w.modes, wts, sc).forward(hid, lens)
-    got = run_gpu(P, w, wts, sc, hid, mask if w.varlen else None)
+    got = run_gpu(P, w, wts, sc, hid, mask if w.varlen else None, fusion=2 if seed % 2 else 0)
     exact = all((m & 3) == FULL_INT8 for m in modes)
     d = compare(got, want, lens, exact or all(m == FP16 for m in modes), f"random {seed}: H{w.hidden} F{w.ffn} B{w.batch} S{seq} {modes}",
                 loose_bound(modes, sc) if any(modes) else None)

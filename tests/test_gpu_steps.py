@@ -279,11 +279,39 @@ def test_int8_attention_bit_exact(P, lens, heads):
     assert np.abs(want).max() > 20
 
 
+@pytest.mark.parametrize("lens,heads,offsets", [([128, 128, 128], 2, False), ([1, 5, 32, 33, 64, 17, 128, 97], 3, True),
+                                                ([96] * 4, 1, False), ([128, 2, 65], 12, True), ([31], 16, True)])
+def test_qkv_gemm_and_attention_in_one_kernel_bit_exact(P, lens, heads, offsets):
+    """The kernel that does the QKV GEMM, its requantisation and the attention of a (sequence, head) at once gives the
+    oracle's requantised GEMM followed by the oracle's attention, and the bytes of the two separate kernels."""
+    rng = np.random.default_rng(sum(lens) + heads)
+    H = heads * 64
+    cu = _cu(lens)
+    T = int(cu[-1])
+    x = rng.integers(-127, 128, (T, H), dtype=np.int8)
+    w = rng.integers(-127, 128, (3 * H, H), dtype=np.int8)
+    m = (26.0 / (73.3 * 73.3 * np.sqrt(H)) * (0.8 + 0.4 * rng.random(3 * H))).astype(np.float32)   # codes ~ N(0, 26)
+    m[::17] *= 4                                                     # some channels reach the clamp
+    b = (rng.standard_normal(3 * H) * 3).astype(np.float32)
+    sc = (0.0209, 0.0249, 0.021, 0.0003, 0.0021)
+    qkv = oracle.epilogue_requant(oracle.gemm_i8_i32(x, w), m, b)
+    assert np.abs(qkv).max() == 127 and 15 < qkv.astype(np.float64).std() < 60
+    want = oracle.attention_i8(qkv, cu, heads, *sc)
+    cu_dev = dev(cu) if offsets else None
+    got = host(P.qkv_attention_i8(dev(x), dev(w), dev(m), dev(b), cu_dev, max(lens), heads, *sc))
+    assert np.array_equal(got, want)
+    if (3 * H) % 128 == 0:                                           # the stand-alone GEMM wants whole 128-channel tiles
+        two = host(P.attention_i8(P.gemm_i8_requant(dev(x), dev(w), dev(m), dev(b)), cu_dev, max(lens), heads, *sc))
+        assert np.array_equal(two, want)
+    assert np.abs(want).max() > 20
+    no_bias = host(P.qkv_attention_i8(dev(x), dev(w), dev(m), None, cu_dev, max(lens), heads, *sc))
+    assert np.array_equal(no_bias, oracle.attention_i8(oracle.epilogue_requant(oracle.gemm_i8_i32(x, w), m, np.zeros(3 * H, np.float32)), cu, heads, *sc))
+
+
 @pytest.mark.parametrize("S,B,heads,unsigned", [(128, 3, 2, False), (256, 2, 1, False), (384, 2, 1, False),
                                                 (512, 2, 1, False), (512, 1, 2, True), (96, 3, 1, False), (320, 2, 1, False)])
 def test_int8_attention_without_sequence_offsets_bit_exact(P, S, B, heads, unsigned):
-    """cu_seqlens NULL: B sequences of exactly S rows.  Lengths of 128, 256, 384 and 512 take the kernels that
-    carry no length tests at all; the others the general ones.  Same bytes as with explicit offsets, and the oracle's."""
+    """cu_seqlens NULL: B sequences of exactly S rows.  Same bytes as with explicit offsets, and the oracle's."""
     rng = np.random.default_rng(S + B)
     H = heads * 64
     cu = _cu([S] * B)
