@@ -177,7 +177,8 @@ SAMP_API int samp_encoder_set_groups(samp_encoder_t *enc, int32_t groups);
 
 /* Section 3.2 hands the QKV GEMM's requantised int8 output straight to the attention; for sequences of at
  * most 128 tokens one kernel can do both per (sequence, head), so that the q, k, v codes never reach memory and
- * a layer has one launch less (symmetric int8 softmax codes only).  mode 0 (default): used where it measured
+ * a layer has one launch less (INT8 blocks with symmetric int8 softmax codes, and FP16 blocks outside
+ * calibration).  mode 0 (default): used where it measured
  * faster (at least 128 (sequence, head) pairs per launch); 1: never; 2: whenever the shape allows.  The
  * context codes are the same bytes either way.                                                            */
 SAMP_API int samp_encoder_set_qkv_fusion(samp_encoder_t *enc, int32_t mode);
@@ -338,6 +339,10 @@ SAMP_API int samp_attention_i8(const int8_t *qkv, const int32_t *cu_seqlens, int
 SAMP_API int samp_qkv_attention_i8(const int8_t *x, const int8_t *w_qkv, const float *m, const float *b,
                                    const int32_t *cu_seqlens, int32_t B, int32_t max_len, int32_t hidden, int32_t heads,
                                    float s_q, float s_k, float s_v, float s_p, float s_ctx, int8_t *ctx, void *stream);
+/* The FP16 counterpart: out = samp_gemm_f16(x, w_qkv, bias, no GELU) followed by samp_attention_f16, in one kernel,
+ * byte for byte.  x dev fp16 [T,hidden], w_qkv dev fp16 [3 hidden, hidden], bias dev float [3 hidden] or NULL.  */
+SAMP_API int samp_qkv_attention_f16(const uint16_t *x, const uint16_t *w_qkv, const float *bias, const int32_t *cu_seqlens,
+                                    int32_t B, int32_t max_len, int32_t hidden, int32_t heads, uint16_t *ctx, void *stream);
 SAMP_API int samp_attention_f16(const uint16_t *qkv, const int32_t *cu_seqlens, int32_t B, int32_t max_len, int32_t hidden,
                                 int32_t heads, uint16_t *ctx, void *stream);
 

@@ -318,6 +318,15 @@ def qkv_attention_i8(x, w_qkv, m, b, cu, max_len: int, heads: int, s_q, s_k, s_v
     return ctx
 
 
+def qkv_attention_f16(x, w_qkv, bias, cu, max_len: int, heads: int):
+    """samp_qkv_attention_f16: ctx [T, H] fp16 from packed fp16 rows x [T, H] and the fp16 QKV weights [3H, H]."""
+    T, H = x.shape
+    B = _batch_of(cu, T, max_len)
+    ctx = torch.zeros((T, H), dtype=torch.float16, device=x.device)
+    _check(lib().samp_qkv_attention_f16(_dp(x), _dp(w_qkv), _dp(bias), _dp(cu), B, max_len, H, heads, _dp(ctx), _stream()))
+    return ctx
+
+
 def classify(hidden: torch.Tensor, w_pool, b_pool, w_cls, b_cls) -> torch.Tensor:
     """samp_classify: float32 logits [B, classes] from the first token of each sequence."""
     B, S, H = hidden.shape

@@ -295,13 +295,19 @@ int run(samp_encoder_t *enc, const void *hidden, const Ids *ids, const int32_t *
                                    nullptr, rows, H, H, st, timing(enc, SAMP_PROF_ATTN_OUT)));
         } else {
             if (am) HIP_TRY(launch_absmax_f16((const __half *)x, rows, H, H, am + 0, st));
-            HIP_TRY(launch_gemm_f16((const __half *)x, (const __half *)Y.w_qkv, Y.b_qkv, false, (__half *)w.qkv, rows,
-                                    3 * H, H, st, timing(enc, SAMP_PROF_QKV)));
-            if (am)
-                for (int part = 0; part < 3; part++)
-                    HIP_TRY(launch_absmax_f16((const __half *)w.qkv + part * H, rows, H, 3 * H, am + 1 + part, st));
-            HIP_TRY(launch_attention_f16((const __half *)w.qkv, cu, B, S, H, heads, 0.125f, (__half *)w.ctx,
-                                         am ? am + 4 : nullptr, st, timing(enc, SAMP_PROF_ATTN)));
+            // (calibration taps q, k, v and the softmax output, so it keeps the two kernels)
+            if (!am && S <= 128 && (enc->fusion_wanted == 2 || (enc->fusion_wanted == 0 && B * heads >= 128))) {
+                HIP_TRY(launch_qkv_attention_f16((const __half *)x, (const __half *)Y.w_qkv, Y.b_qkv, cu, B, S, H, 0.125f,
+                                                 (__half *)w.ctx, st, timing(enc, SAMP_PROF_QKV_ATTN)));
+            } else {
+                HIP_TRY(launch_gemm_f16((const __half *)x, (const __half *)Y.w_qkv, Y.b_qkv, false, (__half *)w.qkv, rows,
+                                        3 * H, H, st, timing(enc, SAMP_PROF_QKV)));
+                if (am)
+                    for (int part = 0; part < 3; part++)
+                        HIP_TRY(launch_absmax_f16((const __half *)w.qkv + part * H, rows, H, 3 * H, am + 1 + part, st));
+                HIP_TRY(launch_attention_f16((const __half *)w.qkv, cu, B, S, H, heads, 0.125f, (__half *)w.ctx,
+                                             am ? am + 4 : nullptr, st, timing(enc, SAMP_PROF_ATTN)));
+            }
             if (am) HIP_TRY(launch_absmax_f16((const __half *)w.ctx, rows, H, H, am + 5, st));
             HIP_TRY(launch_gemm_f16((const __half *)w.ctx, (const __half *)Y.w_o, nullptr, false, (__half *)w.ao, rows, H, H,
                                     st, timing(enc, SAMP_PROF_ATTN_OUT)));
@@ -848,6 +854,18 @@ int samp_qkv_attention_i8(const int8_t *x, const int8_t *w_qkv, const float *m, 
     const float m_ctx = (float)((double)s_p * (double)s_v / (double)s_ctx);
     HIP_TRY(launch_qkv_attention_i8(x, w_qkv, m, b, cu, B, max_len, hidden, m_sc, 1.0f / s_p, m_ctx, ctx, (hipStream_t)stream,
                                     nullptr));
+    return SAMP_OK;
+}
+
+int samp_qkv_attention_f16(const uint16_t *x, const uint16_t *w_qkv, const float *bias, const int32_t *cu, int32_t B,
+                           int32_t max_len, int32_t hidden, int32_t heads, uint16_t *ctx, void *stream)
+{
+    if (!x || !w_qkv || !ctx) return fail(SAMP_ERR_ARG, "NULL pointer");
+    if (B < 1 || max_len < 1 || max_len > 128) return fail(SAMP_ERR_SHAPE, "B >= 1 and 1 <= max_len <= 128 required");
+    if (heads < 1 || hidden != heads * 64) return fail(SAMP_ERR_SHAPE, "head size must be 64");
+    if (!aligned(x, 16) || !aligned(w_qkv, 16) || !aligned(ctx, 16)) return fail(SAMP_ERR_ARG, "tensors must be 16-byte aligned");
+    HIP_TRY(launch_qkv_attention_f16((const __half *)x, (const __half *)w_qkv, bias, cu, B, max_len, hidden, 0.125f, (__half *)ctx,
+                                     (hipStream_t)stream, nullptr));
     return SAMP_OK;
 }
 

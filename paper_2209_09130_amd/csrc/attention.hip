@@ -293,32 +293,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
 // layer is gone.  Every value is produced by the same operations in the same order as in the two separate kernels
 // (the row sums are added tile by tile as the four waves' partial sums are there), so the context codes are the same
 // bytes.
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void qkv_attention_i8_kernel(const char *__restrict__ X, const char *__restrict__ W, const float *__restrict__ m_tab,
-                             const float *__restrict__ b_tab, const int *__restrict__ cu, int max_len, int H, float m_sc,
-                             float inv_sp, float m_ctx, int8_t *__restrict__ ctx)
-{
-    constexpr int TM = 2, TN = 3, BKB = 64, NSTAGE = 3, NWAVES = 4, CH = 4, RPI = 16, KS = 2;
-    constexpr int BM = 128, BN = 192;
-    constexpr int A_BYTES = BM * BKB, STAGE_BYTES = (BM + BN) * BKB, RING_BYTES = NSTAGE * STAGE_BYTES;
-    constexpr int NLD = (BM + BN) / RPI / NWAVES;                 // 1 KiB pieces per wave and stage
-    constexpr int QK_STRIDE = 80, VT_STRIDE = 132;                // bytes per token row of q / k, per channel row of V^T
-    constexpr int Q_OFF = 0, K_OFF = BM * QK_STRIDE, VT_OFF = 2 * BM * QK_STRIDE;
-    static_assert(VT_OFF + 64 * VT_STRIDE <= RING_BYTES, "q, k and V^T take the place of the ring");
-    extern __shared__ __attribute__((aligned(1024))) char lds[];
-    float *tab = reinterpret_cast<float *>(lds + RING_BYTES);     // multipliers, then offsets, of the 192 columns
+struct QkvTile {                                           // the block tile both flavours of the kernel share
+    static constexpr int TM = 2, TN = 3, BKB = 64, NSTAGE = 3, NWAVES = 4, CH = 4, RPI = 16, KS = 2;
+    static constexpr int BM = 128, BN = 192;
+    static constexpr int A_BYTES = BM * BKB, STAGE_BYTES = (BM + BN) * BKB, RING_BYTES = NSTAGE * STAGE_BYTES;
+    static constexpr int NLD = (BM + BN) / RPI / NWAVES;          // 1 KiB pieces per wave and stage
+};
 
-    const int heads = H >> 6;
-    const int item = xcd_contiguous(blockIdx.x, gridDim.x);       // sequences outermost, as in the attention kernel
-    const int seq = item / heads, head = item % heads;
-    const SeqInfo sq = seq_info(cu, seq, max_len);
-    const int n = sq.n;
-    if (n <= 0) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
+// The GEMM part: the wave's 64 x 96 accumulators of X[t0 .. t0+n) . W_head^T, rows of Kbytes bytes; HALF: fp16 operands.
+// The main loop of the large-tile GEMM kernel (same ring, same waits); load_tables() runs once the first stages are
+// requested.  On return the ring is idle.
+template <bool HALF, class Acc, class LoadTables>
+__device__ __forceinline__ void qkv_tile_gemm(const char *__restrict__ X, const char *__restrict__ W, int t0, int n, int head, int H,
+                                              int Kbytes, char *lds, int wave, int lane, Acc (&acc)[3][2], LoadTables load_tables)
+{
+    constexpr int TM = QkvTile::TM, TN = QkvTile::TN, BKB = QkvTile::BKB, NSTAGE = QkvTile::NSTAGE, NWAVES = QkvTile::NWAVES;
+    constexpr int CH = QkvTile::CH, RPI = QkvTile::RPI, KS = QkvTile::KS, BM = QkvTile::BM;
+    constexpr int A_BYTES = QkvTile::A_BYTES, STAGE_BYTES = QkvTile::STAGE_BYTES, RING_BYTES = QkvTile::RING_BYTES, NLD = QkvTile::NLD;
     const int wm = (wave >> 1) * 32 * TM, wn = (wave & 1) * 32 * TN;
     const int r = lane & 31, g = lane >> 5;
-    const int Kbytes = H;
-
     // operand rows: the sequence's tokens (rows past its end repeat the last one), and the head's 64 rows of each of
     // the query, key and value thirds of the weight matrix
     const char *src[NLD];
@@ -327,7 +320,7 @@ void qkv_attention_i8_kernel(const char *__restrict__ X, const char *__restrict_
         const int srow = RPI * (wave + NWAVES * j) + lane / CH;
         if (srow < BM) {
             const int am = min(srow, n - 1);
-            src[j] = X + (size_t)(sq.t0 + am) * Kbytes + (((lane % CH) ^ swz<BKB>(srow)) << 4);
+            src[j] = X + (size_t)(t0 + am) * Kbytes + (((lane % CH) ^ swz<BKB>(srow)) << 4);
         } else {
             const int row = srow - BM;
             src[j] = W + (size_t)((row >> 6) * H + head * 64 + (row & 63)) * Kbytes + (((lane % CH) ^ swz<BKB>(row)) << 4);
@@ -363,13 +356,8 @@ void qkv_attention_i8_kernel(const char *__restrict__ X, const char *__restrict_
 #pragma unroll
     for (int s = 0; s < NSTAGE - 1; s++)
         if (s < KT) issue();
-    for (int c = tid; c < BN; c += 256) {
-        const int col = (c >> 6) * H + head * 64 + (c & 63);
-        tab[c] = m_tab[col];
-        tab[BN + c] = b_tab ? b_tab[col] : 0.0f;
-    }
+    load_tables();
 
-    v16i acc[TN][TM];
 #pragma unroll
     for (int i = 0; i < TN; i++)
 #pragma unroll
@@ -382,11 +370,15 @@ void qkv_attention_i8_kernel(const char *__restrict__ X, const char *__restrict_
         for (int j = 0; j < TM; j++)
             if (rows_live[j]) {
 #pragma unroll
-                for (int i = 0; i < TN; i++) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[i], fa[j], acc[i][j], 0, 0, 0);
+                for (int i = 0; i < TN; i++) {
+                    if constexpr (HALF)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, fw[i]), __builtin_bit_cast(v8h, fa[j]), acc[i][j], 0, 0, 0);
+                    else
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[i], fa[j], acc[i][j], 0, 0, 0);
+                }
             }
     };
 
-    // the main loop of the large-tile GEMM kernel (same ring, same waits)
     v4i fa[2][TM], fw[2][TN];
     if (KT > NSTAGE - 2) wait_vm_and_barrier<(NSTAGE - 2) * NLD>(); else wait_vm_and_barrier<0>();
     fetch(0, 0, fa[0], fw[0]);
@@ -420,6 +412,38 @@ void qkv_attention_i8_kernel(const char *__restrict__ X, const char *__restrict_
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) step(ks, false, false, std::integral_constant<int, 0>());
     wait_vm_and_barrier<0>();                                     // the ring is idle from here on
+}
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void qkv_attention_i8_kernel(const char *__restrict__ X, const char *__restrict__ W, const float *__restrict__ m_tab,
+                             const float *__restrict__ b_tab, const int *__restrict__ cu, int max_len, int H, float m_sc,
+                             float inv_sp, float m_ctx, int8_t *__restrict__ ctx)
+{
+    constexpr int TM = QkvTile::TM, TN = QkvTile::TN, BM = QkvTile::BM, BN = QkvTile::BN, RING_BYTES = QkvTile::RING_BYTES;
+    constexpr int QK_STRIDE = 80, VT_STRIDE = 132;                // bytes per token row of q / k, per channel row of V^T
+    constexpr int Q_OFF = 0, K_OFF = BM * QK_STRIDE, VT_OFF = 2 * BM * QK_STRIDE;
+    static_assert(VT_OFF + 64 * VT_STRIDE <= RING_BYTES, "q, k and V^T take the place of the ring");
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    float *tab = reinterpret_cast<float *>(lds + RING_BYTES);     // multipliers, then offsets, of the 192 columns
+
+    const int heads = H >> 6;
+    const int item = xcd_contiguous(blockIdx.x, gridDim.x);       // sequences outermost, as in the attention kernel
+    const int seq = item / heads, head = item % heads;
+    const SeqInfo sq = seq_info(cu, seq, max_len);
+    const int n = sq.n;
+    if (n <= 0) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
+    const int wm = (wave >> 1) * 32 * TM, wn = (wave & 1) * 32 * TN;
+    const int r = lane & 31, g = lane >> 5;
+
+    v16i acc[TN][TM];
+    qkv_tile_gemm<false>(X, W, sq.t0, n, head, H, H, lds, wave, lane, acc, [&]() {
+        for (int c = tid; c < BN; c += 256) {
+            const int col = (c >> 6) * H + head * 64 + (c & 63);
+            tab[c] = m_tab[col];
+            tab[BN + c] = b_tab ? b_tab[col] : 0.0f;
+        }
+    });
 
     // requantise into LDS: q and k as token rows of 64 codes, v transposed (a channel's codes of all keys in a row).
     // A lane holds one token and groups of four consecutive channels.
@@ -563,6 +587,158 @@ void qkv_attention_i8_kernel(const char *__restrict__ X, const char *__restrict_
         int8_t *dst = ctx + (size_t)(sq.t0 + q0 + query) * H + head * 64 + half * 32;
         *reinterpret_cast<v4i *>(dst) = lo;
         *reinterpret_cast<v4i *>(dst + 16) = hi;
+    }
+}
+
+// The FP16 flavour of the kernel above: fp16 QKV GEMM with its bias, q, k, v rounded to fp16 into LDS, then the
+// arithmetic of attention_f16_kernel.  The products P.V of the four key tiles are formed from zero one by one and
+// added in the order in which that kernel adds its four waves' partial contexts (tiles past the end add +0), and the
+// row sums likewise, so the context is the same bytes as from the two kernels.
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void qkv_attention_f16_kernel(const char *__restrict__ X, const char *__restrict__ W, const float *__restrict__ bias,
+                              const int *__restrict__ cu, int max_len, int H, float scale, __half *__restrict__ ctx)
+{
+    constexpr int TM = QkvTile::TM, TN = QkvTile::TN, BM = QkvTile::BM, BN = QkvTile::BN, RING_BYTES = QkvTile::RING_BYTES;
+    constexpr int QK_STRIDE = 144, VT_STRIDE = 264;               // bytes per token row of q / k (64 fp16 + pad), per channel row of V^T (128 keys + pad)
+    constexpr int Q_OFF = 0, K_OFF = BM * QK_STRIDE, VT_OFF = 2 * BM * QK_STRIDE;
+    static_assert(VT_OFF + 64 * VT_STRIDE <= RING_BYTES, "q, k and V^T take the place of the ring");
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    float *tab = reinterpret_cast<float *>(lds + RING_BYTES);     // bias of the 192 columns
+
+    const int heads = H >> 6;
+    const int item = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int seq = item / heads, head = item % heads;
+    const SeqInfo sq = seq_info(cu, seq, max_len);
+    const int n = sq.n;
+    if (n <= 0) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
+    const int wm = (wave >> 1) * 32 * TM, wn = (wave & 1) * 32 * TN;
+    const int r = lane & 31, g = lane >> 5;
+
+    v16f acc[TN][TM];
+    qkv_tile_gemm<true>(X, W, sq.t0, n, head, H, 2 * H, lds, wave, lane, acc, [&]() {
+        for (int c = tid; c < BN; c += 256) tab[c] = bias ? bias[(c >> 6) * H + head * 64 + (c & 63)] : 0.0f;
+    });
+
+    // fp16(acc + bias) into LDS: q and k as token rows, v transposed
+#pragma unroll
+    for (int io = 0; io < TN; io++) {
+        const int nl = wn + io * 32;
+        const int part = nl >> 6, c0 = nl & 63;
+        v4f bb[4];
+#pragma unroll
+        for (int q = 0; q < 4; q++) bb[q] = *reinterpret_cast<const v4f *>(tab + nl + 8 * q + 4 * g);
+#pragma unroll
+        for (int j = 0; j < TM; j++) {
+            const int row = wm + 32 * j + r;
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                const v16f &a = acc[io][j];
+                const v4h h = {to_half(a[4 * q] + bb[q].x), to_half(a[4 * q + 1] + bb[q].y), to_half(a[4 * q + 2] + bb[q].z),
+                               to_half(a[4 * q + 3] + bb[q].w)};
+                const int c = c0 + 8 * q + 4 * g;
+                if (part < 2) {
+                    *reinterpret_cast<v4h *>(lds + (part ? K_OFF : Q_OFF) + row * QK_STRIDE + c * 2) = h;
+                } else {
+#pragma unroll
+                    for (int t = 0; t < 4; t++) *reinterpret_cast<_Float16 *>(lds + VT_OFF + (c + t) * VT_STRIDE + row * 2) = h[t];
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    const int q0 = wave * QB;
+    if (q0 >= n) return;                                          // no barrier below
+    v8h qf[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ks++) qf[ks] = *reinterpret_cast<const v8h *>(lds + Q_OFF + (q0 + r) * QK_STRIDE + (ks * 16 + g * 8) * 2);
+    float sc[4][16];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const int j0 = 32 * i;
+        if (j0 < n) {
+            v16f s;
+#pragma unroll
+            for (int e = 0; e < 16; e++) s[e] = 0.0f;
+#pragma unroll
+            for (int ks = 0; ks < 4; ks++)
+                s = __builtin_amdgcn_mfma_f32_32x32x16_f16(*reinterpret_cast<const v8h *>(lds + K_OFF + (j0 + r) * QK_STRIDE + (ks * 16 + g * 8) * 2),
+                                                           qf[ks], s, 0, 0, 0);
+#pragma unroll
+            for (int e = 0; e < 16; e++) {
+                const int key = j0 + 8 * (e >> 2) + 4 * g + (e & 3);
+                sc[i][e] = key < n ? s[e] * scale : -INFINITY;
+                mx = __builtin_fmaxf(mx, sc[i][e]);
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 16; e++) sc[i][e] = -INFINITY;
+        }
+    }
+    mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32, 64));
+
+    float tile_sum[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        float part = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+            const float ev = __builtin_amdgcn_exp2f((sc[i][e] - mx) * 1.44269504088896341f);
+            sc[i][e] = ev;
+            part += ev;
+        }
+        tile_sum[i] = part + __shfl_xor(part, 32, 64);
+    }
+    const float S = ((tile_sum[0] + tile_sum[1]) + tile_sum[2]) + tile_sum[3];
+    const float rS = __fdiv_rn(1.0f, S);
+
+    v16f o[2];
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        v16f ot[2];
+#pragma unroll
+        for (int cb = 0; cb < 2; cb++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) ot[cb][e] = 0.0f;
+        if (32 * i < n) {
+#pragma unroll
+            for (int hf = 0; hf < 2; hf++) {                    // keys 8q+4g+t for q in {2hf, 2hf+1}
+                v8h pf;
+#pragma unroll
+                for (int e = 0; e < 8; e++) pf[e] = to_half(sc[i][8 * hf + e] * rS);
+#pragma unroll
+                for (int cb = 0; cb < 2; cb++) {
+                    const char *rowp = lds + VT_OFF + (cb * 32 + r) * VT_STRIDE + 32 * i * 2;
+                    const v4h lo = *reinterpret_cast<const v4h *>(rowp + (16 * hf + 4 * g) * 2);
+                    const v4h hi = *reinterpret_cast<const v4h *>(rowp + (16 * hf + 8 + 4 * g) * 2);
+                    const v8h vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    ot[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(pf, vf, ot[cb], 0, 0, 0);
+                }
+            }
+        }
+#pragma unroll
+        for (int cb = 0; cb < 2; cb++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) o[cb][e] = i == 0 ? ot[cb][e] : o[cb][e] + ot[cb][e];
+    }
+
+    // context: through the wave's own query rows in LDS, out as 64 bytes per lane
+    char *slab = lds + Q_OFF + q0 * QK_STRIDE;
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int cb = 0; cb < 2; cb++)
+#pragma unroll
+        for (int e = 0; e < 16; e++)
+            *reinterpret_cast<_Float16 *>(slab + (8 * (e >> 2) + 4 * g + (e & 3)) * QK_STRIDE + (cb * 32 + r) * 2) = to_half(o[cb][e]);
+    __builtin_amdgcn_wave_barrier();
+    const int query = lane >> 1, half = lane & 1;
+    if (q0 + query < n) {
+        __half *dst = ctx + (size_t)(sq.t0 + q0 + query) * H + head * 64 + half * 32;
+#pragma unroll
+        for (int u = 0; u < 4; u++)
+            *reinterpret_cast<v4i *>(dst + u * 8) = *reinterpret_cast<const v4i *>(slab + query * QK_STRIDE + half * 64 + u * 16);
     }
 }
 
@@ -1216,6 +1392,16 @@ hipError_t launch_qkv_attention_i8(const int8_t *x, const int8_t *w_qkv, const f
     const size_t lds = 3 * (128 + 192) * 64 + 2 * 192 * sizeof(float);
     launch_kernel(qkv_attention_i8_kernel, dim3((unsigned)(B * (H / 64))), dim3(256), lds, st, tm, (const char *)x,
                   (const char *)w_qkv, m, b, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx);
+    return hipGetLastError();
+}
+
+hipError_t launch_qkv_attention_f16(const __half *x, const __half *w_qkv, const float *bias, const int *cu, int B, int max_len,
+                                    int H, float scale, __half *ctx, hipStream_t st, const Timing *tm)
+{
+    if (max_len > 128 || H % 64 || B <= 0) return hipErrorInvalidValue;
+    const size_t lds = 3 * (128 + 192) * 64 + 192 * sizeof(float);
+    launch_kernel(qkv_attention_f16_kernel, dim3((unsigned)(B * (H / 64))), dim3(256), lds, st, tm, (const char *)x,
+                  (const char *)w_qkv, bias, cu, max_len, H, scale, ctx);
     return hipGetLastError();
 }
 

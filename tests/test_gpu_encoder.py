@@ -154,7 +154,8 @@ def test_small_encoder_every_mode(P, mode, varlen):
         assert (d == 0).all()
 
 
-@pytest.mark.parametrize("modes", [(FULL_INT8,) * 3, (MHA_INT8, FULL_INT8, FP16), (FULL_INT8 | P_UNSIGNED, FULL_INT8, FULL_INT8 | P_FP16)])
+@pytest.mark.parametrize("modes", [(FULL_INT8,) * 3, (MHA_INT8, FULL_INT8, FP16), (FULL_INT8 | P_UNSIGNED, FULL_INT8, FULL_INT8 | P_FP16),
+                                   (FP16,) * 3, (FFN_INT8, FP16, FULL_INT8)])
 @pytest.mark.parametrize("varlen", [False, True])
 def test_small_encoder_with_qkv_gemm_and_attention_in_one_kernel(P, modes, varlen):
     """Forcing the kernel that does the QKV GEMM and the attention at once (small batches do not take it by themselves)

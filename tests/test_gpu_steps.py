@@ -415,6 +415,32 @@ def test_fp16_attention_within_tolerance(P, lens, heads):
     assert np.abs(got - want).mean() <= 1e-4
 
 
+@pytest.mark.parametrize("lens,heads,offsets", [([128, 128, 128], 2, False), ([1, 5, 32, 33, 64, 17, 128, 97], 2, True),
+                                                ([128, 2, 65], 12, True), ([96] * 3, 4, False)])
+def test_fp16_qkv_gemm_and_attention_in_one_kernel(P, lens, heads, offsets):
+    """The FP16 kernel that does the QKV GEMM and the attention at once: the bytes of the two separate kernels, and the
+    oracle's GEMM + attention within the tolerance of those kernels."""
+    rng = np.random.default_rng(sum(lens) + heads + 5)
+    H = heads * 64
+    cu = _cu(lens)
+    T = int(cu[-1])
+    x = rng.standard_normal((T, H)).astype(np.float16)
+    w = (rng.standard_normal((3 * H, H)) * 0.6 / np.sqrt(H)).astype(np.float16)
+    bias = (rng.standard_normal(3 * H) * 0.1).astype(np.float32)
+    cu_dev = dev(cu) if offsets else None
+    got = host(P.qkv_attention_f16(dev(x), dev(w), dev(bias), cu_dev, max(lens), heads))
+    two = host(P.attention_f16(P.gemm_f16(dev(x), dev(w), dev(bias), False), cu_dev, max(lens), heads))
+    assert np.array_equal(got.view(np.uint16), two.view(np.uint16))
+    qkv = oracle.gemm_f16(x, w, bias, False)
+    want = oracle.attention_f16(qkv, cu, heads).astype(np.float64)
+    d = np.abs(got.astype(np.float64) - want)
+    assert d.max() <= 4e-3 and d.mean() <= 2e-4                    # q, k, v may differ by an fp16 ulp on top of the attention's own bound
+    assert np.abs(want).max() > 0.05
+    none = host(P.qkv_attention_f16(dev(x), dev(w), None, cu_dev, max(lens), heads))
+    assert np.array_equal(none.view(np.uint16),
+                          host(P.attention_f16(P.gemm_f16(dev(x), dev(w), None, False), cu_dev, max(lens), heads)).view(np.uint16))
+
+
 @pytest.mark.parametrize("lens,heads", [([513], 1), ([700, 31, 1024], 2), ([2048, 515], 1)])
 def test_long_sequence_attention_matches_the_oracle(P, lens, heads):
     """More than 512 keys: the three-sweep kernels (row maxima, row sums, codes and P.V, recomputing the integer
