@@ -60,8 +60,8 @@ def measured_traffic(workload: str, mode: str, kernel: str, tokens_per_launch: i
 
 def algorithmic_work(w, modes, lens, fused=False):
     """Per kernel class, summed over one forward: (ops, bytes) that the method itself needs - operands read once,
-    results written once, weights once per layer.  fused: INT8 attention blocks with symmetric softmax codes run the QKV
-    GEMM and the attention as one kernel (class qkv_attention: the q, k, v codes are not traffic any more)."""
+    results written once, weights once per layer.  fused: attention blocks (INT8 ones with symmetric softmax codes, and FP16
+    ones) run the QKV GEMM and the attention as one kernel (class qkv_attention: q, k, v are not traffic any more)."""
     T = int(lens.sum())
     H, F = w.hidden, w.ffn
     att = float((lens.astype("float64") ** 2).sum()) * 4 * H
@@ -70,8 +70,8 @@ def algorithmic_work(w, modes, lens, fused=False):
         em = 1 if m & 1 else 2
         ef = 1 if m & 2 else 2
         en = 2 if i + 1 == len(modes) else (1 if modes[i + 1] & 1 else 2)
-        one_kernel = fused and (m & 1) and not (m & ~3)
-        front = ((("qkv_attention", 2.0 * T * 3 * H * H + att, T * 2 * H + 3 * H * H),) if one_kernel else
+        one_kernel = fused and not ((m & 1) and (m & ~3))        # not for the unsigned / binary16 softmax variants
+        front = ((("qkv_attention", 2.0 * T * 3 * H * H + att, (T * 2 * H + 3 * H * H) * em),) if one_kernel else
                  (("qkv", 2.0 * T * 3 * H * H, (T * 4 * H + 3 * H * H) * em), ("attention", att, T * 4 * H * em)))
         for k, ops, byts in front + (("attn_out", 2.0 * T * H * H, (T * 2 * H + H * H) * em),
                                      ("ln1", 10.0 * T * H, T * H * (2 * em + ef)),

@@ -35,6 +35,8 @@ def test_algorithmic_work_of_a_bert_base_forward():
     assert one["qkv_attention"][0] == work["qkv"][0] + work["attention"][0]
     assert one["qkv_attention"][1] == (2 * T * H + 3 * H * H) * L
     assert one["ffn1"] == work["ffn1"] and work["qkv_attention"] == [0.0, 0.0]
+    half = b.algorithmic_work(w, (0,) * L, lens, fused=True)
+    assert half["qkv_attention"] == [one["qkv_attention"][0], 2 * one["qkv_attention"][1]] and half["qkv"] == [0.0, 0.0]
     # an FP16 stack moves two bytes per element in every kernel
     fp16 = b.algorithmic_work(w, (0,) * L, lens)
     assert fp16["ffn1"][1] == 2 * work["ffn1"][1] and fp16["ln1"][1] == 2 * work["ln1"][1]
