@@ -303,7 +303,12 @@ struct QkvTile {                                           // the block tile bot
 // The GEMM part: the wave's 64 x 96 accumulators of X[t0 .. t0+n) . W_head^T, rows of Kbytes bytes; HALF: fp16 operands.
 // The main loop of the large-tile GEMM kernel (same ring, same waits); load_tables() runs once the first stages are
 // requested.  On return the ring is idle.
-template <bool HALF, class Acc, class LoadTables>
+// VWAVE: the wave's last two channel tiles are value channels.  Their products are formed with the operands the other
+// way round (token rows first), so that a lane of the result holds ONE channel and four consecutive tokens per
+// register group: exactly a dword (fp16: 8 bytes) of V^T, which the P.V product wants key-contiguous.  The sums are
+// the same (the same products over the same k).  ALL_LIVE: every 32-token tile of the block holds tokens (no tests in
+// the loop).
+template <bool HALF, bool VWAVE, bool ALL_LIVE, class Acc, class LoadTables>
 __device__ __forceinline__ void qkv_tile_gemm(const char *__restrict__ X, const char *__restrict__ W, int t0, int n, int head, int H,
                                               int Kbytes, char *lds, int wave, int lane, Acc (&acc)[3][2], LoadTables load_tables)
 {
@@ -368,13 +373,15 @@ __device__ __forceinline__ void qkv_tile_gemm(const char *__restrict__ X, const 
     auto multiply = [&](const v4i (&fa)[TM], const v4i (&fw)[TN]) {
 #pragma unroll
         for (int j = 0; j < TM; j++)
-            if (rows_live[j]) {
+            if (ALL_LIVE || rows_live[j]) {
 #pragma unroll
                 for (int i = 0; i < TN; i++) {
+                    const bool tokens_first = VWAVE && i >= 1;
+                    const v4i first = tokens_first ? fa[j] : fw[i], second = tokens_first ? fw[i] : fa[j];
                     if constexpr (HALF)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, fw[i]), __builtin_bit_cast(v8h, fa[j]), acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, first), __builtin_bit_cast(v8h, second), acc[i][j], 0, 0, 0);
                     else
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[i], fa[j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(first, second, acc[i][j], 0, 0, 0);
                 }
             }
     };
@@ -414,6 +421,21 @@ __device__ __forceinline__ void qkv_tile_gemm(const char *__restrict__ X, const 
     wait_vm_and_barrier<0>();                                     // the ring is idle from here on
 }
 
+// one of four copies of the loop: by wave column (value channels or not) and by whether all token tiles are live
+template <bool HALF, class Acc, class LoadTables>
+__device__ __forceinline__ void qkv_tile_gemm_any(const char *__restrict__ X, const char *__restrict__ W, int t0, int n, int head, int H,
+                                                  int Kbytes, char *lds, int wave, int lane, Acc (&acc)[3][2], LoadTables load_tables)
+{
+    const bool all_live = n > 96;                                 // block-uniform; wave & 1 is wave-uniform
+    if (wave & 1) {
+        if (all_live) qkv_tile_gemm<HALF, true, true>(X, W, t0, n, head, H, Kbytes, lds, wave, lane, acc, load_tables);
+        else qkv_tile_gemm<HALF, true, false>(X, W, t0, n, head, H, Kbytes, lds, wave, lane, acc, load_tables);
+    } else {
+        if (all_live) qkv_tile_gemm<HALF, false, true>(X, W, t0, n, head, H, Kbytes, lds, wave, lane, acc, load_tables);
+        else qkv_tile_gemm<HALF, false, false>(X, W, t0, n, head, H, Kbytes, lds, wave, lane, acc, load_tables);
+    }
+}
+
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void qkv_attention_i8_kernel(const char *__restrict__ X, const char *__restrict__ W, const float *__restrict__ m_tab,
                              const float *__restrict__ b_tab, const int *__restrict__ cu, int max_len, int H, float m_sc,
@@ -437,7 +459,7 @@ void qkv_attention_i8_kernel(const char *__restrict__ X, const char *__restrict_
     const int r = lane & 31, g = lane >> 5;
 
     v16i acc[TN][TM];
-    qkv_tile_gemm<false>(X, W, sq.t0, n, head, H, H, lds, wave, lane, acc, [&]() {
+    qkv_tile_gemm_any<false>(X, W, sq.t0, n, head, H, H, lds, wave, lane, acc, [&]() {
         for (int c = tid; c < BN; c += 256) {
             const int col = (c >> 6) * H + head * 64 + (c & 63);
             tab[c] = m_tab[col];
@@ -446,35 +468,43 @@ void qkv_attention_i8_kernel(const char *__restrict__ X, const char *__restrict_
     });
 
     // requantise into LDS: q and k as token rows of 64 codes, v transposed (a channel's codes of all keys in a row).
-    // A lane holds one token and groups of four consecutive channels.
+    // In a query / key tile a lane holds one token and groups of four consecutive channels; in a value tile one channel
+    // and groups of four consecutive tokens.
 #pragma unroll
     for (int io = 0; io < TN; io++) {
         const int nl = wn + io * 32;                              // first of the tile's 32 columns among the block's 192 (scalar)
         const int part = nl >> 6, c0 = nl & 63;                   // 0 query, 1 key, 2 value
-        v4f mm[4], bb[4];
-#pragma unroll
-        for (int q = 0; q < 4; q++) {
-            mm[q] = *reinterpret_cast<const v4f *>(tab + nl + 8 * q + 4 * g);
-            bb[q] = *reinterpret_cast<const v4f *>(tab + BN + nl + 8 * q + 4 * g);
-        }
-#pragma unroll
-        for (int j = 0; j < TM; j++) {
-            const int row = wm + 32 * j + r;
+        if (part < 2) {
+            v4f mm[4], bb[4];
 #pragma unroll
             for (int q = 0; q < 4; q++) {
-                const v16i &a = acc[io][j];
-                const int pk = pack_codes(code_bits(__builtin_fmaf((float)a[4 * q + 0], mm[q].x, bb[q].x)),
-                                          code_bits(__builtin_fmaf((float)a[4 * q + 1], mm[q].y, bb[q].y)),
-                                          code_bits(__builtin_fmaf((float)a[4 * q + 2], mm[q].z, bb[q].z)),
-                                          code_bits(__builtin_fmaf((float)a[4 * q + 3], mm[q].w, bb[q].w)));
-                const int c = c0 + 8 * q + 4 * g;
-                if (part < 2) {
-                    *reinterpret_cast<int *>(lds + (part ? K_OFF : Q_OFF) + row * QK_STRIDE + c) = pk;
-                } else {
+                mm[q] = *reinterpret_cast<const v4f *>(tab + nl + 8 * q + 4 * g);
+                bb[q] = *reinterpret_cast<const v4f *>(tab + BN + nl + 8 * q + 4 * g);
+            }
 #pragma unroll
-                    for (int t = 0; t < 4; t++) lds[VT_OFF + (c + t) * VT_STRIDE + row] = (char)(pk >> (8 * t));
+            for (int j = 0; j < TM; j++) {
+                const int row = wm + 32 * j + r;
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const v16i &a = acc[io][j];
+                    const int pk = pack_codes(code_bits(__builtin_fmaf((float)a[4 * q + 0], mm[q].x, bb[q].x)),
+                                              code_bits(__builtin_fmaf((float)a[4 * q + 1], mm[q].y, bb[q].y)),
+                                              code_bits(__builtin_fmaf((float)a[4 * q + 2], mm[q].z, bb[q].z)),
+                                              code_bits(__builtin_fmaf((float)a[4 * q + 3], mm[q].w, bb[q].w)));
+                    *reinterpret_cast<int *>(lds + (part ? K_OFF : Q_OFF) + row * QK_STRIDE + c0 + 8 * q + 4 * g) = pk;
                 }
             }
+        } else {
+            const float mm = tab[nl + r], bb = tab[BN + nl + r];  // the lane's channel
+#pragma unroll
+            for (int j = 0; j < TM; j++)
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const v16i &a = acc[io][j];
+                    const int pk = pack_codes(code_bits(__builtin_fmaf((float)a[4 * q + 0], mm, bb)), code_bits(__builtin_fmaf((float)a[4 * q + 1], mm, bb)),
+                                              code_bits(__builtin_fmaf((float)a[4 * q + 2], mm, bb)), code_bits(__builtin_fmaf((float)a[4 * q + 3], mm, bb)));
+                    *reinterpret_cast<int *>(lds + VT_OFF + (c0 + r) * VT_STRIDE + wm + 32 * j + 8 * q + 4 * g) = pk;
+                }
         }
     }
     __syncthreads();
@@ -565,20 +595,22 @@ void qkv_attention_i8_kernel(const char *__restrict__ X, const char *__restrict_
 #pragma unroll
                 for (int q = 0; q < 4; q++)
                     vf[q] = *reinterpret_cast<const int *>(lds + VT_OFF + (cb * 32 + r) * VT_STRIDE + j0 + 8 * q + 4 * g);
-                o[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(pf, vf, o[cb], 0, 0, 0);
+                o[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, pf, o[cb], 0, 0, 0);   // channels x queries: a lane holds ONE query
             }
         }
     }
 
-    // context codes: a lane holds channel cb*32 + r of queries 8q + 4g + t; they change places through the wave's own
-    // query rows in LDS (read into qf above, read by no other wave) and leave as 32 bytes per lane
+    // context codes: the lane's query, channels cb*32 + 8q + 4g + t: four codes per dword into the wave's own query rows
+    // in LDS (read into qf above, read by no other wave), from where they leave as 32 bytes per lane
     char *slab = lds + Q_OFF + q0 * QK_STRIDE;
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int cb = 0; cb < 2; cb++)
 #pragma unroll
-        for (int e = 0; e < 16; e++)
-            slab[(8 * (e >> 2) + 4 * g + (e & 3)) * QK_STRIDE + cb * 32 + r] = (char)qcode((float)o[cb][e] * m_ctx);
+        for (int q = 0; q < 4; q++)
+            *reinterpret_cast<int *>(slab + r * QK_STRIDE + cb * 32 + 8 * q + 4 * g) =
+                pack4(qcode((float)o[cb][4 * q] * m_ctx), qcode((float)o[cb][4 * q + 1] * m_ctx), qcode((float)o[cb][4 * q + 2] * m_ctx),
+                      qcode((float)o[cb][4 * q + 3] * m_ctx));
     __builtin_amdgcn_wave_barrier();
     const int query = lane >> 1, half = lane & 1;
     if (q0 + query < n) {
@@ -616,34 +648,40 @@ void qkv_attention_f16_kernel(const char *__restrict__ X, const char *__restrict
     const int r = lane & 31, g = lane >> 5;
 
     v16f acc[TN][TM];
-    qkv_tile_gemm<true>(X, W, sq.t0, n, head, H, 2 * H, lds, wave, lane, acc, [&]() {
+    qkv_tile_gemm_any<true>(X, W, sq.t0, n, head, H, 2 * H, lds, wave, lane, acc, [&]() {
         for (int c = tid; c < BN; c += 256) tab[c] = bias ? bias[(c >> 6) * H + head * 64 + (c & 63)] : 0.0f;
     });
 
-    // fp16(acc + bias) into LDS: q and k as token rows, v transposed
+    // fp16(acc + bias) into LDS: q and k as token rows, v transposed (lane layouts as in the INT8 flavour)
 #pragma unroll
     for (int io = 0; io < TN; io++) {
         const int nl = wn + io * 32;
         const int part = nl >> 6, c0 = nl & 63;
-        v4f bb[4];
+        if (part < 2) {
+            v4f bb[4];
 #pragma unroll
-        for (int q = 0; q < 4; q++) bb[q] = *reinterpret_cast<const v4f *>(tab + nl + 8 * q + 4 * g);
+            for (int q = 0; q < 4; q++) bb[q] = *reinterpret_cast<const v4f *>(tab + nl + 8 * q + 4 * g);
 #pragma unroll
-        for (int j = 0; j < TM; j++) {
-            const int row = wm + 32 * j + r;
+            for (int j = 0; j < TM; j++) {
+                const int row = wm + 32 * j + r;
 #pragma unroll
-            for (int q = 0; q < 4; q++) {
-                const v16f &a = acc[io][j];
-                const v4h h = {to_half(a[4 * q] + bb[q].x), to_half(a[4 * q + 1] + bb[q].y), to_half(a[4 * q + 2] + bb[q].z),
-                               to_half(a[4 * q + 3] + bb[q].w)};
-                const int c = c0 + 8 * q + 4 * g;
-                if (part < 2) {
-                    *reinterpret_cast<v4h *>(lds + (part ? K_OFF : Q_OFF) + row * QK_STRIDE + c * 2) = h;
-                } else {
-#pragma unroll
-                    for (int t = 0; t < 4; t++) *reinterpret_cast<_Float16 *>(lds + VT_OFF + (c + t) * VT_STRIDE + row * 2) = h[t];
+                for (int q = 0; q < 4; q++) {
+                    const v16f &a = acc[io][j];
+                    const v4h h = {to_half(a[4 * q] + bb[q].x), to_half(a[4 * q + 1] + bb[q].y), to_half(a[4 * q + 2] + bb[q].z),
+                                   to_half(a[4 * q + 3] + bb[q].w)};
+                    *reinterpret_cast<v4h *>(lds + (part ? K_OFF : Q_OFF) + row * QK_STRIDE + (c0 + 8 * q + 4 * g) * 2) = h;
                 }
             }
+        } else {
+            const float bb = tab[nl + r];                         // the lane's channel
+#pragma unroll
+            for (int j = 0; j < TM; j++)
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const v16f &a = acc[io][j];
+                    const v4h h = {to_half(a[4 * q] + bb), to_half(a[4 * q + 1] + bb), to_half(a[4 * q + 2] + bb), to_half(a[4 * q + 3] + bb)};
+                    *reinterpret_cast<v4h *>(lds + VT_OFF + (c0 + r) * VT_STRIDE + (wm + 32 * j + 8 * q + 4 * g) * 2) = h;
+                }
         }
     }
     __syncthreads();
@@ -714,7 +752,7 @@ void qkv_attention_f16_kernel(const char *__restrict__ X, const char *__restrict
                     const v4h lo = *reinterpret_cast<const v4h *>(rowp + (16 * hf + 4 * g) * 2);
                     const v4h hi = *reinterpret_cast<const v4h *>(rowp + (16 * hf + 8 + 4 * g) * 2);
                     const v8h vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                    ot[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(pf, vf, ot[cb], 0, 0, 0);
+                    ot[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf, ot[cb], 0, 0, 0);   // channels x queries: a lane holds ONE query
                 }
             }
         }
@@ -724,14 +762,16 @@ void qkv_attention_f16_kernel(const char *__restrict__ X, const char *__restrict
             for (int e = 0; e < 16; e++) o[cb][e] = i == 0 ? ot[cb][e] : o[cb][e] + ot[cb][e];
     }
 
-    // context: through the wave's own query rows in LDS, out as 64 bytes per lane
+    // context: the lane's query, channels cb*32 + 8q + 4g + t; through the wave's own query rows in LDS, out as 64 bytes per lane
     char *slab = lds + Q_OFF + q0 * QK_STRIDE;
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int cb = 0; cb < 2; cb++)
 #pragma unroll
-        for (int e = 0; e < 16; e++)
-            *reinterpret_cast<_Float16 *>(slab + (8 * (e >> 2) + 4 * g + (e & 3)) * QK_STRIDE + (cb * 32 + r) * 2) = to_half(o[cb][e]);
+        for (int q = 0; q < 4; q++) {
+            const v4h h = {to_half(o[cb][4 * q]), to_half(o[cb][4 * q + 1]), to_half(o[cb][4 * q + 2]), to_half(o[cb][4 * q + 3])};
+            *reinterpret_cast<v4h *>(slab + r * QK_STRIDE + (cb * 32 + 8 * q + 4 * g) * 2) = h;
+        }
     __builtin_amdgcn_wave_barrier();
     const int query = lane >> 1, half = lane & 1;
     if (q0 + query < n) {
