@@ -552,15 +552,8 @@ void qkv_attention_i8_kernel(const char *__restrict__ X, const char *__restrict_
     for (int i = 0; i < 4; i++) {
         const int j0 = 32 * i;
         double part = 0.0;
-        if (j0 + 32 <= n) {
-#pragma unroll
-            for (int e = 0; e < 16; e++) {
-                const float ev = (float)exp_nonpos((double)(sc[i][e] - mx));
-                sc[i][e] = ev;
-                part += (double)ev;
-            }
-        } else if (j0 < n) {
-#pragma unroll
+        if (j0 < n) {                                            // (one copy of the exponentials per tile: the clamp, which only a
+#pragma unroll                                                    //  ragged tile needs, costs less than the second copy's instruction fetches)
             for (int e = 0; e < 16; e++) {
                 const float ev = (float)exp_nonpos((double)__builtin_fmaxf(sc[i][e] - mx, -746.0f));
                 sc[i][e] = ev;
