@@ -275,8 +275,10 @@ int run(samp_encoder_t *enc, const void *hidden, const Ids *ids, const int32_t *
         if (mha8) {
             // sequences of at most 128 tokens: the QKV tile of a (sequence, head) is one block tile and all that head's
             // attention needs, so one kernel does both.  It pays from about 128 such blocks per launch (BERT-base, 128
-            // tokens: batch 4 +12 %, 8 +-0, 16 -1.6 %, 32 -4.9 %, 256 -6.8 % on the forward)
-            const bool can_fuse = S <= 128 && !(Y.mode & (SAMP_P_FP16 | SAMP_P_UNSIGNED));
+            // tokens: batch 4 +12 %, 8 +-0, 16 -1.6 %, 32 -4.9 %, 256 -6.8 % on the forward).  The 256-token flavour
+            // (one block per CU, a wave's 64 queries one after the other) loses against the two kernels, whose exact
+            // exponentials run four blocks to a CU (BERT-large 32 x 256: +6 %); it runs only when forced.
+            const bool can_fuse = S <= (enc->fusion_wanted == 2 ? 256 : 128) && !(Y.mode & (SAMP_P_FP16 | SAMP_P_UNSIGNED));
             if (can_fuse && (enc->fusion_wanted == 2 || (enc->fusion_wanted == 0 && B * heads >= 128)))
                 HIP_TRY(launch_qkv_attention_i8((const int8_t *)x, (const int8_t *)Y.w_qkv, Y.m_qkv, Y.bq_qkv, cu, B, S, H, Y.m_sc,
                                                 Y.inv_sp, Y.m_ctx, (int8_t *)w.ctx, st, timing(enc, SAMP_PROF_QKV_ATTN)));
@@ -295,8 +297,9 @@ int run(samp_encoder_t *enc, const void *hidden, const Ids *ids, const int32_t *
                                    nullptr, rows, H, H, st, timing(enc, SAMP_PROF_ATTN_OUT)));
         } else {
             if (am) HIP_TRY(launch_absmax_f16((const __half *)x, rows, H, H, am + 0, st));
-            // (calibration taps q, k, v and the softmax output, so it keeps the two kernels)
-            if (!am && S <= 128 && (enc->fusion_wanted == 2 || (enc->fusion_wanted == 0 && B * heads >= 128))) {
+            // (calibration taps q, k, v and the softmax output, so it keeps the two kernels; with binary32 exponentials
+            //  the 256-token flavour pays as well: BERT-large 32 x 256 with FP16 attention blocks -12.7 %)
+            if (!am && S <= 256 && (enc->fusion_wanted == 2 || (enc->fusion_wanted == 0 && B * heads >= 128))) {
                 HIP_TRY(launch_qkv_attention_f16((const __half *)x, (const __half *)Y.w_qkv, Y.b_qkv, cu, B, S, H, 0.125f,
                                                  (__half *)w.ctx, st, timing(enc, SAMP_PROF_QKV_ATTN)));
             } else {
@@ -843,7 +846,7 @@ int samp_qkv_attention_i8(const int8_t *x, const int8_t *w_qkv, const float *m, 
                           float s_ctx, int8_t *ctx, void *stream)
 {
     if (!x || !w_qkv || !m || !ctx) return fail(SAMP_ERR_ARG, "NULL pointer");
-    if (B < 1 || max_len < 1 || max_len > 128) return fail(SAMP_ERR_SHAPE, "B >= 1 and 1 <= max_len <= 128 required");
+    if (B < 1 || max_len < 1 || max_len > 256) return fail(SAMP_ERR_SHAPE, "B >= 1 and 1 <= max_len <= 256 required");
     if (heads < 1 || hidden != heads * 64) return fail(SAMP_ERR_SHAPE, "head size must be 64");
     if (!aligned(x, 16) || !aligned(w_qkv, 16) || !aligned(ctx, 16) || !aligned(m, 16) || (b && !aligned(b, 16)))
         return fail(SAMP_ERR_ARG, "tensors must be 16-byte aligned");
@@ -861,7 +864,7 @@ int samp_qkv_attention_f16(const uint16_t *x, const uint16_t *w_qkv, const float
                            int32_t max_len, int32_t hidden, int32_t heads, uint16_t *ctx, void *stream)
 {
     if (!x || !w_qkv || !ctx) return fail(SAMP_ERR_ARG, "NULL pointer");
-    if (B < 1 || max_len < 1 || max_len > 128) return fail(SAMP_ERR_SHAPE, "B >= 1 and 1 <= max_len <= 128 required");
+    if (B < 1 || max_len < 1 || max_len > 256) return fail(SAMP_ERR_SHAPE, "B >= 1 and 1 <= max_len <= 256 required");
     if (heads < 1 || hidden != heads * 64) return fail(SAMP_ERR_SHAPE, "head size must be 64");
     if (!aligned(x, 16) || !aligned(w_qkv, 16) || !aligned(ctx, 16)) return fail(SAMP_ERR_ARG, "tensors must be 16-byte aligned");
     HIP_TRY(launch_qkv_attention_f16((const __half *)x, (const __half *)w_qkv, bias, cu, B, max_len, hidden, 0.125f, (__half *)ctx,

@@ -17,6 +17,8 @@
 // operations; exp and the row sum are evaluated in binary64 and rounded once.
 #include "samp_common.h"
 #include "mfma_tile.h"
+
+#include <atomic>
 #include <hip/hip_ext.h>
 
 namespace samp {
@@ -293,9 +295,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
 // layer is gone.  Every value is produced by the same operations in the same order as in the two separate kernels
 // (the row sums are added tile by tile as the four waves' partial sums are there), so the context codes are the same
 // bytes.
+template <int QT>                                          // QT 32-query tiles per wave: sequences of at most 128 QT tokens
 struct QkvTile {                                           // the block tile both flavours of the kernel share
-    static constexpr int TM = 2, TN = 3, BKB = 64, NSTAGE = 3, NWAVES = 4, CH = 4, RPI = 16, KS = 2;
-    static constexpr int BM = 128, BN = 192;
+    static constexpr int TM = 2 * QT, TN = 3, BKB = 64, NSTAGE = 3, NWAVES = 4, CH = 4, RPI = 16, KS = 2;
+    static constexpr int BM = 128 * QT, BN = 192;
     static constexpr int A_BYTES = BM * BKB, STAGE_BYTES = (BM + BN) * BKB, RING_BYTES = NSTAGE * STAGE_BYTES;
     static constexpr int NLD = (BM + BN) / RPI / NWAVES;          // 1 KiB pieces per wave and stage
 };
@@ -308,13 +311,15 @@ struct QkvTile {                                           // the block tile bot
 // register group: exactly a dword (fp16: 8 bytes) of V^T, which the P.V product wants key-contiguous.  The sums are
 // the same (the same products over the same k).  ALL_LIVE: every 32-token tile of the block holds tokens (no tests in
 // the loop).
-template <bool HALF, bool VWAVE, bool ALL_LIVE, class Acc, class LoadTables>
+template <int QT, bool HALF, bool VWAVE, bool ALL_LIVE, class Acc, class LoadTables>
 __device__ __forceinline__ void qkv_tile_gemm(const char *__restrict__ X, const char *__restrict__ W, int t0, int n, int head, int H,
-                                              int Kbytes, char *lds, int wave, int lane, Acc (&acc)[3][2], LoadTables load_tables)
+                                              int Kbytes, char *lds, int wave, int lane, Acc (&acc)[3][2 * QT], LoadTables load_tables)
 {
-    constexpr int TM = QkvTile::TM, TN = QkvTile::TN, BKB = QkvTile::BKB, NSTAGE = QkvTile::NSTAGE, NWAVES = QkvTile::NWAVES;
-    constexpr int CH = QkvTile::CH, RPI = QkvTile::RPI, KS = QkvTile::KS, BM = QkvTile::BM;
-    constexpr int A_BYTES = QkvTile::A_BYTES, STAGE_BYTES = QkvTile::STAGE_BYTES, RING_BYTES = QkvTile::RING_BYTES, NLD = QkvTile::NLD;
+    typedef QkvTile<QT> Tile;
+    constexpr int TM = Tile::TM, TN = Tile::TN, BKB = Tile::BKB, NSTAGE = Tile::NSTAGE, NWAVES = Tile::NWAVES;
+    constexpr int CH = Tile::CH, RPI = Tile::RPI, KS = Tile::KS, BM = Tile::BM;
+    constexpr int A_BYTES = Tile::A_BYTES, STAGE_BYTES = Tile::STAGE_BYTES, RING_BYTES = Tile::RING_BYTES, NLD = Tile::NLD;
+    static_assert((Tile::BM + Tile::BN) % (RPI * NWAVES) == 0, "a stage must split into whole pieces per wave");
     const int wm = (wave >> 1) * 32 * TM, wn = (wave & 1) * 32 * TN;
     const int r = lane & 31, g = lane >> 5;
     // operand rows: the sequence's tokens (rows past its end repeat the last one), and the head's 64 rows of each of
@@ -369,7 +374,9 @@ __device__ __forceinline__ void qkv_tile_gemm(const char *__restrict__ X, const 
         for (int j = 0; j < TM; j++)
 #pragma unroll
             for (int e = 0; e < 16; e++) acc[i][j][e] = 0;
-    const bool rows_live[TM] = {wm < n, wm + 32 < n};             // wave-uniform: token tiles past the sequence's end are not multiplied
+    bool rows_live[TM];                                           // wave-uniform: token tiles past the sequence's end are not multiplied
+#pragma unroll
+    for (int j = 0; j < TM; j++) rows_live[j] = wm + 32 * j < n;
     auto multiply = [&](const v4i (&fa)[TM], const v4i (&fw)[TN]) {
 #pragma unroll
         for (int j = 0; j < TM; j++)
@@ -422,27 +429,29 @@ __device__ __forceinline__ void qkv_tile_gemm(const char *__restrict__ X, const 
 }
 
 // one of four copies of the loop: by wave column (value channels or not) and by whether all token tiles are live
-template <bool HALF, class Acc, class LoadTables>
+template <int QT, bool HALF, class Acc, class LoadTables>
 __device__ __forceinline__ void qkv_tile_gemm_any(const char *__restrict__ X, const char *__restrict__ W, int t0, int n, int head, int H,
-                                                  int Kbytes, char *lds, int wave, int lane, Acc (&acc)[3][2], LoadTables load_tables)
+                                                  int Kbytes, char *lds, int wave, int lane, Acc (&acc)[3][2 * QT], LoadTables load_tables)
 {
-    const bool all_live = n > 96;                                 // block-uniform; wave & 1 is wave-uniform
+    const bool all_live = n > QkvTile<QT>::BM - 32;               // block-uniform; wave & 1 is wave-uniform
     if (wave & 1) {
-        if (all_live) qkv_tile_gemm<HALF, true, true>(X, W, t0, n, head, H, Kbytes, lds, wave, lane, acc, load_tables);
-        else qkv_tile_gemm<HALF, true, false>(X, W, t0, n, head, H, Kbytes, lds, wave, lane, acc, load_tables);
+        if (all_live) qkv_tile_gemm<QT, HALF, true, true>(X, W, t0, n, head, H, Kbytes, lds, wave, lane, acc, load_tables);
+        else qkv_tile_gemm<QT, HALF, true, false>(X, W, t0, n, head, H, Kbytes, lds, wave, lane, acc, load_tables);
     } else {
-        if (all_live) qkv_tile_gemm<HALF, false, true>(X, W, t0, n, head, H, Kbytes, lds, wave, lane, acc, load_tables);
-        else qkv_tile_gemm<HALF, false, false>(X, W, t0, n, head, H, Kbytes, lds, wave, lane, acc, load_tables);
+        if (all_live) qkv_tile_gemm<QT, HALF, false, true>(X, W, t0, n, head, H, Kbytes, lds, wave, lane, acc, load_tables);
+        else qkv_tile_gemm<QT, HALF, false, false>(X, W, t0, n, head, H, Kbytes, lds, wave, lane, acc, load_tables);
     }
 }
 
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+template <int QT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(QT == 1 ? 2 : 1, QT == 1 ? 2 : 1)))
 void qkv_attention_i8_kernel(const char *__restrict__ X, const char *__restrict__ W, const float *__restrict__ m_tab,
                              const float *__restrict__ b_tab, const int *__restrict__ cu, int max_len, int H, float m_sc,
                              float inv_sp, float m_ctx, int8_t *__restrict__ ctx)
 {
-    constexpr int TM = QkvTile::TM, TN = QkvTile::TN, BM = QkvTile::BM, BN = QkvTile::BN, RING_BYTES = QkvTile::RING_BYTES;
-    constexpr int QK_STRIDE = 80, VT_STRIDE = 132;                // bytes per token row of q / k, per channel row of V^T
+    typedef QkvTile<QT> Tile;
+    constexpr int TM = Tile::TM, TN = Tile::TN, BM = Tile::BM, BN = Tile::BN, RING_BYTES = Tile::RING_BYTES, NKT = 4 * QT;
+    constexpr int QK_STRIDE = 80, VT_STRIDE = BM + 4;             // bytes per token row of q / k, per channel row of V^T
     constexpr int Q_OFF = 0, K_OFF = BM * QK_STRIDE, VT_OFF = 2 * BM * QK_STRIDE;
     static_assert(VT_OFF + 64 * VT_STRIDE <= RING_BYTES, "q, k and V^T take the place of the ring");
     extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -459,7 +468,7 @@ void qkv_attention_i8_kernel(const char *__restrict__ X, const char *__restrict_
     const int r = lane & 31, g = lane >> 5;
 
     v16i acc[TN][TM];
-    qkv_tile_gemm_any<false>(X, W, sq.t0, n, head, H, H, lds, wave, lane, acc, [&]() {
+    qkv_tile_gemm_any<QT, false>(X, W, sq.t0, n, head, H, H, lds, wave, lane, acc, [&]() {
         for (int c = tid; c < BN; c += 256) {
             const int col = (c >> 6) * H + head * 64 + (c & 63);
             tab[c] = m_tab[col];
@@ -509,109 +518,112 @@ void qkv_attention_i8_kernel(const char *__restrict__ X, const char *__restrict_
     }
     __syncthreads();
 
-    // attention: this wave's 32 queries against all keys
-    const int q0 = wave * QB;
-    if (q0 >= n) return;                                          // no barrier below
-    v4i qf[2];
+    // attention: this wave's 32 QT queries against all keys, 32 queries at a time
+#pragma unroll 1
+    for (int qt = 0; qt < QT; qt++) {
+        const int q0 = (wave * QT + qt) * QB;
+        if (q0 >= n) break;                                       // no barrier below
+        v4i qf[2];
 #pragma unroll
-    for (int ks = 0; ks < 2; ks++) qf[ks] = *reinterpret_cast<const v4i *>(lds + Q_OFF + (q0 + r) * QK_STRIDE + ks * 32 + g * 16);
-    float sc[4][16];
-    float mx = -INFINITY;
+        for (int ks = 0; ks < 2; ks++) qf[ks] = *reinterpret_cast<const v4i *>(lds + Q_OFF + (q0 + r) * QK_STRIDE + ks * 32 + g * 16);
+        float sc[NKT][16];
+        float mx = -INFINITY;
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-        const int j0 = 32 * i;
-        if (j0 < n) {                                            // wave-uniform
-            v4i kf[2];
+        for (int i = 0; i < NKT; i++) {
+            const int j0 = 32 * i;
+            if (j0 < n) {                                        // wave-uniform
+                v4i kf[2];
 #pragma unroll
-            for (int ks = 0; ks < 2; ks++) kf[ks] = *reinterpret_cast<const v4i *>(lds + K_OFF + (j0 + r) * QK_STRIDE + ks * 32 + g * 16);
-            v16i s;
+                for (int ks = 0; ks < 2; ks++) kf[ks] = *reinterpret_cast<const v4i *>(lds + K_OFF + (j0 + r) * QK_STRIDE + ks * 32 + g * 16);
+                v16i s;
 #pragma unroll
-            for (int e = 0; e < 16; e++) s[e] = 0;
+                for (int e = 0; e < 16; e++) s[e] = 0;
 #pragma unroll
-            for (int ks = 0; ks < 2; ks++) s = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf[ks], qf[ks], s, 0, 0, 0);
-            if (j0 + 32 <= n) {
+                for (int ks = 0; ks < 2; ks++) s = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf[ks], qf[ks], s, 0, 0, 0);
+                if (j0 + 32 <= n) {
 #pragma unroll
-                for (int e = 0; e < 16; e++) {
-                    sc[i][e] = (float)s[e] * m_sc;
-                    mx = __builtin_fmaxf(mx, sc[i][e]);
+                    for (int e = 0; e < 16; e++) {
+                        sc[i][e] = (float)s[e] * m_sc;
+                        mx = __builtin_fmaxf(mx, sc[i][e]);
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 16; e++) {
+                        const int key = j0 + 8 * (e >> 2) + 4 * g + (e & 3);
+                        sc[i][e] = key < n ? (float)s[e] * m_sc : -INFINITY;
+                        mx = __builtin_fmaxf(mx, sc[i][e]);
+                    }
                 }
-            } else {
+            }
+        }
+        mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32, 64));
+
+        // row sums: key tile i adds to partial sum i mod 4, in ascending order, as wave i mod 4 of the attention kernel does
+        double part[4] = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
+        for (int i = 0; i < NKT; i++) {
+            if (32 * i < n) {                                    // (one copy of the exponentials per tile: the clamp, which only a
+#pragma unroll                                                    //  ragged tile needs, costs less than a second copy's instruction fetches)
                 for (int e = 0; e < 16; e++) {
-                    const int key = j0 + 8 * (e >> 2) + 4 * g + (e & 3);
-                    sc[i][e] = key < n ? (float)s[e] * m_sc : -INFINITY;
-                    mx = __builtin_fmaxf(mx, sc[i][e]);
+                    const float ev = (float)exp_nonpos((double)__builtin_fmaxf(sc[i][e] - mx, -746.0f));
+                    sc[i][e] = ev;
+                    part[i & 3] += (double)ev;
                 }
             }
         }
-    }
-    mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32, 64));
-
-    double tile_sum[4];
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-        const int j0 = 32 * i;
-        double part = 0.0;
-        if (j0 < n) {                                            // (one copy of the exponentials per tile: the clamp, which only a
-#pragma unroll                                                    //  ragged tile needs, costs less than the second copy's instruction fetches)
-            for (int e = 0; e < 16; e++) {
-                const float ev = (float)exp_nonpos((double)__builtin_fmaxf(sc[i][e] - mx, -746.0f));
-                sc[i][e] = ev;
-                part += (double)ev;
+        for (int u = 0; u < 4; u++) part[u] += __shfl_xor(part[u], 32, 64);
+        const float S = (float)(((part[0] + part[1]) + part[2]) + part[3]);
+        const float rS = __fdiv_rn(1.0f, S);
+
+        v16i o[2];
+#pragma unroll
+        for (int cb = 0; cb < 2; cb++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) o[cb][e] = opaque_zero();
+#pragma unroll
+        for (int i = 0; i < NKT; i++) {
+            const int j0 = 32 * i;
+            if (j0 < n) {
+                v4i pf;
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    float f[4];
+#pragma unroll
+                    for (int t = 0; t < 4; t++) f[t] = __builtin_amdgcn_fmed3f((sc[i][4 * q + t] * rS) * inv_sp, -127.0f, 127.0f) + SAMP_RNE_MAGIC;
+                    pf[q] = pack_codes(f[0], f[1], f[2], f[3]);
+                }
+#pragma unroll
+                for (int cb = 0; cb < 2; cb++) {
+                    v4i vf;
+#pragma unroll
+                    for (int q = 0; q < 4; q++)
+                        vf[q] = *reinterpret_cast<const int *>(lds + VT_OFF + (cb * 32 + r) * VT_STRIDE + j0 + 8 * q + 4 * g);
+                    o[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, pf, o[cb], 0, 0, 0);   // channels x queries: a lane holds ONE query
+                }
             }
         }
-        tile_sum[i] = part + __shfl_xor(part, 32, 64);
-    }
-    const float S = (float)(((tile_sum[0] + tile_sum[1]) + tile_sum[2]) + tile_sum[3]);
-    const float rS = __fdiv_rn(1.0f, S);
 
-    v16i o[2];
+        // context codes: the lane's query, channels cb*32 + 8q + 4g + t: four codes per dword into the wave's own query rows
+        // in LDS (read into qf above, read by no other wave), from where they leave as 32 bytes per lane
+        char *slab = lds + Q_OFF + q0 * QK_STRIDE;
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
-    for (int cb = 0; cb < 2; cb++)
+        for (int cb = 0; cb < 2; cb++)
 #pragma unroll
-        for (int e = 0; e < 16; e++) o[cb][e] = opaque_zero();
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-        const int j0 = 32 * i;
-        if (j0 < n) {
-            v4i pf;
-#pragma unroll
-            for (int q = 0; q < 4; q++) {
-                float f[4];
-#pragma unroll
-                for (int t = 0; t < 4; t++) f[t] = __builtin_amdgcn_fmed3f((sc[i][4 * q + t] * rS) * inv_sp, -127.0f, 127.0f) + SAMP_RNE_MAGIC;
-                pf[q] = pack_codes(f[0], f[1], f[2], f[3]);
-            }
-#pragma unroll
-            for (int cb = 0; cb < 2; cb++) {
-                v4i vf;
-#pragma unroll
-                for (int q = 0; q < 4; q++)
-                    vf[q] = *reinterpret_cast<const int *>(lds + VT_OFF + (cb * 32 + r) * VT_STRIDE + j0 + 8 * q + 4 * g);
-                o[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, pf, o[cb], 0, 0, 0);   // channels x queries: a lane holds ONE query
-            }
+            for (int q = 0; q < 4; q++)
+                *reinterpret_cast<int *>(slab + r * QK_STRIDE + cb * 32 + 8 * q + 4 * g) =
+                    pack4(qcode((float)o[cb][4 * q] * m_ctx), qcode((float)o[cb][4 * q + 1] * m_ctx), qcode((float)o[cb][4 * q + 2] * m_ctx),
+                          qcode((float)o[cb][4 * q + 3] * m_ctx));
+        __builtin_amdgcn_wave_barrier();
+        const int query = lane >> 1, half = lane & 1;
+        if (q0 + query < n) {
+            const v4i lo = *reinterpret_cast<const v4i *>(slab + query * QK_STRIDE + half * 32);
+            const v4i hi = *reinterpret_cast<const v4i *>(slab + query * QK_STRIDE + half * 32 + 16);
+            int8_t *dst = ctx + (size_t)(sq.t0 + q0 + query) * H + head * 64 + half * 32;
+            *reinterpret_cast<v4i *>(dst) = lo;
+            *reinterpret_cast<v4i *>(dst + 16) = hi;
         }
-    }
-
-    // context codes: the lane's query, channels cb*32 + 8q + 4g + t: four codes per dword into the wave's own query rows
-    // in LDS (read into qf above, read by no other wave), from where they leave as 32 bytes per lane
-    char *slab = lds + Q_OFF + q0 * QK_STRIDE;
-    __builtin_amdgcn_wave_barrier();
-#pragma unroll
-    for (int cb = 0; cb < 2; cb++)
-#pragma unroll
-        for (int q = 0; q < 4; q++)
-            *reinterpret_cast<int *>(slab + r * QK_STRIDE + cb * 32 + 8 * q + 4 * g) =
-                pack4(qcode((float)o[cb][4 * q] * m_ctx), qcode((float)o[cb][4 * q + 1] * m_ctx), qcode((float)o[cb][4 * q + 2] * m_ctx),
-                      qcode((float)o[cb][4 * q + 3] * m_ctx));
-    __builtin_amdgcn_wave_barrier();
-    const int query = lane >> 1, half = lane & 1;
-    if (q0 + query < n) {
-        const v4i lo = *reinterpret_cast<const v4i *>(slab + query * QK_STRIDE + half * 32);
-        const v4i hi = *reinterpret_cast<const v4i *>(slab + query * QK_STRIDE + half * 32 + 16);
-        int8_t *dst = ctx + (size_t)(sq.t0 + q0 + query) * H + head * 64 + half * 32;
-        *reinterpret_cast<v4i *>(dst) = lo;
-        *reinterpret_cast<v4i *>(dst + 16) = hi;
     }
 }
 
@@ -619,16 +631,19 @@ void qkv_attention_i8_kernel(const char *__restrict__ X, const char *__restrict_
 // arithmetic of attention_f16_kernel.  The products P.V of the four key tiles are formed from zero one by one and
 // added in the order in which that kernel adds its four waves' partial contexts (tiles past the end add +0), and the
 // row sums likewise, so the context is the same bytes as from the two kernels.
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+template <int QT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(QT == 1 ? 2 : 1, QT == 1 ? 2 : 1)))
 void qkv_attention_f16_kernel(const char *__restrict__ X, const char *__restrict__ W, const float *__restrict__ bias,
                               const int *__restrict__ cu, int max_len, int H, float scale, __half *__restrict__ ctx)
 {
-    constexpr int TM = QkvTile::TM, TN = QkvTile::TN, BM = QkvTile::BM, BN = QkvTile::BN, RING_BYTES = QkvTile::RING_BYTES;
-    constexpr int QK_STRIDE = 144, VT_STRIDE = 264;               // bytes per token row of q / k (64 fp16 + pad), per channel row of V^T (128 keys + pad)
+    typedef QkvTile<QT> Tile;
+    constexpr int TM = Tile::TM, TN = Tile::TN, BM = Tile::BM, BN = Tile::BN, RING_BYTES = Tile::RING_BYTES, NKT = 4 * QT;
+    constexpr int QK_STRIDE = 144, VT_STRIDE = 2 * BM + 8;        // bytes per token row of q / k (64 fp16 + pad), per channel row of V^T (all keys + pad)
     constexpr int Q_OFF = 0, K_OFF = BM * QK_STRIDE, VT_OFF = 2 * BM * QK_STRIDE;
-    static_assert(VT_OFF + 64 * VT_STRIDE <= RING_BYTES, "q, k and V^T take the place of the ring");
+    constexpr int QKV_BYTES = VT_OFF + 64 * VT_STRIDE;            // q, k and V^T take the place of the ring (and more, for 256 tokens)
+    constexpr int TAB_OFF = QKV_BYTES > RING_BYTES ? QKV_BYTES : RING_BYTES;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
-    float *tab = reinterpret_cast<float *>(lds + RING_BYTES);     // bias of the 192 columns
+    float *tab = reinterpret_cast<float *>(lds + TAB_OFF);        // bias of the 192 columns
 
     const int heads = H >> 6;
     const int item = xcd_contiguous(blockIdx.x, gridDim.x);
@@ -641,7 +656,7 @@ void qkv_attention_f16_kernel(const char *__restrict__ X, const char *__restrict
     const int r = lane & 31, g = lane >> 5;
 
     v16f acc[TN][TM];
-    qkv_tile_gemm_any<true>(X, W, sq.t0, n, head, H, 2 * H, lds, wave, lane, acc, [&]() {
+    qkv_tile_gemm_any<QT, true>(X, W, sq.t0, n, head, H, 2 * H, lds, wave, lane, acc, [&]() {
         for (int c = tid; c < BN; c += 256) tab[c] = bias ? bias[(c >> 6) * H + head * 64 + (c & 63)] : 0.0f;
     });
 
@@ -679,99 +694,106 @@ void qkv_attention_f16_kernel(const char *__restrict__ X, const char *__restrict
     }
     __syncthreads();
 
-    const int q0 = wave * QB;
-    if (q0 >= n) return;                                          // no barrier below
-    v8h qf[4];
+#pragma unroll 1
+    for (int qt = 0; qt < QT; qt++) {
+        const int q0 = (wave * QT + qt) * QB;
+        if (q0 >= n) break;                                       // no barrier below
+        v8h qf[4];
 #pragma unroll
-    for (int ks = 0; ks < 4; ks++) qf[ks] = *reinterpret_cast<const v8h *>(lds + Q_OFF + (q0 + r) * QK_STRIDE + (ks * 16 + g * 8) * 2);
-    float sc[4][16];
-    float mx = -INFINITY;
+        for (int ks = 0; ks < 4; ks++) qf[ks] = *reinterpret_cast<const v8h *>(lds + Q_OFF + (q0 + r) * QK_STRIDE + (ks * 16 + g * 8) * 2);
+        float sc[NKT][16];
+        float mx = -INFINITY;
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-        const int j0 = 32 * i;
-        if (j0 < n) {
-            v16f s;
+        for (int i = 0; i < NKT; i++) {
+            const int j0 = 32 * i;
+            if (j0 < n) {
+                v16f s;
 #pragma unroll
-            for (int e = 0; e < 16; e++) s[e] = 0.0f;
+                for (int e = 0; e < 16; e++) s[e] = 0.0f;
 #pragma unroll
-            for (int ks = 0; ks < 4; ks++)
-                s = __builtin_amdgcn_mfma_f32_32x32x16_f16(*reinterpret_cast<const v8h *>(lds + K_OFF + (j0 + r) * QK_STRIDE + (ks * 16 + g * 8) * 2),
-                                                           qf[ks], s, 0, 0, 0);
+                for (int ks = 0; ks < 4; ks++)
+                    s = __builtin_amdgcn_mfma_f32_32x32x16_f16(*reinterpret_cast<const v8h *>(lds + K_OFF + (j0 + r) * QK_STRIDE + (ks * 16 + g * 8) * 2),
+                                                               qf[ks], s, 0, 0, 0);
+#pragma unroll
+                for (int e = 0; e < 16; e++) {
+                    const int key = j0 + 8 * (e >> 2) + 4 * g + (e & 3);
+                    sc[i][e] = key < n ? s[e] * scale : -INFINITY;
+                    mx = __builtin_fmaxf(mx, sc[i][e]);
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; e++) sc[i][e] = -INFINITY;
+            }
+        }
+        mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32, 64));
+
+        float part[4] = {0.0f, 0.0f, 0.0f, 0.0f};                // key tile i adds to partial sum i mod 4, in ascending order
+#pragma unroll
+        for (int i = 0; i < NKT; i++)
 #pragma unroll
             for (int e = 0; e < 16; e++) {
-                const int key = j0 + 8 * (e >> 2) + 4 * g + (e & 3);
-                sc[i][e] = key < n ? s[e] * scale : -INFINITY;
-                mx = __builtin_fmaxf(mx, sc[i][e]);
+                const float ev = __builtin_amdgcn_exp2f((sc[i][e] - mx) * 1.44269504088896341f);
+                sc[i][e] = ev;
+                part[i & 3] += ev;
             }
-        } else {
 #pragma unroll
-            for (int e = 0; e < 16; e++) sc[i][e] = -INFINITY;
-        }
-    }
-    mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32, 64));
+        for (int u = 0; u < 4; u++) part[u] += __shfl_xor(part[u], 32, 64);
+        const float S = ((part[0] + part[1]) + part[2]) + part[3];
+        const float rS = __fdiv_rn(1.0f, S);
 
-    float tile_sum[4];
+        // partial context u: the key tiles u, u + 4, ... from zero, as wave u of the attention kernel forms it; then added in its order
+        v16f o[2];
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-        float part = 0.0f;
+        for (int u = 0; u < 4; u++) {
+            v16f ot[2];
 #pragma unroll
-        for (int e = 0; e < 16; e++) {
-            const float ev = __builtin_amdgcn_exp2f((sc[i][e] - mx) * 1.44269504088896341f);
-            sc[i][e] = ev;
-            part += ev;
-        }
-        tile_sum[i] = part + __shfl_xor(part, 32, 64);
-    }
-    const float S = ((tile_sum[0] + tile_sum[1]) + tile_sum[2]) + tile_sum[3];
-    const float rS = __fdiv_rn(1.0f, S);
-
-    v16f o[2];
+            for (int cb = 0; cb < 2; cb++)
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-        v16f ot[2];
+                for (int e = 0; e < 16; e++) ot[cb][e] = 0.0f;
 #pragma unroll
-        for (int cb = 0; cb < 2; cb++)
+            for (int ii = 0; ii < QT; ii++) {
+                const int i = u + 4 * ii;
+                if (32 * i < n) {
 #pragma unroll
-            for (int e = 0; e < 16; e++) ot[cb][e] = 0.0f;
-        if (32 * i < n) {
+                    for (int hf = 0; hf < 2; hf++) {                // keys 8q+4g+t for q in {2hf, 2hf+1}
+                        v8h pf;
 #pragma unroll
-            for (int hf = 0; hf < 2; hf++) {                    // keys 8q+4g+t for q in {2hf, 2hf+1}
-                v8h pf;
+                        for (int e = 0; e < 8; e++) pf[e] = to_half(sc[i][8 * hf + e] * rS);
 #pragma unroll
-                for (int e = 0; e < 8; e++) pf[e] = to_half(sc[i][8 * hf + e] * rS);
-#pragma unroll
-                for (int cb = 0; cb < 2; cb++) {
-                    const char *rowp = lds + VT_OFF + (cb * 32 + r) * VT_STRIDE + 32 * i * 2;
-                    const v4h lo = *reinterpret_cast<const v4h *>(rowp + (16 * hf + 4 * g) * 2);
-                    const v4h hi = *reinterpret_cast<const v4h *>(rowp + (16 * hf + 8 + 4 * g) * 2);
-                    const v8h vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                    ot[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf, ot[cb], 0, 0, 0);   // channels x queries: a lane holds ONE query
+                        for (int cb = 0; cb < 2; cb++) {
+                            const char *rowp = lds + VT_OFF + (cb * 32 + r) * VT_STRIDE + 32 * i * 2;
+                            const v4h lo = *reinterpret_cast<const v4h *>(rowp + (16 * hf + 4 * g) * 2);
+                            const v4h hi = *reinterpret_cast<const v4h *>(rowp + (16 * hf + 8 + 4 * g) * 2);
+                            const v8h vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                            ot[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf, ot[cb], 0, 0, 0);   // channels x queries: a lane holds ONE query
+                        }
+                    }
                 }
             }
+#pragma unroll
+            for (int cb = 0; cb < 2; cb++)
+#pragma unroll
+                for (int e = 0; e < 16; e++) o[cb][e] = u == 0 ? ot[cb][e] : o[cb][e] + ot[cb][e];
         }
+
+        // context: the lane's query, channels cb*32 + 8q + 4g + t; through the wave's own query rows in LDS, out as 64 bytes per lane
+        char *slab = lds + Q_OFF + q0 * QK_STRIDE;
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int cb = 0; cb < 2; cb++)
 #pragma unroll
-            for (int e = 0; e < 16; e++) o[cb][e] = i == 0 ? ot[cb][e] : o[cb][e] + ot[cb][e];
-    }
-
-    // context: the lane's query, channels cb*32 + 8q + 4g + t; through the wave's own query rows in LDS, out as 64 bytes per lane
-    char *slab = lds + Q_OFF + q0 * QK_STRIDE;
-    __builtin_amdgcn_wave_barrier();
+            for (int q = 0; q < 4; q++) {
+                const v4h h = {to_half(o[cb][4 * q]), to_half(o[cb][4 * q + 1]), to_half(o[cb][4 * q + 2]), to_half(o[cb][4 * q + 3])};
+                *reinterpret_cast<v4h *>(slab + r * QK_STRIDE + (cb * 32 + 8 * q + 4 * g) * 2) = h;
+            }
+        __builtin_amdgcn_wave_barrier();
+        const int query = lane >> 1, half = lane & 1;
+        if (q0 + query < n) {
+            __half *dst = ctx + (size_t)(sq.t0 + q0 + query) * H + head * 64 + half * 32;
 #pragma unroll
-    for (int cb = 0; cb < 2; cb++)
-#pragma unroll
-        for (int q = 0; q < 4; q++) {
-            const v4h h = {to_half(o[cb][4 * q]), to_half(o[cb][4 * q + 1]), to_half(o[cb][4 * q + 2]), to_half(o[cb][4 * q + 3])};
-            *reinterpret_cast<v4h *>(slab + r * QK_STRIDE + (cb * 32 + 8 * q + 4 * g) * 2) = h;
+            for (int u = 0; u < 4; u++)
+                *reinterpret_cast<v4i *>(dst + u * 8) = *reinterpret_cast<const v4i *>(slab + query * QK_STRIDE + half * 64 + u * 16);
         }
-    __builtin_amdgcn_wave_barrier();
-    const int query = lane >> 1, half = lane & 1;
-    if (q0 + query < n) {
-        __half *dst = ctx + (size_t)(sq.t0 + q0 + query) * H + head * 64 + half * 32;
-#pragma unroll
-        for (int u = 0; u < 4; u++)
-            *reinterpret_cast<v4i *>(dst + u * 8) = *reinterpret_cast<const v4i *>(slab + query * QK_STRIDE + half * 64 + u * 16);
     }
 }
 
@@ -1421,20 +1443,49 @@ hipError_t launch_qkv_attention_i8(const int8_t *x, const int8_t *w_qkv, const f
                                    int max_len, int H, float m_sc, float inv_sp, float m_ctx, int8_t *ctx, hipStream_t st,
                                    const Timing *tm)
 {
-    if (max_len > 128 || H % 64 || B <= 0) return hipErrorInvalidValue;
-    const size_t lds = 3 * (128 + 192) * 64 + 2 * 192 * sizeof(float);
-    launch_kernel(qkv_attention_i8_kernel, dim3((unsigned)(B * (H / 64))), dim3(256), lds, st, tm, (const char *)x,
-                  (const char *)w_qkv, m, b, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx);
+    if (max_len > 256 || H % 64 || B <= 0) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)(B * (H / 64)));
+    if (max_len <= 128) {
+        const size_t lds = QkvTile<1>::RING_BYTES + 2 * 192 * sizeof(float);
+        launch_kernel(qkv_attention_i8_kernel<1>, grid, dim3(256), lds, st, tm, (const char *)x, (const char *)w_qkv, m, b, cu,
+                      max_len, H, m_sc, inv_sp, m_ctx, ctx);
+    } else {
+        const size_t lds = QkvTile<2>::RING_BYTES + 2 * 192 * sizeof(float);
+        static std::atomic<bool> attr_set{false};
+        if (!attr_set.load(std::memory_order_acquire)) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(qkv_attention_i8_kernel<2>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            attr_set.store(true, std::memory_order_release);
+        }
+        launch_kernel(qkv_attention_i8_kernel<2>, grid, dim3(256), lds, st, tm, (const char *)x, (const char *)w_qkv, m, b, cu,
+                      max_len, H, m_sc, inv_sp, m_ctx, ctx);
+    }
     return hipGetLastError();
 }
 
 hipError_t launch_qkv_attention_f16(const __half *x, const __half *w_qkv, const float *bias, const int *cu, int B, int max_len,
                                     int H, float scale, __half *ctx, hipStream_t st, const Timing *tm)
 {
-    if (max_len > 128 || H % 64 || B <= 0) return hipErrorInvalidValue;
-    const size_t lds = 3 * (128 + 192) * 64 + 192 * sizeof(float);
-    launch_kernel(qkv_attention_f16_kernel, dim3((unsigned)(B * (H / 64))), dim3(256), lds, st, tm, (const char *)x,
-                  (const char *)w_qkv, bias, cu, max_len, H, scale, ctx);
+    if (max_len > 256 || H % 64 || B <= 0) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)(B * (H / 64)));
+    if (max_len <= 128) {
+        const size_t lds = QkvTile<1>::RING_BYTES + 192 * sizeof(float);
+        launch_kernel(qkv_attention_f16_kernel<1>, grid, dim3(256), lds, st, tm, (const char *)x, (const char *)w_qkv, bias, cu,
+                      max_len, H, scale, ctx);
+    } else {
+        constexpr size_t qkv_bytes = 2 * 256 * 144 + 64 * (2 * 256 + 8);
+        const size_t lds = (qkv_bytes > (size_t)QkvTile<2>::RING_BYTES ? qkv_bytes : (size_t)QkvTile<2>::RING_BYTES) + 192 * sizeof(float);
+        static std::atomic<bool> attr_set{false};
+        if (!attr_set.load(std::memory_order_acquire)) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(qkv_attention_f16_kernel<2>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            attr_set.store(true, std::memory_order_release);
+        }
+        launch_kernel(qkv_attention_f16_kernel<2>, grid, dim3(256), lds, st, tm, (const char *)x, (const char *)w_qkv, bias, cu,
+                      max_len, H, scale, ctx);
+    }
     return hipGetLastError();
 }
 

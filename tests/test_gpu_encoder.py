@@ -156,11 +156,11 @@ def test_small_encoder_every_mode(P, mode, varlen):
 
 @pytest.mark.parametrize("modes", [(FULL_INT8,) * 3, (MHA_INT8, FULL_INT8, FP16), (FULL_INT8 | P_UNSIGNED, FULL_INT8, FULL_INT8 | P_FP16),
                                    (FP16,) * 3, (FFN_INT8, FP16, FULL_INT8)])
-@pytest.mark.parametrize("varlen", [False, True])
-def test_small_encoder_with_qkv_gemm_and_attention_in_one_kernel(P, modes, varlen):
+@pytest.mark.parametrize("varlen,seq", [(False, 128), (True, 128), (True, 256), (False, 192)])
+def test_small_encoder_with_qkv_gemm_and_attention_in_one_kernel(P, modes, varlen, seq):
     """Forcing the kernel that does the QKV GEMM and the attention at once (small batches do not take it by themselves)
-    changes no byte of the output, on sequences of 1 to 128 tokens, and the Fully-Quant stack stays the oracle's."""
-    w = small(modes, batch=7, seq=128, varlen=varlen)
+    changes no byte of the output, on sequences of 1 to 256 tokens, and the Fully-Quant stack stays the oracle's."""
+    w = small(modes, batch=7 if seq == 128 else 4, seq=seq, varlen=varlen)
     wts = W.make_weights(w)
     hid, lens, mask = W.make_hidden(w)
     sc = oracle.calibrate(*args(w), wts, W.make_calibration_batch(w))

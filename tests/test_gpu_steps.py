@@ -280,7 +280,8 @@ def test_int8_attention_bit_exact(P, lens, heads):
 
 
 @pytest.mark.parametrize("lens,heads,offsets", [([128, 128, 128], 2, False), ([1, 5, 32, 33, 64, 17, 128, 97], 3, True),
-                                                ([96] * 4, 1, False), ([128, 2, 65], 12, True), ([31], 16, True)])
+                                                ([96] * 4, 1, False), ([128, 2, 65], 12, True), ([31], 16, True),
+                                                ([256, 256], 2, False), ([200, 129, 256, 7, 160], 3, True), ([192] * 3, 4, False)])
 def test_qkv_gemm_and_attention_in_one_kernel_bit_exact(P, lens, heads, offsets):
     """The kernel that does the QKV GEMM, its requantisation and the attention of a (sequence, head) at once gives the
     oracle's requantised GEMM followed by the oracle's attention, and the bytes of the two separate kernels."""
@@ -416,7 +417,8 @@ def test_fp16_attention_within_tolerance(P, lens, heads):
 
 
 @pytest.mark.parametrize("lens,heads,offsets", [([128, 128, 128], 2, False), ([1, 5, 32, 33, 64, 17, 128, 97], 2, True),
-                                                ([128, 2, 65], 12, True), ([96] * 3, 4, False)])
+                                                ([128, 2, 65], 12, True), ([96] * 3, 4, False),
+                                                ([256, 256], 2, False), ([200, 129, 256, 7, 160], 2, True), ([192] * 3, 4, False)])
 def test_fp16_qkv_gemm_and_attention_in_one_kernel(P, lens, heads, offsets):
     """The FP16 kernel that does the QKV GEMM and the attention at once: the bytes of the two separate kernels, and the
     oracle's GEMM + attention within the tolerance of those kernels."""
