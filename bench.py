@@ -273,7 +273,10 @@ def main() -> int:
                     "traffic": measured_traffic(a.workload, name, "ffn1", tokens_per_launch),
                     "algorithmic_bytes": (T * w0.hidden + T * w0.ffn) / (per_forward / w0.layers) + w0.ffn * w0.hidden,
                     "launches_timed": launches, "launches_per_step": per_forward, "tokens_per_launch": tokens_per_launch,
-                    "mean_launch_us": kms * 1e3, "ops_per_launch": ops}
+                    "mean_launch_us": kms * 1e3, "ops_per_launch": ops,
+                    "choice": "the largest dense contraction of a step (2 T F H operations per layer); where the QKV GEMM and the "
+                              "attention run as one kernel, that mixed kernel (GEMM + softmax) can take longer per launch: its "
+                              "figures are kernels.qkv_attention"}
             kernels = kernel_table(P, enc, hid, mask, out, w0, modes, lens, a.steps, torch)
         elif mode == P.FP16:
             kernels_fp16 = kernel_table(P, enc, hid, mask, out, w0, modes, lens, a.steps, torch)
