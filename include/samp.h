@@ -177,7 +177,7 @@ SAMP_API int samp_encoder_set_groups(samp_encoder_t *enc, int32_t groups);
 
 /* Section 3.2 hands the QKV GEMM's requantised int8 output straight to the attention; for sequences of at
  * most 256 tokens one kernel can do both per (sequence, head), so that q, k, v never reach memory and a layer
- * has one launch less (INT8 blocks with symmetric int8 softmax codes, and FP16 blocks outside calibration).
+ * has one launch less (INT8 blocks with int8 softmax codes, signed or unsigned, and FP16 blocks outside calibration).
  * mode 0 (default): used where it measured faster (at least 128 (sequence, head) pairs per launch; INT8 blocks
  * up to 128 tokens, FP16 blocks up to 256); 1: never; 2: whenever the shape allows.  The context is the same
  * bytes either way.                                                                                       */
@@ -331,14 +331,15 @@ SAMP_API int samp_gemm_f16(const uint16_t *A, const uint16_t *W, const float *bi
 SAMP_API int samp_attention_i8(const int8_t *qkv, const int32_t *cu_seqlens, int32_t B, int32_t max_len, int32_t hidden,
                                int32_t heads, float s_q, float s_k, float s_v, float s_p, float s_ctx, int32_t p_kind,
                                int8_t *ctx, uint64_t *p_hist, void *stream);
-/* QKV GEMM, its requantisation and the INT8 attention (p_kind 0) of sequences of at most 256 tokens in one kernel
+/* QKV GEMM, its requantisation and the INT8 attention (p_kind 0 or 1) of sequences of at most 256 tokens in one kernel
  * (Section 3.2: the same two steps, the q, k, v codes staying on chip): x dev int8 [T,hidden] packed rows,
  * w_qkv dev int8 [3 hidden, hidden] (rows [0,H) Q, [H,2H) K, [2H,3H) V), m and b dev float [3 hidden] as in
  * samp_gemm_i8_requant (b NULL = zeros); cu_seqlens, B, max_len <= 256, scales and ctx as in samp_attention_i8.
  * ctx equals samp_gemm_i8_requant followed by samp_attention_i8 byte for byte.                              */
 SAMP_API int samp_qkv_attention_i8(const int8_t *x, const int8_t *w_qkv, const float *m, const float *b,
                                    const int32_t *cu_seqlens, int32_t B, int32_t max_len, int32_t hidden, int32_t heads,
-                                   float s_q, float s_k, float s_v, float s_p, float s_ctx, int8_t *ctx, void *stream);
+                                   float s_q, float s_k, float s_v, float s_p, float s_ctx, int32_t p_kind, int8_t *ctx,
+                                   void *stream);
 /* The FP16 counterpart: out = samp_gemm_f16(x, w_qkv, bias, no GELU) followed by samp_attention_f16, in one kernel,
  * byte for byte.  x dev fp16 [T,hidden], w_qkv dev fp16 [3 hidden, hidden], bias dev float [3 hidden] or NULL.  */
 SAMP_API int samp_qkv_attention_f16(const uint16_t *x, const uint16_t *w_qkv, const float *bias, const int32_t *cu_seqlens,

@@ -308,13 +308,13 @@ def attention_i8(qkv, cu, max_len: int, heads: int, s_q, s_k, s_v, s_p, s_ctx, p
     return (ctx, hist) if want_hist else ctx
 
 
-def qkv_attention_i8(x, w_qkv, m, b, cu, max_len: int, heads: int, s_q, s_k, s_v, s_p, s_ctx):
+def qkv_attention_i8(x, w_qkv, m, b, cu, max_len: int, heads: int, s_q, s_k, s_v, s_p, s_ctx, p_unsigned: bool = False):
     """samp_qkv_attention_i8: ctx [T, H] int8 from packed int8 rows x [T, H] and the int8 QKV weights [3H, H]."""
     T, H = x.shape
     B = _batch_of(cu, T, max_len)
     ctx = torch.zeros((T, H), dtype=torch.int8, device=x.device)
     _check(lib().samp_qkv_attention_i8(_dp(x), _dp(w_qkv), _dp(m), _dp(b), _dp(cu), B, max_len, H, heads, _f(s_q), _f(s_k),
-                                       _f(s_v), _f(s_p), _f(s_ctx), _dp(ctx), _stream()))
+                                       _f(s_v), _f(s_p), _f(s_ctx), int(bool(p_unsigned)), _dp(ctx), _stream()))
     return ctx
 
 

@@ -278,10 +278,11 @@ int run(samp_encoder_t *enc, const void *hidden, const Ids *ids, const int32_t *
             // tokens: batch 4 +12 %, 8 +-0, 16 -1.6 %, 32 -4.9 %, 256 -6.8 % on the forward).  The 256-token flavour
             // (one block per CU, a wave's 64 queries one after the other) loses against the two kernels, whose exact
             // exponentials run four blocks to a CU (BERT-large 32 x 256: +6 %); it runs only when forced.
-            const bool can_fuse = S <= (enc->fusion_wanted == 2 ? 256 : 128) && !(Y.mode & (SAMP_P_FP16 | SAMP_P_UNSIGNED));
+            const bool can_fuse = S <= (enc->fusion_wanted == 2 ? 256 : 128) && !(Y.mode & SAMP_P_FP16);
             if (can_fuse && (enc->fusion_wanted == 2 || (enc->fusion_wanted == 0 && B * heads >= 128)))
                 HIP_TRY(launch_qkv_attention_i8((const int8_t *)x, (const int8_t *)Y.w_qkv, Y.m_qkv, Y.bq_qkv, cu, B, S, H, Y.m_sc,
-                                                Y.inv_sp, Y.m_ctx, (int8_t *)w.ctx, st, timing(enc, SAMP_PROF_QKV_ATTN)));
+                                                Y.inv_sp, Y.m_ctx, (Y.mode & SAMP_P_UNSIGNED) != 0, (int8_t *)w.ctx, st,
+                                                timing(enc, SAMP_PROF_QKV_ATTN)));
             else {
                 HIP_TRY(launch_gemm_i8(EPI_REQUANT, (const int8_t *)x, (const int8_t *)Y.w_qkv, w.qkv, Y.m_qkv, Y.bq_qkv, 0.f,
                                        nullptr, rows, 3 * H, H, st, timing(enc, SAMP_PROF_QKV)));
@@ -843,8 +844,9 @@ int samp_attention_i8(const int8_t *qkv, const int32_t *cu, int32_t B, int32_t m
 
 int samp_qkv_attention_i8(const int8_t *x, const int8_t *w_qkv, const float *m, const float *b, const int32_t *cu, int32_t B,
                           int32_t max_len, int32_t hidden, int32_t heads, float s_q, float s_k, float s_v, float s_p,
-                          float s_ctx, int8_t *ctx, void *stream)
+                          float s_ctx, int32_t p_kind, int8_t *ctx, void *stream)
 {
+    if (p_kind < 0 || p_kind > 1) return fail(SAMP_ERR_ARG, "p_kind must be 0 or 1");
     if (!x || !w_qkv || !m || !ctx) return fail(SAMP_ERR_ARG, "NULL pointer");
     if (B < 1 || max_len < 1 || max_len > 256) return fail(SAMP_ERR_SHAPE, "B >= 1 and 1 <= max_len <= 256 required");
     if (heads < 1 || hidden != heads * 64) return fail(SAMP_ERR_SHAPE, "head size must be 64");
@@ -855,8 +857,8 @@ int samp_qkv_attention_i8(const int8_t *x, const int8_t *w_qkv, const float *m, 
     const float m_sc = (float)((double)s_q * (double)s_k / std::sqrt(64.0));
     if (!good_score_multiplier(m_sc)) return fail(SAMP_ERR_SCALE, "s_q * s_k / 8 must not exceed %g", (double)MAX_SCORE_MULTIPLIER);
     const float m_ctx = (float)((double)s_p * (double)s_v / (double)s_ctx);
-    HIP_TRY(launch_qkv_attention_i8(x, w_qkv, m, b, cu, B, max_len, hidden, m_sc, 1.0f / s_p, m_ctx, ctx, (hipStream_t)stream,
-                                    nullptr));
+    HIP_TRY(launch_qkv_attention_i8(x, w_qkv, m, b, cu, B, max_len, hidden, m_sc, 1.0f / s_p, m_ctx, p_kind == 1, ctx,
+                                    (hipStream_t)stream, nullptr));
     return SAMP_OK;
 }
 

@@ -443,7 +443,7 @@ __device__ __forceinline__ void qkv_tile_gemm_any(const char *__restrict__ X, co
     }
 }
 
-template <int QT>
+template <int QT, bool PU>                                 // PU: unsigned softmax codes, as in attention_i8_kernel
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(QT == 1 ? 2 : 1, QT == 1 ? 2 : 1)))
 void qkv_attention_i8_kernel(const char *__restrict__ X, const char *__restrict__ W, const float *__restrict__ m_tab,
                              const float *__restrict__ b_tab, const int *__restrict__ cu, int max_len, int H, float m_sc,
@@ -576,11 +576,13 @@ void qkv_attention_i8_kernel(const char *__restrict__ X, const char *__restrict_
         const float S = (float)(((part[0] + part[1]) + part[2]) + part[3]);
         const float rS = __fdiv_rn(1.0f, S);
 
-        v16i o[2];
+        v16i o[2], o1[PU ? 2 : 1];
 #pragma unroll
         for (int cb = 0; cb < 2; cb++)
 #pragma unroll
-            for (int e = 0; e < 16; e++) o[cb][e] = opaque_zero();
+            for (int e = 0; e < 16; e++) { o[cb][e] = opaque_zero(); if (PU) o1[cb][e] = opaque_zero(); }
+        const float lo = PU ? 0.0f : -127.0f, hi = PU ? 255.0f : 127.0f;
+        const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
 #pragma unroll
         for (int i = 0; i < NKT; i++) {
             const int j0 = 32 * i;
@@ -590,8 +592,9 @@ void qkv_attention_i8_kernel(const char *__restrict__ X, const char *__restrict_
                 for (int q = 0; q < 4; q++) {
                     float f[4];
 #pragma unroll
-                    for (int t = 0; t < 4; t++) f[t] = __builtin_amdgcn_fmed3f((sc[i][4 * q + t] * rS) * inv_sp, -127.0f, 127.0f) + SAMP_RNE_MAGIC;
+                    for (int t = 0; t < 4; t++) f[t] = __builtin_amdgcn_fmed3f((sc[i][4 * q + t] * rS) * inv_sp, lo, hi) + SAMP_RNE_MAGIC;
                     pf[q] = pack_codes(f[0], f[1], f[2], f[3]);
+                    if (PU) pf[q] ^= (int)0x80808080u;             // code - 128 as a signed byte
                 }
 #pragma unroll
                 for (int cb = 0; cb < 2; cb++) {
@@ -600,10 +603,17 @@ void qkv_attention_i8_kernel(const char *__restrict__ X, const char *__restrict_
                     for (int q = 0; q < 4; q++)
                         vf[q] = *reinterpret_cast<const int *>(lds + VT_OFF + (cb * 32 + r) * VT_STRIDE + j0 + 8 * q + 4 * g);
                     o[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, pf, o[cb], 0, 0, 0);   // channels x queries: a lane holds ONE query
+                    if (PU) o1[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, ones, o1[cb], 0, 0, 0);   // 128 times this is added back below
                 }
             }
         }
 
+        if (PU) {
+#pragma unroll
+            for (int cb = 0; cb < 2; cb++)
+#pragma unroll
+                for (int e = 0; e < 16; e++) o[cb][e] += o1[cb][e] * 128;
+        }
         // context codes: the lane's query, channels cb*32 + 8q + 4g + t: four codes per dword into the wave's own query rows
         // in LDS (read into qf above, read by no other wave), from where they leave as 32 bytes per lane
         char *slab = lds + Q_OFF + q0 * QK_STRIDE;
@@ -1439,29 +1449,36 @@ hipError_t launch_attention_i8(const int8_t *qkv, const int *cu, int B, int max_
     return hipGetLastError();
 }
 
-hipError_t launch_qkv_attention_i8(const int8_t *x, const int8_t *w_qkv, const float *m, const float *b, const int *cu, int B,
-                                   int max_len, int H, float m_sc, float inv_sp, float m_ctx, int8_t *ctx, hipStream_t st,
-                                   const Timing *tm)
+template <int QT, bool PU>
+static hipError_t launch_qkv_attention_i8_variant(const int8_t *x, const int8_t *w_qkv, const float *m, const float *b, const int *cu,
+                                                  int B, int max_len, int H, float m_sc, float inv_sp, float m_ctx, int8_t *ctx,
+                                                  hipStream_t st, const Timing *tm)
 {
-    if (max_len > 256 || H % 64 || B <= 0) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)(B * (H / 64)));
-    if (max_len <= 128) {
-        const size_t lds = QkvTile<1>::RING_BYTES + 2 * 192 * sizeof(float);
-        launch_kernel(qkv_attention_i8_kernel<1>, grid, dim3(256), lds, st, tm, (const char *)x, (const char *)w_qkv, m, b, cu,
-                      max_len, H, m_sc, inv_sp, m_ctx, ctx);
-    } else {
-        const size_t lds = QkvTile<2>::RING_BYTES + 2 * 192 * sizeof(float);
+    const size_t lds = QkvTile<QT>::RING_BYTES + 2 * 192 * sizeof(float);
+    if (lds > 64 * 1024) {
         static std::atomic<bool> attr_set{false};
         if (!attr_set.load(std::memory_order_acquire)) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(qkv_attention_i8_kernel<2>),
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(qkv_attention_i8_kernel<QT, PU>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
             attr_set.store(true, std::memory_order_release);
         }
-        launch_kernel(qkv_attention_i8_kernel<2>, grid, dim3(256), lds, st, tm, (const char *)x, (const char *)w_qkv, m, b, cu,
-                      max_len, H, m_sc, inv_sp, m_ctx, ctx);
     }
+    launch_kernel(qkv_attention_i8_kernel<QT, PU>, dim3((unsigned)(B * (H / 64))), dim3(256), lds, st, tm, (const char *)x,
+                  (const char *)w_qkv, m, b, cu, max_len, H, m_sc, inv_sp, m_ctx, ctx);
     return hipGetLastError();
+}
+
+hipError_t launch_qkv_attention_i8(const int8_t *x, const int8_t *w_qkv, const float *m, const float *b, const int *cu, int B,
+                                   int max_len, int H, float m_sc, float inv_sp, float m_ctx, bool p_unsigned, int8_t *ctx,
+                                   hipStream_t st, const Timing *tm)
+{
+    if (max_len > 256 || H % 64 || B <= 0) return hipErrorInvalidValue;
+    if (max_len <= 128)
+        return p_unsigned ? launch_qkv_attention_i8_variant<1, true>(x, w_qkv, m, b, cu, B, max_len, H, m_sc, inv_sp, m_ctx, ctx, st, tm)
+                          : launch_qkv_attention_i8_variant<1, false>(x, w_qkv, m, b, cu, B, max_len, H, m_sc, inv_sp, m_ctx, ctx, st, tm);
+    return p_unsigned ? launch_qkv_attention_i8_variant<2, true>(x, w_qkv, m, b, cu, B, max_len, H, m_sc, inv_sp, m_ctx, ctx, st, tm)
+                      : launch_qkv_attention_i8_variant<2, false>(x, w_qkv, m, b, cu, B, max_len, H, m_sc, inv_sp, m_ctx, ctx, st, tm);
 }
 
 hipError_t launch_qkv_attention_f16(const __half *x, const __half *w_qkv, const float *bias, const int *cu, int B, int max_len,

@@ -185,8 +185,8 @@ hipError_t launch_attention_i8(const int8_t *qkv, const int *cu, int B, int max_
                                float inv_sp, float m_ctx, bool p_unsigned, int8_t *ctx, unsigned long long *p_hist,
                                hipStream_t st, const Timing *tm);
 hipError_t launch_qkv_attention_i8(const int8_t *x, const int8_t *w_qkv, const float *m, const float *b, const int *cu, int B,
-                                   int max_len, int H, float m_sc, float inv_sp, float m_ctx, int8_t *ctx, hipStream_t st,
-                                   const Timing *tm);
+                                   int max_len, int H, float m_sc, float inv_sp, float m_ctx, bool p_unsigned, int8_t *ctx,
+                                   hipStream_t st, const Timing *tm);
 hipError_t launch_qkv_attention_f16(const __half *x, const __half *w_qkv, const float *bias, const int *cu, int B, int max_len,
                                     int H, float scale, __half *ctx, hipStream_t st, const Timing *tm);
 hipError_t launch_code_histogram(const int8_t *codes, size_t n, unsigned long long *hist, hipStream_t st);

@@ -109,10 +109,11 @@ def test_later_entry_points_reject_bad_arguments_on_the_host(L):
     assert b"256" in L.samp_last_error()
     # the kernel that does the QKV GEMM and the attention at once: sequences of at most 128 tokens, head size 64
     f1 = C.c_float(0.02)
-    assert L.samp_qkv_attention_i8(None, ptr, ptr, None, cu, 1, 16, 128, 2, f1, f1, f1, f1, f1, ptr, None) == -1
-    assert L.samp_qkv_attention_i8(ptr, ptr, ptr, None, cu, 1, 257, 128, 2, f1, f1, f1, f1, f1, ptr, None) == -2
-    assert L.samp_qkv_attention_i8(ptr, ptr, ptr, None, cu, 1, 16, 100, 2, f1, f1, f1, f1, f1, ptr, None) == -2
-    assert L.samp_qkv_attention_i8(ptr, ptr, ptr, None, cu, 1, 16, 128, 2, C.c_float(64), C.c_float(64), f1, f1, f1, ptr, None) == -5
+    assert L.samp_qkv_attention_i8(None, ptr, ptr, None, cu, 1, 16, 128, 2, f1, f1, f1, f1, f1, 0, ptr, None) == -1
+    assert L.samp_qkv_attention_i8(ptr, ptr, ptr, None, cu, 1, 257, 128, 2, f1, f1, f1, f1, f1, 0, ptr, None) == -2
+    assert L.samp_qkv_attention_i8(ptr, ptr, ptr, None, cu, 1, 16, 100, 2, f1, f1, f1, f1, f1, 0, ptr, None) == -2
+    assert L.samp_qkv_attention_i8(ptr, ptr, ptr, None, cu, 1, 16, 128, 2, f1, f1, f1, f1, f1, 2, ptr, None) == -1   # no binary16 softmax output here
+    assert L.samp_qkv_attention_i8(ptr, ptr, ptr, None, cu, 1, 16, 128, 2, C.c_float(64), C.c_float(64), f1, f1, f1, 0, ptr, None) == -5
     assert L.samp_encoder_set_qkv_fusion(None, 0) == -1
     assert L.samp_qkv_attention_f16(ptr, ptr, None, cu, 1, 257, 128, 2, ptr, None) == -2
     assert L.samp_qkv_attention_f16(ptr, None, None, cu, 1, 16, 128, 2, ptr, None) == -1

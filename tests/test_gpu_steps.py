@@ -305,6 +305,9 @@ def test_qkv_gemm_and_attention_in_one_kernel_bit_exact(P, lens, heads, offsets)
         two = host(P.attention_i8(P.gemm_i8_requant(dev(x), dev(w), dev(m), dev(b)), cu_dev, max(lens), heads, *sc))
         assert np.array_equal(two, want)
     assert np.abs(want).max() > 20
+    scu = (sc[0], sc[1], sc[2], sc[3] * 0.5, sc[4])                   # unsigned softmax codes: twice the levels
+    unsigned = host(P.qkv_attention_i8(dev(x), dev(w), dev(m), dev(b), cu_dev, max(lens), heads, *scu, p_unsigned=True))
+    assert np.array_equal(unsigned, oracle.attention_i8(qkv, cu, heads, *scu, p_unsigned=True))
     no_bias = host(P.qkv_attention_i8(dev(x), dev(w), dev(m), None, cu_dev, max(lens), heads, *sc))
     assert np.array_equal(no_bias, oracle.attention_i8(oracle.epilogue_requant(oracle.gemm_i8_i32(x, w), m, np.zeros(3 * H, np.float32)), cu, heads, *sc))
 
