@@ -291,10 +291,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
 // is all that head's attention needs (Section 3.2: the QKV GEMM's requantised int8 output is the attention's only
 // input).  The block therefore runs that GEMM's main loop (three-deep ring of 64-byte stages, direct global->LDS
 // loads, wave tiles of 64 x 96), requantises q, k, v into LDS where the ring was, and goes on as the attention
-// kernel above does, one wave per 32 queries over all keys: the q, k, v codes never reach memory and one launch per
-// layer is gone.  Every value is produced by the same operations in the same order as in the two separate kernels
-// (the row sums are added tile by tile as the four waves' partial sums are there), so the context codes are the same
-// bytes.
+// kernels above do, one wave per 32 queries over all keys: q, k, v never reach memory and one launch per layer is
+// gone.  Every value is produced by the same operations in the same order as in the two separate kernels (row sums
+// and, for FP16, partial contexts are accumulated per key tile modulo 4 in ascending order, which is how the four
+// waves of those kernels form them), so the context is the same bytes.  QT = 2 is the same for up to 256 tokens: a
+// 256 x 192 block tile, wave tiles of 128 x 96, a wave's 64 queries 32 at a time.
 template <int QT>                                          // QT 32-query tiles per wave: sequences of at most 128 QT tokens
 struct QkvTile {                                           // the block tile both flavours of the kernel share
     static constexpr int TM = 2 * QT, TN = 3, BKB = 64, NSTAGE = 3, NWAVES = 4, CH = 4, RPI = 16, KS = 2;
@@ -303,7 +304,7 @@ struct QkvTile {                                           // the block tile bot
     static constexpr int NLD = (BM + BN) / RPI / NWAVES;          // 1 KiB pieces per wave and stage
 };
 
-// The GEMM part: the wave's 64 x 96 accumulators of X[t0 .. t0+n) . W_head^T, rows of Kbytes bytes; HALF: fp16 operands.
+// The GEMM part: the wave's (64 QT) x 96 accumulators of X[t0 .. t0+n) . W_head^T, rows of Kbytes bytes; HALF: fp16 operands.
 // The main loop of the large-tile GEMM kernel (same ring, same waits); load_tables() runs once the first stages are
 // requested.  On return the ring is idle.
 // VWAVE: the wave's last two channel tiles are value channels.  Their products are formed with the operands the other
