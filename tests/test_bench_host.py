@@ -48,3 +48,11 @@ def test_measured_traffic_comes_from_the_tracked_profiles():
     assert got is not None and 10.22e6 < got < 60e6            # at least the algorithmic bytes, the same order of magnitude
     assert b.measured_traffic("C2", "FULL_INT8", "ffn1", 4096) is None      # another launch size: no figure, no guess
     assert b.measured_traffic("C9", "FULL_INT8", "ffn1", 2048) is None
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    """Everything here runs on one GPU: bench.py --gpus 2 exits with a message that says so, before touching any GPU."""
+    import subprocess
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "--gpus 1" in r.stderr and r.stdout.strip() == ""
